@@ -1,0 +1,103 @@
+"""ctypes loader for the CPU oracle (``verify_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()``
+and by the ``cpu_baseline`` leg of ``bench.py``.  The product package never
+imports this module, and this module never imports the product package.
+
+The oracle is Alg. 1 (token verification), Alg. 2 (block verification) and
+Alg. 4 (greedy block verification) of the paper, in double precision, one
+sequence at a time; see the header of ``verify_oracle.c`` for the conventions.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "verify_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_verify.so")
+
+BLOCK, TOKEN, GREEDY = 0, 1, 2
+F32, BF16 = 0, 1
+DBG_STRIDE = 6  # w, S, h, logZ_target, logZ_draft, log r
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  Returns the path of the shared object."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.oracle_spec_verify.restype = ctypes.c_int
+        lib.oracle_spec_verify.argtypes = [
+            ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int,
+        ]
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_num_threads.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def num_threads(requested: int = 0) -> int:
+    return int(_load().oracle_num_threads(int(requested)))
+
+
+def _as_logits(x, dtype_code):
+    """A C-contiguous numpy view of the logits: float32, or uint16 holding bf16 bits."""
+    if dtype_code == F32:
+        arr = np.ascontiguousarray(x, dtype=np.float32)
+    else:
+        arr = np.ascontiguousarray(x)
+        if arr.dtype != np.uint16:
+            raise TypeError("bf16 logits must be passed as their uint16 bit patterns")
+    return arr
+
+
+def verify(algo: int, target_logits, draft_logits, draft_tokens, uniforms,
+           temperature: float, dtype: int = F32, nthreads: int = 0):
+    """Run the oracle on a batch.
+
+    target_logits [B, gamma+1, V], draft_logits [B, gamma, V] (float32 arrays, or uint16
+    arrays of bf16 bit patterns when ``dtype == BF16``), draft_tokens [B, gamma] int32,
+    uniforms [B, gamma+1] float32.  Returns a dict with ``accept_len`` [B], ``next_token``
+    [B], ``dbg`` [B, gamma+1, 6] (w, S, h, logZ_target, logZ_draft, log r), ``margins``
+    [B, 2] and ``n_fallback``.
+    """
+    lib = _load()
+    tl = _as_logits(target_logits, dtype)
+    dl = _as_logits(draft_logits, dtype)
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    uni = np.ascontiguousarray(uniforms, dtype=np.float32)
+    B, g1, V = tl.shape
+    gamma = g1 - 1
+    if dl.shape != (B, gamma, V) or tok.shape != (B, gamma) or uni.shape != (B, gamma + 1):
+        raise ValueError("shape mismatch between the oracle's inputs")
+    tau = np.empty(B, dtype=np.int32)
+    y = np.empty(B, dtype=np.int32)
+    dbg = np.empty((B, gamma + 1, DBG_STRIDE), dtype=np.float64)
+    margins = np.empty((B, 2), dtype=np.float64)
+    nfb = ctypes.c_int32(0)
+    rc = lib.oracle_spec_verify(
+        int(algo), tl.ctypes.data, dl.ctypes.data, tok.ctypes.data, uni.ctypes.data,
+        B, gamma, V, int(dtype), float(temperature),
+        tau.ctypes.data, y.ctypes.data, dbg.ctypes.data, margins.ctypes.data,
+        ctypes.addressof(nfb), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"oracle_spec_verify failed with code {rc}")
+    return {"accept_len": tau, "next_token": y, "dbg": dbg, "margins": margins,
+            "n_fallback": int(nfb.value)}
