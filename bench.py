@@ -1,0 +1,118 @@
+"""Throughput of batched draft verification on one MI355X.
+
+One step = one `spec_verify_block` call (the whole hot path) on one batch of synthetic inputs
+of the headline configuration (B=64, gamma=8, V=128256, bf16, T=0.8), inputs resident in HBM.
+Consecutive steps rotate through several distinct input sets so that no step can be served
+from the Infinity Cache.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+
+
+def cpu_baseline(cfg, inputs, budget_s=12.0):
+    """The oracle as it stands, timed on this machine's host cores on the same inputs."""
+    import oracle
+    import workloads
+    host = workloads.to_numpy(inputs)
+    dtype = oracle.BF16 if cfg.dtype == "bf16" else oracle.F32
+    cores = oracle.num_threads(0)
+    calls, t0 = 0, time.perf_counter()
+    while True:
+        oracle.verify(oracle.BLOCK, host["target_logits"], host["draft_logits"], host["draft_tokens"],
+                      host["uniforms"], cfg.temperature, dtype=dtype, nthreads=cores)
+        calls += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or calls >= 20:
+            break
+    return {"value": calls / el, "unit": "calls/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{calls} full block-verification call(s) of the same workload "
+                      f"(B={cfg.B}, all sequences), {el:.1f} s wall",
+            "seq_verifications_per_s": calls * cfg.B / el,
+            "algorithmic_GBps": calls * cfg.algorithmic_bytes / el / 1e9}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--config", type=int, default=3, help="workload configuration (3 = headline)")
+    ap.add_argument("--algo", default="block", choices=["block", "token", "greedy"])
+    ap.add_argument("--sets", type=int, default=4, help="distinct input sets rotated through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU only (sequences are independent; more GPUs "
+              "shard the batch with no exchange). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2403_10444_amd as sv
+    import workloads
+
+    sv.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = workloads.CONFIGS[args.config]
+    fn = {"block": sv.spec_verify_block, "token": sv.spec_verify_token, "greedy": sv.spec_verify_greedy}[args.algo]
+
+    sets = [workloads.generate(cfg, seed=9000 + s, device=dev) for s in range(args.sets)]
+    ws = sv.alloc_workspace(cfg.B, cfg.gamma, cfg.V, dev)
+    tau = torch.empty(cfg.B, dtype=torch.int32, device=dev)
+    y = torch.empty(cfg.B, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream(dev)
+
+    def step(i):
+        s = sets[i % len(sets)]
+        fn(s["target_logits"], s["draft_logits"], s["draft_tokens"], s["uniforms"], cfg.temperature,
+           workspace=ws, accept_len=tau, next_token=y, stream=stream.cuda_stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        step(i)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_ms = ev0.elapsed_time(ev1) / args.steps          # device time per call, HIP events on the launch stream
+
+    ms_per_step = wall / args.steps * 1e3
+    calls_per_s = args.steps / wall
+    achieved = cfg.algorithmic_bytes / (dev_ms * 1e-3) / 1e9
+    out = {
+        "metric": "verify calls/sec", "value": calls_per_s, "unit": "calls/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "algo": args.algo, "B": cfg.B, "gamma": cfg.gamma, "V": cfg.V,
+                   "logit_dtype": cfg.dtype, "temperature": cfg.temperature, "input_sets": len(sets)},
+        "seq_verifications_per_s": calls_per_s * cfg.B,
+        "mean_accept_len": float(tau.float().mean().item()),
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "whole call (all kernels of one verification)",
+                     "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, sets[0])
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

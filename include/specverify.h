@@ -1,0 +1,109 @@
+/*
+ * specverify -- batched draft verification for speculative decoding on AMD MI355X (gfx950).
+ *
+ * One call verifies B independent sequences.  For sequence b the caller hands over the
+ * target model's logits at gamma+1 positions, the draft model's logits at gamma positions,
+ * the gamma drafted tokens and gamma+1 uniforms; the library returns the accept length tau
+ * and the extra token Y, so that the text to append is X_1..X_tau, Y ("Return X^tau, Y" in
+ * Alg. 1 and Alg. 2 of "Block Verification Accelerates Speculative Decoding").
+ *
+ * Definitions (row i of a sequence is conditioned on the first i draft tokens):
+ *   p_i = softmax(target row i / T), i = 0..gamma;  q_i = softmax(draft row i / T), i < gamma;
+ *   r_i = p_{i-1}(X_i) / q_{i-1}(X_i)                 (acceptance ratio, Sec. 1)
+ *   block verification (Alg. 2):  w_0 = 1, w_i = min(w_{i-1} r_i, 1);
+ *       S_i = sum_x max(w_i p_i(x) - q_i(x), 0),  h_i = S_i / (S_i + 1 - w_i) for i < gamma,
+ *       h_gamma = w_gamma (the acceptance-probability box next to Alg. 2);
+ *       tau = the LAST i in 1..gamma with eta_i < h_i, or 0;
+ *       Y ~ p_gamma if tau = gamma, else Y ~ max(w_tau p_tau - q_tau, 0) normalised.
+ *   token verification (Alg. 1):  h_i = min(r_i, 1); tau = number of leading i with
+ *       eta_i < h_i; Y ~ p_gamma if tau = gamma, else Y ~ max(p_tau - q_tau, 0) normalised.
+ *   greedy block verification (Alg. 4):  w_i = w_{i-1} r_i (no clip);
+ *       h_i = S_i / sum_x max(q_i(x) - w_i p_i(x), 0) for i < gamma, h_gamma = w_gamma;
+ *       tau and Y as in block verification.
+ * Conventions the paper leaves open: uniforms lie in [0,1) and a test passes iff eta < h;
+ * h_i = 1 when w_i >= 1; Y is an inverse-CDF draw in vocabulary-index order:
+ * Y = min{x : sum_{x' <= x} rho(x') > u * sum rho}, so a token of zero weight is never drawn.
+ *
+ * All data pointers are DEVICE pointers owned by the caller.  Calls are asynchronous: work
+ * is enqueued on `stream` (a hipStream_t passed as void*; NULL is the default stream) and
+ * the outputs are valid once the caller has synchronised that stream.  The library never
+ * allocates, frees or synchronises, and keeps no reference to any argument after return.
+ * Errors are reported by return code only.  Finite logits, tokens in [0, V) and uniforms in
+ * [0, 1) are the caller's contract and are not checked on the device.
+ * Two calls may run concurrently only with disjoint workspaces.
+ */
+#ifndef SPECVERIFY_H
+#define SPECVERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SV_OK = 0,
+    SV_ERR_INVALID_ARG = 1,          /* NULL pointer, B/gamma/V < 1, bad dtype, T not finite or <= 0 */
+    SV_ERR_UNSUPPORTED = 2,          /* gamma above SV_MAX_GAMMA, or sizes that overflow 32-bit grids  */
+    SV_ERR_WORKSPACE_TOO_SMALL = 3,
+    SV_ERR_HIP = 4                   /* a launch failed; see hipGetLastError                           */
+} sv_status_t;
+
+typedef enum { SV_DTYPE_F32 = 0, SV_DTYPE_BF16 = 1 } sv_dtype_t;
+
+#define SV_MAX_GAMMA 64
+
+/* Bytes of device workspace a call with these sizes needs (0 if the sizes are invalid).
+ * The workspace must be 256-byte aligned.  Its contents need no initialisation and are
+ * scratch: nothing in it is meaningful to the caller after a call.                        */
+size_t spec_verify_workspace_bytes(int32_t B, int32_t gamma, int32_t V);
+
+/*
+ * Block verification (Alg. 2).
+ *   target_logits  [B, gamma+1, V]  dtype, V contiguous, rows dense (stride V)
+ *   draft_logits   [B, gamma,   V]  dtype
+ *   draft_tokens   [B, gamma]       X_1..X_gamma
+ *   uniforms       [B, gamma+1]     eta_1..eta_gamma, then u (draws Y)
+ *   temperature    T > 0, applied to both models
+ *   accept_len     [B] out: tau in [0, gamma]
+ *   next_token     [B] out: Y in [0, V)
+ *   debug_out      NULL, or [B, gamma+1, 3] floats out: w_i, S_i, h_i (S_gamma = w_gamma,
+ *                  h_0 = 1)
+ * 16-byte loads are used when both logit pointers and V*sizeof(dtype) are multiples of 16;
+ * any other V or alignment is served by an element-wise path with the same results.
+ */
+sv_status_t spec_verify_block(const void *target_logits, const void *draft_logits,
+                              const int32_t *draft_tokens, const float *uniforms,
+                              int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                              float temperature, void *workspace, size_t workspace_bytes,
+                              int32_t *accept_len, int32_t *next_token, float *debug_out,
+                              void *stream);
+
+/* Token verification (Alg. 1); same arguments.  debug_out holds w_i = 1,
+ * S_i = sum_x max(p_i - q_i, 0) and h_i = min(r_i, 1).                                   */
+sv_status_t spec_verify_token(const void *target_logits, const void *draft_logits,
+                              const int32_t *draft_tokens, const float *uniforms,
+                              int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                              float temperature, void *workspace, size_t workspace_bytes,
+                              int32_t *accept_len, int32_t *next_token, float *debug_out,
+                              void *stream);
+
+/* Greedy block verification (Alg. 4); same arguments.  debug_out holds the unclipped
+ * w_i, S_i and h_i clipped to [0, 1].  Its output keeps the target distribution only
+ * when the caller also applies the paper's distribution modification (Alg. 5) to the
+ * following gamma - tau - 1 positions; that step needs the models and is not part of
+ * this library.                                                                          */
+sv_status_t spec_verify_greedy(const void *target_logits, const void *draft_logits,
+                               const int32_t *draft_tokens, const float *uniforms,
+                               int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                               float temperature, void *workspace, size_t workspace_bytes,
+                               int32_t *accept_len, int32_t *next_token, float *debug_out,
+                               void *stream);
+
+const char *spec_verify_status_string(sv_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVERIFY_H */

@@ -1,0 +1,9 @@
+"""MI355X-native draft verification for speculative decoding (block / token / greedy).
+
+The work is done by HIP kernels in ``csrc/`` behind the C ABI of ``include/specverify.h``;
+this package only marshals arguments.
+"""
+from .binding import (  # noqa: F401
+    SpecVerifyError, alloc_workspace, load, spec_verify_block, spec_verify_greedy,
+    spec_verify_token, spec_verify_workspace_bytes, status_string,
+)

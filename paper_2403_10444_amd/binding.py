@@ -1,0 +1,149 @@
+"""ctypes binding of libspecverify.so: argument marshalling only.
+
+Every step of the verification path runs in the HIP kernels behind the C ABI declared
+in ``include/specverify.h``.  PyTorch is used for device memory and streams, nothing
+else.  There is no CPU fallback: if the library has not been built, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecverify.so")
+
+SV_OK = 0
+SV_ERR_INVALID_ARG = 1
+SV_ERR_UNSUPPORTED = 2
+SV_ERR_WORKSPACE_TOO_SMALL = 3
+SV_ERR_HIP = 4
+SV_DTYPE_F32 = 0
+SV_DTYPE_BF16 = 1
+
+EXPORTED = (
+    "spec_verify_workspace_bytes",
+    "spec_verify_block",
+    "spec_verify_token",
+    "spec_verify_greedy",
+    "spec_verify_status_string",
+)
+
+_VERIFY_ARGTYPES = [
+    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+    ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_float,
+    ctypes.c_void_p, ctypes.c_size_t,
+    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+]
+
+_lib = None
+
+
+class SpecVerifyError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"specverify: {text} (status {code})")
+        self.code = code
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library; raises if it is missing (build it with build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2403_10444_amd.build` "
+                "(there is no fallback implementation)")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.spec_verify_workspace_bytes.restype = ctypes.c_size_t
+        lib.spec_verify_workspace_bytes.argtypes = [ctypes.c_int32] * 3
+        for name in ("spec_verify_block", "spec_verify_token", "spec_verify_greedy"):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = _VERIFY_ARGTYPES
+        lib.spec_verify_status_string.restype = ctypes.c_char_p
+        lib.spec_verify_status_string.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return load().spec_verify_status_string(int(code)).decode()
+
+
+def spec_verify_workspace_bytes(B: int, gamma: int, V: int) -> int:
+    return int(load().spec_verify_workspace_bytes(int(B), int(gamma), int(V)))
+
+
+def alloc_workspace(B: int, gamma: int, V: int, device="cuda") -> torch.Tensor:
+    """A device byte buffer of the size the library asks for (256-byte aligned by torch)."""
+    n = spec_verify_workspace_bytes(B, gamma, V)
+    if n == 0:
+        raise SpecVerifyError(SV_ERR_UNSUPPORTED, "sizes not supported")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SV_DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return SV_DTYPE_BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature,
+          workspace=None, accept_len=None, next_token=None, debug_out=None, stream=None):
+    lib = load()
+    B, g1, V = target_logits.shape
+    gamma = g1 - 1
+    dev = target_logits.device
+    if dev.type != "cuda":
+        raise ValueError("specverify runs on the GPU only; tensors must live on a cuda device")
+    if tuple(draft_logits.shape) != (B, gamma, V) or tuple(draft_tokens.shape) != (B, gamma) \
+            or tuple(uniforms.shape) != (B, gamma + 1):
+        raise ValueError("shape mismatch between the inputs")
+    if draft_logits.dtype != target_logits.dtype:
+        raise TypeError("target and draft logits must share a dtype")
+    for t, want in ((draft_tokens, torch.int32), (uniforms, torch.float32)):
+        if t.dtype != want:
+            raise TypeError(f"expected {want}, got {t.dtype}")
+    for t in (target_logits, draft_logits, draft_tokens, uniforms):
+        if not t.is_contiguous() or t.device != dev:
+            raise ValueError("inputs must be contiguous and on one device")
+    if workspace is None:
+        workspace = alloc_workspace(B, gamma, V, dev)
+    if accept_len is None:
+        accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    if next_token is None:
+        next_token = torch.empty(B, dtype=torch.int32, device=dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    code = getattr(lib, name)(
+        target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), uniforms.data_ptr(),
+        B, gamma, V, _dtype_code(target_logits), float(temperature),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        accept_len.data_ptr(), next_token.data_ptr(),
+        debug_out.data_ptr() if debug_out is not None else None, stream)
+    if code != SV_OK:
+        raise SpecVerifyError(code, status_string(code))
+    return accept_len, next_token
+
+
+def spec_verify_block(target_logits, draft_logits, draft_tokens, uniforms, temperature, **kw):
+    """Block verification (Alg. 2): returns (accept_len [B], next_token [B]) int32 device tensors.
+
+    Asynchronous on the current (or given) stream.  Optional keyword arguments: ``workspace``
+    (uint8 device tensor from `alloc_workspace`), preallocated ``accept_len`` / ``next_token``,
+    ``debug_out`` (float32 [B, gamma+1, 3] device tensor receiving w, S, h) and ``stream``
+    (a raw hipStream_t handle)."""
+    return _call("spec_verify_block", target_logits, draft_logits, draft_tokens, uniforms, temperature, **kw)
+
+
+def spec_verify_token(target_logits, draft_logits, draft_tokens, uniforms, temperature, **kw):
+    """Token verification (Alg. 1); same arguments and returns as `spec_verify_block`."""
+    return _call("spec_verify_token", target_logits, draft_logits, draft_tokens, uniforms, temperature, **kw)
+
+
+def spec_verify_greedy(target_logits, draft_logits, draft_tokens, uniforms, temperature, **kw):
+    """Greedy block verification (Alg. 4); same arguments and returns as `spec_verify_block`."""
+    return _call("spec_verify_greedy", target_logits, draft_logits, draft_tokens, uniforms, temperature, **kw)

@@ -1,0 +1,77 @@
+"""The C-ABI library loads and exports what include/specverify.h declares; argument
+validation is host-side and runs without a GPU (no kernel is launched in this file)."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2403_10444_amd as sv
+from paper_2403_10444_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "specverify.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spec_verify_\w+)\s*\(", text)))
+
+
+def test_header_and_library_agree_on_exports():
+    lib = sv.load()
+    declared = _declared_functions()
+    assert declared == sorted(binding.EXPORTED)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_workspace_query():
+    assert sv.spec_verify_workspace_bytes(64, 8, 128256) > 0
+    assert sv.spec_verify_workspace_bytes(64, 8, 128256) % 256 == 0
+    assert sv.spec_verify_workspace_bytes(0, 8, 128256) == 0
+    assert sv.spec_verify_workspace_bytes(1, 0, 10) == 0
+    assert sv.spec_verify_workspace_bytes(1, 1, 0) == 0
+    assert sv.spec_verify_workspace_bytes(1, 65, 10) == 0          # above SV_MAX_GAMMA
+    assert sv.spec_verify_workspace_bytes(1 << 20, 64, 1 << 30) == 0  # grid would overflow
+
+
+def _raw(name, *, B=2, gamma=3, V=100, dtype=0, T=1.0, ws=0x1000, ws_bytes=1 << 30,
+         target=0x1000, draft=0x1000, tokens=0x1000, uniforms=0x1000, tau=0x1000, y=0x1000):
+    # fake non-null pointers: validation must reject the call before anything is dereferenced
+    lib = sv.load()
+    return getattr(lib, name)(target, draft, tokens, uniforms, B, gamma, V, dtype, T, ws, ws_bytes,
+                              tau, y, None, None)
+
+
+@pytest.mark.parametrize("name", ["spec_verify_block", "spec_verify_token", "spec_verify_greedy"])
+def test_argument_validation_returns_codes(name):
+    assert _raw(name, B=0) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, gamma=0) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, V=0) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, T=0.0) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, T=-1.0) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, T=float("inf")) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, T=float("nan")) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, dtype=7) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, target=None) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, tau=None) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, ws=None) == binding.SV_ERR_INVALID_ARG
+    assert _raw(name, ws=0x1010) == binding.SV_ERR_INVALID_ARG       # workspace not 256-byte aligned
+    assert _raw(name, gamma=65) == binding.SV_ERR_UNSUPPORTED
+    assert _raw(name, ws_bytes=16) == binding.SV_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_status_strings():
+    seen = {sv.status_string(c) for c in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert sv.status_string(99) == "unknown status"
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    t = torch.zeros((1, 2, 8))
+    with pytest.raises(ValueError):
+        sv.spec_verify_block(t, t[:, :1], torch.zeros((1, 1), dtype=torch.int32), torch.zeros((1, 2)), 1.0)

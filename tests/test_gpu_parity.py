@@ -1,0 +1,209 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on seeded inputs."""
+from __future__ import annotations
+
+import json
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2403_10444_amd as sv
+import workloads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(report):
+    print(json.dumps(report), flush=True)
+
+
+def _custom(B, gamma, V, dtype="f32", sigma_t=3.0, sigma_d=1.0, T=1.0, zipf=False):
+    return workloads.Config(f"custom_B{B}_g{gamma}_V{V}_{dtype}", B, gamma, V, dtype, sigma_t, sigma_d, T, zipf, 1)
+
+
+# ------------------------------------------------------------------ the five configurations
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+def test_cfg1_ten_thousand_calls_batched(algo):
+    # the 10,000 calls of configuration 1 as one batch of 10,000 independent sequences
+    cfg = workloads.with_overrides(workloads.CONFIGS[1], B=10000)
+    inp = workloads.generate(cfg, seed=101, device=DEV)
+    rep = parity.compare(parity.run_gpu(algo, inp, cfg.temperature), parity.run_oracle(algo, inp, cfg.temperature),
+                         label=f"cfg1/{algo}")
+    _say(rep)
+
+
+def test_cfg1_single_sequence_calls():
+    cfg = workloads.CONFIGS[1]
+    ws = sv.alloc_workspace(cfg.B, cfg.gamma, cfg.V, DEV)
+    for call in range(40):
+        inp = workloads.generate(cfg, seed=1000 + call, device=DEV)
+        for algo in ("block", "token"):
+            parity.compare(parity.run_gpu(algo, inp, cfg.temperature, workspace=ws),
+                           parity.run_oracle(algo, inp, cfg.temperature), label=f"cfg1/call{call}/{algo}")
+
+
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+def test_cfg2_calls(algo):
+    cfg = workloads.CONFIGS[2]
+    ws = sv.alloc_workspace(cfg.B, cfg.gamma, cfg.V, DEV)
+    taus = []
+    for call in range(12):
+        inp = workloads.generate(cfg, seed=2000 + call, device=DEV)
+        gpu = parity.run_gpu(algo, inp, cfg.temperature, workspace=ws)
+        rep = parity.compare(gpu, parity.run_oracle(algo, inp, cfg.temperature), label=f"cfg2/call{call}/{algo}")
+        taus.append(rep["mean_tau"])
+    _say({"label": f"cfg2/{algo}", "mean_tau": float(np.mean(taus)), "last": rep})
+
+
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+def test_cfg3_full_batch(algo):
+    cfg = workloads.CONFIGS[3]
+    for seed in (3000, 3001):
+        inp = workloads.generate(cfg, seed=seed, device=DEV)
+        rep = parity.compare(parity.run_gpu(algo, inp, cfg.temperature),
+                             parity.run_oracle(algo, inp, cfg.temperature), label=f"cfg3/seed{seed}/{algo}")
+        _say(rep)
+
+
+@pytest.mark.parametrize("sigma", workloads.CFG4_DRAFT_SIGMAS)
+def test_cfg4_acceptance_sweep(sigma):
+    cfg = workloads.with_overrides(workloads.CONFIGS[4], sigma_draft=sigma)
+    inp = workloads.generate(cfg, seed=4000 + int(sigma * 10), device=DEV)
+    rows = np.arange(0, cfg.B, 8)            # 32 sequences go through the oracle one by one
+    means = {}
+    for algo in ("block", "token"):
+        gpu = parity.run_gpu(algo, inp, cfg.temperature)
+        rep = parity.compare(gpu, parity.run_oracle(algo, inp, cfg.temperature, rows=rows), rows=rows,
+                             label=f"cfg4/sigma{sigma}/{algo}")
+        means[algo] = float(gpu["accept_len"].mean())
+        _say(rep)
+    _say({"label": f"cfg4/sigma{sigma}", "mean_tau_block": means["block"], "mean_tau_token": means["token"]})
+    # Theorem 2 holds in expectation over drafts and uniforms; 256 sequences sharing their uniforms
+    # between the two algorithms leave little noise
+    assert means["block"] >= means["token"] - 0.05
+
+
+def test_cfg5_sharp_distributions_sampled_rows():
+    cfg = workloads.CONFIGS[5]
+    inp = workloads.generate(cfg, seed=5000, device=DEV)
+    rows = np.arange(0, cfg.B, 32)           # 32 sequences
+    for algo in ("block", "token"):
+        gpu = parity.run_gpu(algo, inp, cfg.temperature)
+        rep = parity.compare(gpu, parity.run_oracle(algo, inp, cfg.temperature, rows=rows), rows=rows,
+                             label=f"cfg5/{algo}")
+        _say(rep)
+        assert np.all((gpu["next_token"] >= 0) & (gpu["next_token"] < cfg.V))
+
+
+# ------------------------------------------------------------------ shapes and edge cases
+SHAPES = [
+    # B, gamma, V, dtype           what it exercises
+    (3, 1, 1, "f32"),            # one-token vocabulary
+    (3, 2, 7, "bf16"),           # tiny, unaligned rows
+    (5, 3, 8191, "f32"),         # one element short of a chunk, unaligned
+    (5, 3, 8192, "bf16"),        # exactly one chunk
+    (4, 2, 8200, "bf16"),        # a chunk and a ragged tail, aligned
+    (4, 5, 16389, "bf16"),       # unaligned, three chunks
+    (2, 4, 50001, "f32"),        # unaligned, odd
+    (7, 64, 1000, "f32"),        # the longest draft block the library takes
+    (1, 8, 128256, "bf16"),      # one sequence of the headline shape
+    (33, 6, 32000, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,gamma,V,dtype", SHAPES)
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+def test_shapes(B, gamma, V, dtype, algo):
+    cfg = _custom(B, gamma, V, dtype, sigma_t=2.5, sigma_d=0.8, T=0.9)
+    inp = workloads.generate(cfg, seed=B * 1000 + gamma * 10 + V % 7, device=DEV)
+    rep = parity.compare(parity.run_gpu(algo, inp, cfg.temperature), parity.run_oracle(algo, inp, cfg.temperature),
+                         label=f"{cfg.name}/{algo}")
+    _say(rep)
+
+
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+def test_unaligned_base_pointers(algo):
+    cfg = _custom(4, 3, 4096, "bf16")
+    inp = workloads.generate(cfg, seed=77, device=DEV)
+    # shift both logit buffers by one element so that the 16-byte path cannot be taken
+    def shifted(t):
+        buf = torch.empty(t.numel() + 1, dtype=t.dtype, device=t.device)
+        buf[1:] = t.reshape(-1)
+        return buf[1:].view(t.shape)
+    inp2 = dict(inp, target_logits=shifted(inp["target_logits"]), draft_logits=shifted(inp["draft_logits"]))
+    assert inp2["target_logits"].data_ptr() % 16 != 0
+    a = parity.run_gpu(algo, inp, cfg.temperature)
+    b = parity.run_gpu(algo, inp2, cfg.temperature)
+    assert np.array_equal(a["accept_len"], b["accept_len"]) and np.array_equal(a["next_token"], b["next_token"])
+    assert np.array_equal(a["dbg"], b["dbg"])
+    parity.compare(b, parity.run_oracle(algo, inp, cfg.temperature))
+
+
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+def test_identical_models_accept_everything(algo):
+    cfg = _custom(16, 5, 20000, "bf16", sigma_t=4.0)
+    inp = workloads.generate(cfg, seed=5, device=DEV)
+    inp["draft_logits"] = inp["target_logits"][:, :cfg.gamma].contiguous()
+    gpu = parity.run_gpu(algo, inp, 0.7)
+    assert np.all(gpu["accept_len"] == cfg.gamma)
+    parity.compare(gpu, parity.run_oracle(algo, inp, 0.7))
+
+
+@pytest.mark.parametrize("algo", ["block", "token"])
+def test_disjoint_supports_reject_everything(algo):
+    # the draft puts its mass where the target has none: ratios underflow, tau = 0, and Y comes from
+    # the residual, which is the target itself to rounding
+    cfg = _custom(8, 4, 4096, "f32", sigma_t=1.0)
+    inp = workloads.generate(cfg, seed=6, device=DEV)
+    V = cfg.V
+    inp["target_logits"][..., : V // 2] -= 60.0
+    inp["draft_logits"][..., V // 2:] -= 60.0
+    q = torch.softmax(inp["draft_logits"].double(), -1)
+    inp["draft_tokens"] = torch.multinomial(q.view(-1, V), 1).view(cfg.B, cfg.gamma).to(torch.int32)
+    gpu = parity.run_gpu(algo, inp, 1.0)
+    assert np.all(gpu["accept_len"] == 0)
+    assert np.all(gpu["next_token"] >= V // 2)
+    parity.compare(gpu, parity.run_oracle(algo, inp, 1.0))
+
+
+def test_uniform_extremes():
+    cfg = _custom(6, 4, 9000, "bf16")
+    inp = workloads.generate(cfg, seed=8, device=DEV)
+    for value in (0.0, 1.0 - 2.0 ** -24):
+        inp2 = dict(inp, uniforms=torch.full_like(inp["uniforms"], value))
+        for algo in ("block", "token", "greedy"):
+            parity.compare(parity.run_gpu(algo, inp2, 1.0), parity.run_oracle(algo, inp2, 1.0))
+
+
+def test_results_are_bit_reproducible():
+    cfg = workloads.with_overrides(workloads.CONFIGS[3], B=8)
+    inp = workloads.generate(cfg, seed=9, device=DEV)
+    a = parity.run_gpu("block", inp, cfg.temperature)
+    for _ in range(3):
+        b = parity.run_gpu("block", inp, cfg.temperature)
+        assert np.array_equal(a["accept_len"], b["accept_len"])
+        assert np.array_equal(a["next_token"], b["next_token"])
+        assert np.array_equal(a["dbg"], b["dbg"])
+
+
+def test_gamma_one_block_equals_token():
+    cfg = _custom(64, 1, 5000, "bf16", sigma_d=1.5)
+    inp = workloads.generate(cfg, seed=10, device=DEV)
+    a = parity.run_gpu("block", inp, 1.0)
+    b = parity.run_gpu("token", inp, 1.0)
+    assert np.array_equal(a["accept_len"], b["accept_len"]) and np.array_equal(a["next_token"], b["next_token"])
+
+
+def test_runs_on_a_side_stream():
+    cfg = _custom(4, 3, 30000, "bf16")
+    inp = workloads.generate(cfg, seed=11, device=DEV)
+    ref = parity.run_gpu("block", inp, 1.0)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        tau, y = sv.spec_verify_block(inp["target_logits"], inp["draft_logits"], inp["draft_tokens"],
+                                      inp["uniforms"], 1.0)
+    s.synchronize()
+    assert np.array_equal(tau.cpu().numpy(), ref["accept_len"]) and np.array_equal(y.cpu().numpy(), ref["next_token"])
