@@ -47,7 +47,8 @@ typedef enum {
     SV_ERR_INVALID_ARG = 1,          /* NULL pointer, B/gamma/V < 1, bad dtype, T not finite or <= 0 */
     SV_ERR_UNSUPPORTED = 2,          /* gamma above SV_MAX_GAMMA, or sizes that overflow 32-bit grids  */
     SV_ERR_WORKSPACE_TOO_SMALL = 3,
-    SV_ERR_HIP = 4                   /* a launch failed; see hipGetLastError                           */
+    SV_ERR_HIP = 4,                  /* a launch or copy failed; see hipGetLastError                   */
+    SV_ERR_INTERNAL = 5              /* workspace_check: a bounded wait inside a kernel ran out        */
 } sv_status_t;
 
 typedef enum { SV_DTYPE_F32 = 0, SV_DTYPE_BF16 = 1 } sv_dtype_t;
@@ -55,9 +56,31 @@ typedef enum { SV_DTYPE_F32 = 0, SV_DTYPE_BF16 = 1 } sv_dtype_t;
 #define SV_MAX_GAMMA 64
 
 /* Bytes of device workspace a call with these sizes needs (0 if the sizes are invalid).
- * The workspace must be 256-byte aligned.  Its contents need no initialisation and are
- * scratch: nothing in it is meaningful to the caller after a call.                        */
+ * The workspace must be 256-byte aligned.                                                 */
 size_t spec_verify_workspace_bytes(int32_t B, int32_t gamma, int32_t V);
+
+/* Prepares a workspace for calls of exactly the shape (B, gamma, V): enqueues one small
+ * kernel on `stream` that clears the control words the verification kernel synchronises
+ * its workgroups with.  Required once after allocation (and again before using the same
+ * memory for another shape); every verification call leaves the control words clear for
+ * the next one.  A verification call on a workspace that was not initialised for its shape
+ * touches nothing else and writes -1 to every accept_len and next_token.                  */
+sv_status_t spec_verify_workspace_init(void *workspace, size_t workspace_bytes,
+                                       int32_t B, int32_t gamma, int32_t V, void *stream);
+
+/* Synchronises `stream` and reads the workspace's status words back to the host: SV_OK,
+ * SV_ERR_INVALID_ARG if the workspace is not initialised for this shape, SV_ERR_INTERNAL
+ * if a workgroup gave up a bounded wait during an earlier call (the results of that call
+ * are then invalid; re-initialise the workspace).  Meant for tests and debugging: it is
+ * the one entry point that blocks.                                                        */
+sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_t gamma, int32_t V,
+                                        void *stream);
+
+/* Testing hook, process-wide: `path` 0 = the library's default kernels, 1 = the four-launch
+ * staged kernels, 2 = the single-launch fused kernel (takes V <= 128 * 8192; larger sizes
+ * are then refused); `spin_limit` bounds every wait inside the fused kernel in polls
+ * (negative: default).                                                                    */
+void spec_verify_debug_config(int32_t path, int32_t spin_limit);
 
 /*
  * Block verification (Alg. 2).

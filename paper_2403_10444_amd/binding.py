@@ -19,11 +19,15 @@ SV_ERR_INVALID_ARG = 1
 SV_ERR_UNSUPPORTED = 2
 SV_ERR_WORKSPACE_TOO_SMALL = 3
 SV_ERR_HIP = 4
+SV_ERR_INTERNAL = 5
 SV_DTYPE_F32 = 0
 SV_DTYPE_BF16 = 1
 
 EXPORTED = (
     "spec_verify_workspace_bytes",
+    "spec_verify_workspace_init",
+    "spec_verify_workspace_check",
+    "spec_verify_debug_config",
     "spec_verify_block",
     "spec_verify_token",
     "spec_verify_greedy",
@@ -61,6 +65,14 @@ def load() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.restype = ctypes.c_int
             fn.argtypes = _VERIFY_ARGTYPES
+        lib.spec_verify_workspace_init.restype = ctypes.c_int
+        lib.spec_verify_workspace_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
+                                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+        lib.spec_verify_workspace_check.restype = ctypes.c_int
+        lib.spec_verify_workspace_check.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                                    ctypes.c_int32, ctypes.c_void_p]
+        lib.spec_verify_debug_config.restype = None
+        lib.spec_verify_debug_config.argtypes = [ctypes.c_int32, ctypes.c_int32]
         lib.spec_verify_status_string.restype = ctypes.c_char_p
         lib.spec_verify_status_string.argtypes = [ctypes.c_int]
         _lib = lib
@@ -75,12 +87,35 @@ def spec_verify_workspace_bytes(B: int, gamma: int, V: int) -> int:
     return int(load().spec_verify_workspace_bytes(int(B), int(gamma), int(V)))
 
 
+def spec_verify_workspace_init(workspace: torch.Tensor, B: int, gamma: int, V: int, stream=None) -> None:
+    if stream is None:
+        stream = torch.cuda.current_stream(workspace.device).cuda_stream
+    code = load().spec_verify_workspace_init(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                             int(B), int(gamma), int(V), stream)
+    if code != SV_OK:
+        raise SpecVerifyError(code, status_string(code))
+
+
+def spec_verify_workspace_check(workspace: torch.Tensor, B: int, gamma: int, V: int, stream=None) -> int:
+    """Blocks on the stream and returns the workspace's status code (SV_OK when healthy)."""
+    if stream is None:
+        stream = torch.cuda.current_stream(workspace.device).cuda_stream
+    return int(load().spec_verify_workspace_check(workspace.data_ptr(), int(B), int(gamma), int(V), stream))
+
+
+def spec_verify_debug_config(path: int = 0, spin_limit: int = -1) -> None:
+    load().spec_verify_debug_config(int(path), int(spin_limit))
+
+
 def alloc_workspace(B: int, gamma: int, V: int, device="cuda") -> torch.Tensor:
-    """A device byte buffer of the size the library asks for (256-byte aligned by torch)."""
+    """A device byte buffer of the size the library asks for, initialised for this shape."""
     n = spec_verify_workspace_bytes(B, gamma, V)
     if n == 0:
         raise SpecVerifyError(SV_ERR_UNSUPPORTED, "sizes not supported")
-    return torch.empty(n, dtype=torch.uint8, device=device)
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    with torch.cuda.device(ws.device):
+        spec_verify_workspace_init(ws, B, gamma, V)
+    return ws
 
 
 def _dtype_code(t: torch.Tensor) -> int:

@@ -11,6 +11,9 @@ LIB = os.path.join(HERE, "libspecverify.so")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
+    # no implicit fused multiply-adds: a shift computed as m * k must be the SAME rounded number
+    # wherever it is used (the kernels write every fma they want explicitly)
+    "-ffp-contract=off",
     # keep the compiler from forming packed-FP32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",

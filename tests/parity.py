@@ -13,11 +13,13 @@ import workloads
 # chosen token's CDF cell, relative to the total).
 MARGIN = 1e-6
 # Residual masses: relative tolerance, plus a floor proportional to w_i.  The floor is what
-# fp32 cancels away when w p and q nearly agree on the tokens that carry the mass: each term
-# max(w p - q, 0) is formed from two fp32 exponentials of relative error ~1e-7, so its
-# absolute error is ~1e-7 * w p, and the terms of a row add up to at most w.
+# fp32 cancels away when w p and q nearly agree on the tokens that carry the mass (S << w):
+# a term w p(x) - q(x) is formed from two hardware exp2 (1 ulp = 2^-23 each) and about four
+# roundings (2^-24 each), so its absolute error is at most ~4.8e-7 * (w p(x) + q(x)); over
+# the active tokens (w p > q) both sums are at most w, which bounds the row's error by
+# ~1e-6 * w, and the fp32 normalisers add a common factor error of a few 1e-7 on top.
 S_RTOL = 1e-5
-S_FLOOR = 4e-7
+S_FLOOR = 1.5e-6
 
 ALGOS = {"block": (oracle.BLOCK, sv.spec_verify_block),
          "token": (oracle.TOKEN, sv.spec_verify_token),
@@ -44,8 +46,11 @@ def run_oracle(algo, inputs, temperature, rows=None, nthreads=0):
                          host["uniforms"], temperature, dtype=dtype, nthreads=nthreads)
 
 
-def compare(gpu, ref, rows=None, label=""):
-    """Element-by-element comparison; returns a report dict and raises on a violation."""
+def compare(gpu, ref, rows=None, label="", greedy=False):
+    """Element-by-element comparison; returns a report dict and raises on a violation.
+
+    `greedy`: h_i of greedy block verification is a ratio of two residual masses; where both are
+    rounding noise (the two models agree on the row) it is 0/0 and is not compared."""
     g_tau, g_y, g_dbg = gpu["accept_len"], gpu["next_token"], gpu["dbg"]
     if rows is not None:
         rows = np.asarray(rows)
@@ -71,7 +76,7 @@ def compare(gpu, ref, rows=None, label=""):
         "frac_S_within_1e-5_rel": float(np.mean(s_rel[S > 0] <= S_RTOL)) if np.any(S > 0) else 1.0,
         # w below float32's normal range cannot be reported in the float32 debug block
         "max_w_rel_err": float(np.max(np.where(w > 1e-30, np.abs(gw - w) / np.maximum(w, 1e-300), 0.0))),
-        "max_h_abs_err": float(np.max(np.abs(gh - h))),
+        "max_h_abs_err": float(np.max(np.where(greedy & (S < 1e-12), 0.0, np.abs(gh - h)))),
         "mean_tau": float(np.mean(g_tau)),
         "n_fallback_oracle": int(ref["n_fallback"]),
     }

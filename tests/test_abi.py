@@ -64,9 +64,29 @@ def test_argument_validation_returns_codes(name):
     assert _raw(name, ws_bytes=16) == binding.SV_ERR_WORKSPACE_TOO_SMALL
 
 
+def test_workspace_init_validates_on_the_host():
+    lib = sv.load()
+    assert lib.spec_verify_workspace_init(None, 1 << 30, 2, 3, 100, None) == binding.SV_ERR_INVALID_ARG
+    assert lib.spec_verify_workspace_init(0x1010, 1 << 30, 2, 3, 100, None) == binding.SV_ERR_INVALID_ARG
+    assert lib.spec_verify_workspace_init(0x1000, 1 << 30, 0, 3, 100, None) == binding.SV_ERR_INVALID_ARG
+    assert lib.spec_verify_workspace_init(0x1000, 1 << 30, 2, 65, 100, None) == binding.SV_ERR_UNSUPPORTED
+    assert lib.spec_verify_workspace_init(0x1000, 16, 2, 3, 100, None) == binding.SV_ERR_WORKSPACE_TOO_SMALL
+    assert lib.spec_verify_workspace_check(None, 2, 3, 100, None) == binding.SV_ERR_INVALID_ARG
+
+
+def test_forcing_the_fused_path_refuses_vocabularies_it_cannot_take():
+    try:
+        sv.spec_verify_debug_config(2, -1)
+        assert _raw("spec_verify_block", V=129 * 8192) == binding.SV_ERR_UNSUPPORTED
+        sv.spec_verify_debug_config(0, -1)
+        assert _raw("spec_verify_block", V=129 * 8192, ws_bytes=16) == binding.SV_ERR_WORKSPACE_TOO_SMALL
+    finally:
+        sv.spec_verify_debug_config(0, -1)
+
+
 def test_status_strings():
-    seen = {sv.status_string(c) for c in range(5)}
-    assert len(seen) == 5 and "ok" in seen
+    seen = {sv.status_string(c) for c in range(6)}
+    assert len(seen) == 6 and "ok" in seen
     assert sv.status_string(99) == "unknown status"
 
 

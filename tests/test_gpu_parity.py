@@ -15,6 +15,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
+@pytest.fixture(autouse=True, params=["fused", "staged"])
+def path(request):
+    """Every test runs on both kernel paths: the single-launch fused one and the staged one."""
+    sv.spec_verify_debug_config({"staged": 1, "fused": 2}[request.param], -1)
+    yield request.param
+    sv.spec_verify_debug_config(0, -1)
+
+
 def _say(report):
     print(json.dumps(report), flush=True)
 
@@ -148,7 +156,7 @@ def test_identical_models_accept_everything(algo):
     inp["draft_logits"] = inp["target_logits"][:, :cfg.gamma].contiguous()
     gpu = parity.run_gpu(algo, inp, 0.7)
     assert np.all(gpu["accept_len"] == cfg.gamma)
-    parity.compare(gpu, parity.run_oracle(algo, inp, 0.7))
+    parity.compare(gpu, parity.run_oracle(algo, inp, 0.7), greedy=algo == "greedy")
 
 
 @pytest.mark.parametrize("algo", ["block", "token"])
@@ -207,3 +215,51 @@ def test_runs_on_a_side_stream():
                                       inp["uniforms"], 1.0)
     s.synchronize()
     assert np.array_equal(tau.cpu().numpy(), ref["accept_len"]) and np.array_equal(y.cpu().numpy(), ref["next_token"])
+
+
+def test_workspace_must_be_initialised_for_the_shape(path):
+    if path != "fused":
+        pytest.skip("only the fused kernel synchronises through the workspace")
+    cfg = _custom(4, 3, 9000, "bf16")
+    inp = workloads.generate(cfg, seed=12, device=DEV)
+    n = sv.spec_verify_workspace_bytes(cfg.B, cfg.gamma, cfg.V)
+    ws = torch.zeros(n, dtype=torch.uint8, device=DEV)          # allocated, never initialised
+    tau, y = sv.spec_verify_block(inp["target_logits"], inp["draft_logits"], inp["draft_tokens"],
+                                  inp["uniforms"], 1.0, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.all(tau == -1) and torch.all(y == -1)
+    assert sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V) == 1     # SV_ERR_INVALID_ARG
+    sv.spec_verify_workspace_init(ws, cfg.B, cfg.gamma, cfg.V)
+    for _ in range(3):                                          # the control words clear themselves
+        gpu = parity.run_gpu("block", inp, 1.0, workspace=ws)
+        parity.compare(gpu, parity.run_oracle("block", inp, 1.0))
+    assert sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V) == 0
+    # initialised for another shape: refused the same way
+    other = _custom(2, 3, 9000, "bf16")
+    inp2 = workloads.generate(other, seed=13, device=DEV)
+    tau, y = sv.spec_verify_block(inp2["target_logits"], inp2["draft_logits"], inp2["draft_tokens"],
+                                  inp2["uniforms"], 1.0, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.all(tau == -1)
+
+
+def test_a_wait_that_runs_out_is_reported_not_hung(path):
+    if path != "fused":
+        pytest.skip("only the fused kernel waits")
+    cfg = _custom(16, 8, 40000, "bf16")
+    inp = workloads.generate(cfg, seed=14, device=DEV)
+    ws = sv.alloc_workspace(cfg.B, cfg.gamma, cfg.V, DEV)
+    sv.spec_verify_debug_config(2, 0)            # every wait gives up after its first poll
+    try:
+        tau, y = sv.spec_verify_block(inp["target_logits"], inp["draft_logits"], inp["draft_tokens"],
+                                      inp["uniforms"], cfg.temperature, workspace=ws)
+        torch.cuda.synchronize()                 # the kernel ends normally whatever it computed
+        assert torch.all((tau >= 0) & (tau <= cfg.gamma)) and torch.all((y >= 0) & (y < cfg.V))
+        status = sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V)
+        assert status in (0, 5)                  # 5 = SV_ERR_INTERNAL when some unit really had to wait
+    finally:
+        sv.spec_verify_debug_config(2, -1)
+    sv.spec_verify_workspace_init(ws, cfg.B, cfg.gamma, cfg.V)
+    parity.compare(parity.run_gpu("block", inp, cfg.temperature, workspace=ws),
+                   parity.run_oracle("block", inp, cfg.temperature))
+    assert sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V) == 0
