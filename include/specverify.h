@@ -82,6 +82,12 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
  * (negative: default).                                                                    */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);
 
+/* Tuning hook, process-wide: when `device_buffer` is not NULL the fused kernel stores eight
+ * 64-bit timestamps (100 MHz ticks) per workgroup into it, [workgroups, 8]: start, first
+ * sweep done, partials announced, wait over, second sweep done, sequence counted, accept
+ * tests done, exit.  The buffer must hold 64 bytes per workgroup of the largest launch.  */
+void spec_verify_debug_profile(void *device_buffer);
+
 /*
  * Block verification (Alg. 2).
  *   target_logits  [B, gamma+1, V]  dtype, V contiguous, rows dense (stride V)

@@ -28,6 +28,7 @@ EXPORTED = (
     "spec_verify_workspace_init",
     "spec_verify_workspace_check",
     "spec_verify_debug_config",
+    "spec_verify_debug_profile",
     "spec_verify_block",
     "spec_verify_token",
     "spec_verify_greedy",
@@ -73,6 +74,8 @@ def load() -> ctypes.CDLL:
                                                     ctypes.c_int32, ctypes.c_void_p]
         lib.spec_verify_debug_config.restype = None
         lib.spec_verify_debug_config.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        lib.spec_verify_debug_profile.restype = None
+        lib.spec_verify_debug_profile.argtypes = [ctypes.c_void_p]
         lib.spec_verify_status_string.restype = ctypes.c_char_p
         lib.spec_verify_status_string.argtypes = [ctypes.c_int]
         _lib = lib

@@ -67,6 +67,7 @@ struct FusedParams {
     float *rpart;                 // [B, gamma, nw] greedy only: partial sums of max(q - w p, 0)
     int32_t *accept_len, *next_token;
     float *debug_out;
+    long long *prof;              // NULL, or [units, 8] timestamps (100 MHz ticks) for tuning
 };
 
 // ---- accessors for data that other workgroups (on any XCD) write or read.
@@ -185,6 +186,8 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
         return;
     }
     const int ticket = blockIdx.x;
+#define SV_STAMP(slot) do { if (P.prof && tid == 0) P.prof[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+    SV_STAMP(0);
     const int b = ticket / P.units_per_seq;
     const int r = ticket - b * P.units_per_seq;
     const bool last_row = r >= gamma * P.nu;            // a unit of target row gamma (no draft row)
@@ -216,6 +219,7 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
     float shiftA, mkA, sA, shiftB, mkB, sB;
     exp_sum(xa, k, shiftA, mkA, sA);
     exp_sum(xb, k, shiftB, mkB, sB);
+    SV_STAMP(1);
     {
         const unsigned long long stA = wave_stat(mkA, sA), stB = wave_stat(mkB, sB);
         if (lane == 0) {
@@ -228,6 +232,7 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
     __syncthreads();
     if (tid == 0) s_int[0] = add_count(P.rowcnt + trow, 1) == (last_row ? P.nuf : P.nu) - 1;
     __syncthreads();
+    SV_STAMP(2);
     if (s_int[0]) {
         // this unit completed the row: reduce the partials to the row's normalisers
         float Mp, Mq = 0.f;
@@ -282,6 +287,7 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
             if (lane == i) { s_alpha[0] = Lp - log2w; s_alpha[1] = Lq; }
         }
         __syncthreads();
+        SV_STAMP(3);
 
         // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq
         const float cp = fast_exp2((float)((double)shiftA - s_alpha[0]));
@@ -302,10 +308,12 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
     }
 
     // ---- count this unit as done; the unit that completes the sequence finishes it
+    SV_STAMP(4);
     drain_stores();
     __syncthreads();
     if (tid == 0) s_int[0] = add_count(P.seqcnt + b, 1) == P.units_per_seq - 1;
     __syncthreads();
+    SV_STAMP(5);
     if (!s_int[0]) return;
 
     const int base = b * (gamma + 1);
@@ -364,6 +372,7 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
     }
     __syncthreads();
     const int tau = s_int[1];
+    SV_STAMP(6);
 
     // ---- inverse-CDF draw of Y, first over the row's wave-chunk partials (wave 0)
     if (wave == 0) {
@@ -441,6 +450,8 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
     // ---- leave the sequence's counters zero for the next call
     for (int j = tid; j <= gamma; j += kThreads) { P.rowcnt[base + j] = 0; P.rowflag[base + j] = 0; }
     if (tid == 0) P.seqcnt[b] = 0;
+    SV_STAMP(7);
+#undef SV_STAMP
 }
 
 // Clears the control words of a workspace and marks it initialised.

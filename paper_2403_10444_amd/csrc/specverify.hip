@@ -25,6 +25,7 @@ constexpr int kDefaultSpinLimit = 1 << 20;
 
 std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused (testing hook)
 std::atomic<int> g_spin_limit{kDefaultSpinLimit};
+std::atomic<long long *> g_prof{nullptr};          // device buffer for per-unit timestamps (tuning hook)
 
 struct Layout {
     int nu;                 // chunks of kChunk logits per row
@@ -125,6 +126,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.spart = reinterpret_cast<float *>(ws + L.off_spart);
     P.rpart = reinterpret_cast<float *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
+    P.prof = g_prof.load();
     const unsigned grid = (unsigned)((size_t)B * L.units_per_seq);   // exactly one workgroup per ticket
     if (algo == kGreedy) fused_verify_kernel<T, ALIGNED, true><<<grid, kThreads, 0, stream>>>(P);
     else fused_verify_kernel<T, ALIGNED, false><<<grid, kThreads, 0, stream>>>(P);
@@ -210,6 +212,11 @@ void spec_verify_debug_config(int32_t path, int32_t spin_limit)
 {
     g_path.store(path >= 0 && path <= 2 ? path : 0);
     g_spin_limit.store(spin_limit >= 0 ? spin_limit : kDefaultSpinLimit);
+}
+
+void spec_verify_debug_profile(void *device_buffer)
+{
+    g_prof.store(static_cast<long long *>(device_buffer));
 }
 
 sv_status_t spec_verify_block(const void *target_logits, const void *draft_logits,
