@@ -18,9 +18,6 @@ namespace {
 
 using namespace sv;
 
-// The fused kernel lets the units of one row wait for each other, so all of them must be able
-// to be resident at once; with at most this many units per row they fit on any gfx950 part.
-constexpr int kMaxFusedUnitsPerRow = 128;
 constexpr int kDefaultSpinLimit = 1 << 20;
 
 std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused (testing hook)
@@ -28,14 +25,14 @@ std::atomic<int> g_spin_limit{kDefaultSpinLimit};
 std::atomic<long long *> g_prof{nullptr};          // device buffer for per-unit timestamps (tuning hook)
 
 struct Layout {
-    int nu;                 // chunks of kChunk logits per row
     size_t total;
     // fused path
     bool fused_ok;
-    int nuf, nw, units_per_seq;
-    size_t control_words;   // header + rowcnt + rowflag + seqcnt, in ints, at offset 0
-    size_t off_rowcnt, off_rowflag, off_seqcnt, off_rowrec, off_pstats, off_qstats, off_spart, off_rpart;
+    int nu, nuf, units_per_seq;   // wave chunks per row, units of the last target row, units per sequence
+    size_t control_words;         // header, seqcnt, ratio, pstat, qstat: in ints, at offset 0, zero between calls
+    size_t off_seqcnt, off_ratio, off_pstat, off_qstat, off_spart, off_rpart;
     // staged path
+    int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
     size_t off_stats, off_coef, off_sspart, off_srpart;
 };
@@ -43,32 +40,44 @@ struct Layout {
 bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
 {
     if (B < 1 || gamma < 1 || V < 1 || gamma > SV_MAX_GAMMA) return false;
-    L.nu = (V + kChunk - 1) / kChunk;
+    L.nchunks = (V + kChunk - 1) / kChunk;
     L.rows_total = (size_t)B * (2 * (size_t)gamma + 1);
-    if (L.rows_total * (size_t)L.nu > 0x7fffffffull) return false;          // 1-D grids of 32-bit size
+    if (L.rows_total * (size_t)L.nchunks > 0x7fffffffull) return false;     // 1-D grids of 32-bit size
     const size_t rows_t = (size_t)B * (gamma + 1), rows_d = (size_t)B * gamma;
 
+    L.nu = (V + kWaveChunk - 1) / kWaveChunk;
     L.nuf = (L.nu + 1) / 2;
-    L.nw = 2 * L.nuf * kWaves;
     L.units_per_seq = gamma * L.nu + L.nuf;
-    L.fused_ok = L.nu <= kMaxFusedUnitsPerRow;
-    L.control_words = kHdrWords + 2 * rows_t + (size_t)B;
-    L.off_rowcnt = kHdrWords * sizeof(int);
-    L.off_rowflag = L.off_rowcnt + rows_t * sizeof(int);
-    L.off_seqcnt = L.off_rowflag + rows_t * sizeof(int);
-    size_t off = align_up(L.control_words * sizeof(int), 256);
-    L.off_rowrec = off; off = align_up(off + rows_t * sizeof(RowRec), 256);
-    L.off_pstats = off; off = align_up(off + rows_t * L.nw * sizeof(unsigned long long), 256);
-    L.off_qstats = off; off = align_up(off + rows_d * L.nw * sizeof(unsigned long long), 256);
-    L.off_spart = off;  off = align_up(off + rows_d * L.nw * sizeof(float), 256);
-    L.off_rpart = off;  off = align_up(off + rows_d * L.nw * sizeof(float), 256);
+    L.fused_ok = L.nu <= kMaxUnitsPerRow && (size_t)B * L.units_per_seq <= 0x7fffffffull;
+    size_t off = kHdrWords * sizeof(int);
+    L.off_seqcnt = off; off = align_up(off + (size_t)B * 2 * sizeof(int), 8);
+    L.off_ratio = off;  off += rows_d * sizeof(u64);
+    L.off_pstat = off;  off += rows_t * 2 * L.nuf * sizeof(u64);
+    L.off_qstat = off;  off += rows_d * L.nu * sizeof(u64);
+    L.control_words = off / sizeof(int);
+    off = align_up(off, 256);
+    L.off_spart = off;  off = align_up(off + rows_d * L.nu * sizeof(float), 256);
+    L.off_rpart = off;  off = align_up(off + rows_d * L.nu * sizeof(float), 256);
     // the staged path's scratch follows, so that it never touches the control words
-    L.off_stats = off;  off = align_up(off + L.rows_total * L.nu * sizeof(float2), 256);
+    L.off_stats = off;  off = align_up(off + L.rows_total * L.nchunks * sizeof(float2), 256);
     L.off_coef = off;   off = align_up(off + rows_t * sizeof(SeqCoef), 256);
-    L.off_sspart = off; off = align_up(off + rows_d * L.nu * sizeof(float), 256);
-    L.off_srpart = off; off = align_up(off + rows_d * L.nu * sizeof(float), 256);
+    L.off_sspart = off; off = align_up(off + rows_d * L.nchunks * sizeof(float), 256);
+    L.off_srpart = off; off = align_up(off + rows_d * L.nchunks * sizeof(float), 256);
     L.total = off;
     return true;
+}
+
+// One-wave workgroups of a kernel that the current device keeps resident at once (cached per kernel).
+template <typename K>
+int resident_waves(K kernel, int &cache)
+{
+    if (cache > 0) return cache;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kWave, 0) != hipSuccess) return 0;
+    cache = cus * per_cu;
+    return cache;
 }
 
 template <typename T, bool ALIGNED>
@@ -85,21 +94,21 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
     float *rpart = reinterpret_cast<float *>(ws + L.off_srpart);
     const int n_target_rows = B * (gamma + 1);
 
-    row_stats_kernel<T, ALIGNED><<<(unsigned)(L.rows_total * L.nu), kThreads, 0, stream>>>(
-        target, draft, B, gamma, V, k, L.nu, stats);
+    row_stats_kernel<T, ALIGNED><<<(unsigned)(L.rows_total * L.nchunks), kThreads, 0, stream>>>(
+        target, draft, B, gamma, V, k, L.nchunks, stats);
     const size_t sm2 = 2 * (gamma + 1) * sizeof(double) + 2 * (gamma + 1) * sizeof(float);
-    prefix_weights_kernel<T><<<B, 64, sm2, stream>>>(target, draft, tokens, gamma, V, k, kd, kd / (double)k - 1.0, L.nu,
+    prefix_weights_kernel<T><<<B, 64, sm2, stream>>>(target, draft, tokens, gamma, V, k, kd, kd / (double)k - 1.0, L.nchunks,
                                                     n_target_rows, algo, stats, coef);
-    const unsigned pair_blocks = (unsigned)((size_t)B * gamma * L.nu);
+    const unsigned pair_blocks = (unsigned)((size_t)B * gamma * L.nchunks);
     if (algo == kGreedy)
         residual_kernel<T, ALIGNED, true><<<pair_blocks, kThreads, 0, stream>>>(
-            target, draft, gamma, V, k, L.nu, coef, spart, rpart);
+            target, draft, gamma, V, k, L.nchunks, coef, spart, rpart);
     else
         residual_kernel<T, ALIGNED, false><<<pair_blocks, kThreads, 0, stream>>>(
-            target, draft, gamma, V, k, L.nu, coef, spart, rpart);
+            target, draft, gamma, V, k, L.nchunks, coef, spart, rpart);
     const size_t sm4 = 2 * (gamma + 1) * sizeof(double);
     finalize_kernel<T, ALIGNED><<<B, kThreads, sm4, stream>>>(
-        target, draft, uniforms, gamma, V, k, L.nu, algo, stats, coef, spart, rpart,
+        target, draft, uniforms, gamma, V, k, L.nchunks, algo, stats, coef, spart, rpart,
         accept_len, next_token, debug_out);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
@@ -110,26 +119,37 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
 {
+    static int cap_plain = 0, cap_greedy = 0;       // resident waves of the two instantiations
+    const int capacity = algo == kGreedy ? resident_waves(fused_verify_kernel<T, ALIGNED, true>, cap_greedy)
+                                         : resident_waves(fused_verify_kernel<T, ALIGNED, false>, cap_plain);
+    if (capacity < 2) return SV_ERR_HIP;
     FusedParams P;
     P.target = target; P.draft = draft; P.tokens = tokens; P.uniforms = uniforms;
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
-    P.nu = L.nu; P.nuf = L.nuf; P.units_per_seq = L.units_per_seq; P.nw = L.nw;
+    P.nu = L.nu; P.nuf = L.nuf; P.units_per_seq = L.units_per_seq;
+    P.total_units = B * L.units_per_seq;
+    // all waves must be resident together: they wait for each other
+    P.n_waves = capacity < P.total_units ? capacity : P.total_units;
+    if (P.n_waves < P.total_units && P.n_waves < 2 * L.nu) return SV_ERR_UNSUPPORTED;   // a row's units run side by side
+    // groups of sequences so large that one position of a group fills at least one round of waves
+    {
+        const int min_seqs = (P.n_waves + L.nu - 1) / L.nu;
+        const int groups = B / min_seqs > 1 ? B / min_seqs : 1;
+        P.group_seqs = (B + groups - 1) / groups;
+    }
     P.spin_limit = g_spin_limit.load();
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);
-    P.rowcnt = reinterpret_cast<int *>(ws + L.off_rowcnt);
-    P.rowflag = reinterpret_cast<int *>(ws + L.off_rowflag);
     P.seqcnt = reinterpret_cast<int *>(ws + L.off_seqcnt);
-    P.rowrec = reinterpret_cast<RowRec *>(ws + L.off_rowrec);
-    P.pstats = reinterpret_cast<unsigned long long *>(ws + L.off_pstats);
-    P.qstats = reinterpret_cast<unsigned long long *>(ws + L.off_qstats);
+    P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
+    P.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
+    P.qstat = reinterpret_cast<u64 *>(ws + L.off_qstat);
     P.spart = reinterpret_cast<float *>(ws + L.off_spart);
     P.rpart = reinterpret_cast<float *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
     P.prof = g_prof.load();
-    const unsigned grid = (unsigned)((size_t)B * L.units_per_seq);   // exactly one workgroup per ticket
-    if (algo == kGreedy) fused_verify_kernel<T, ALIGNED, true><<<grid, kThreads, 0, stream>>>(P);
-    else fused_verify_kernel<T, ALIGNED, false><<<grid, kThreads, 0, stream>>>(P);
+    if (algo == kGreedy) fused_verify_kernel<T, ALIGNED, true><<<(unsigned)P.n_waves, kWave, 0, stream>>>(P);
+    else fused_verify_kernel<T, ALIGNED, false><<<(unsigned)P.n_waves, kWave, 0, stream>>>(P);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
