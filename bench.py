@@ -51,6 +51,10 @@ def main():
     ap.add_argument("--algo", default="block", choices=["block", "token", "greedy"])
     ap.add_argument("--sets", type=int, default=4, help="distinct input sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", default="default", choices=["default", "staged", "fused"],
+                    help="kernel path (testing hook of the library)")
+    ap.add_argument("--spin-limit", type=int, default=-1,
+                    help="bound of the fused kernel's waits in polls (testing hook; 0 makes results invalid)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (sequences are independent; more GPUs "
@@ -62,6 +66,7 @@ def main():
     import workloads
 
     sv.load()
+    sv.spec_verify_debug_config({"default": 0, "staged": 1, "fused": 2}[args.path], args.spin_limit)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -101,7 +106,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "algo": args.algo, "B": cfg.B, "gamma": cfg.gamma, "V": cfg.V,
-                   "logit_dtype": cfg.dtype, "temperature": cfg.temperature, "input_sets": len(sets)},
+                   "logit_dtype": cfg.dtype, "temperature": cfg.temperature, "input_sets": len(sets), "path": args.path},
         "seq_verifications_per_s": calls_per_s * cfg.B,
         "mean_accept_len": float(tau.float().mean().item()),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -77,7 +77,7 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
                                         void *stream);
 
 /* Testing hook, process-wide: `path` 0 = the library's default kernels, 1 = the four-launch
- * staged kernels, 2 = the single-launch fused kernel (takes V <= 512 * 2048; larger sizes
+ * staged kernels, 2 = the single-launch fused kernel (takes V <= 128 * 8192; larger sizes
  * are then refused); `spin_limit` bounds every wait inside the fused kernel in polls
  * (negative: default).                                                                    */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);

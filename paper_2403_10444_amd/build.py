@@ -14,6 +14,9 @@ HIPCC_FLAGS = [
     # no implicit fused multiply-adds: a shift computed as m * k must be the SAME rounded number
     # wherever it is used (the kernels write every fma they want explicitly)
     "-ffp-contract=off",
+    # no NaN ever enters the arithmetic (logits are finite by contract; -inf marks positions beyond a
+    # row and is only ever compared, scaled or exponentiated): lets max/min compile to one instruction
+    "-fno-honor-nans",
     # keep the compiler from forming packed-FP32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",

@@ -106,34 +106,35 @@ __device__ __forceinline__ void load_vec(const T *row, int V, int idx, float *ou
 }
 
 // ------------------------------------------------------------------ wavefront reductions
-// Cross-lane moves inside a row of 16 lanes go through DPP, the last two steps through
-// the LDS crossbar.  Every lane ends with the same value; the order is fixed.
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v)
+// All cross-lane moves go through DPP (no LDS crossbar): four steps inside each row of 16 lanes,
+// two row broadcasts that leave the result in lane 63, one readlane.  Every lane gets the same
+// value; the order of the operations is fixed.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_move(float v, float fill = 0.f)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
 }
 
 __device__ __forceinline__ float wave_sum(float v)
 {
-    v += dpp_move<0xB1>(v);      // quad_perm [1,0,3,2]
-    v += dpp_move<0x4E>(v);      // quad_perm [2,3,0,1]
-    v += dpp_move<0x141>(v);     // row_half_mirror
-    v += dpp_move<0x140>(v);     // row_mirror
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
+    v += dpp_move<0xB1>(v);              // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);              // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);             // row_half_mirror
+    v += dpp_move<0x140>(v);             // row_mirror: every lane holds its row's sum
+    v += dpp_move<0x142, 0xa>(v);        // row_bcast15 into rows 1 and 3
+    v += dpp_move<0x143, 0xc>(v);        // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ float wave_max(float v)
 {
-    v = fmaxf(v, dpp_move<0xB1>(v));
-    v = fmaxf(v, dpp_move<0x4E>(v));
-    v = fmaxf(v, dpp_move<0x141>(v));
-    v = fmaxf(v, dpp_move<0x140>(v));
-    v = fmaxf(v, __shfl_xor(v, 16, 64));
-    v = fmaxf(v, __shfl_xor(v, 32, 64));
-    return v;
+    v = fmaxf(v, dpp_move<0xB1>(v, v));
+    v = fmaxf(v, dpp_move<0x4E>(v, v));
+    v = fmaxf(v, dpp_move<0x141>(v, v));
+    v = fmaxf(v, dpp_move<0x140>(v, v));
+    v = fmaxf(v, dpp_move<0x142, 0xa>(v, v));
+    v = fmaxf(v, dpp_move<0x143, 0xc>(v, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ double wave_sum_double(double v)

@@ -3,37 +3,38 @@
 // The method needs two sweeps over each (target row i, draft row i) pair: the residual mass
 // S_i = sum_x max(w_i p_i(x) - q_i(x), 0) of Alg. 2 depends on the rows' normalisers and on
 // w_i, which depends on the normalisers of all earlier rows of the sequence.  Here the second
-// sweep never touches memory.  The kernel is a grid of independent, persistent WAVEFRONTS
-// (workgroups of 64 threads; no LDS, no workgroup barrier).  A *unit* is 2048 contiguous logits
-// of a row pair (or two such chunks of the last target row, which has no draft row).  A wave
-//   1. unpacks its unit's 2 x 2048 logits (32 + 32 per lane) and at once issues the loads of its
-//      NEXT unit into the freed registers, so that HBM stays busy during everything below,
-//   2. turns the logits into exp2(y - shift) with per-lane shifts and KEEPS those 2 x 32 floats
-//      per lane in registers; publishes the unit's partial normalisers (shift, sum) as two words,
-//   3. waits for the words of the other units of its row, derives L_p and L_q, and, with the
-//      ratios of the earlier rows (fetched a round ago), w_i (Alg. 2: w_i = min(w_{i-1} r_i, 1)),
-//   4. forms its share of S_i from the registers, stores it, counts itself done, and goes on.
-// Wave g handles units g, g+G, g+2G, ... where G is the number of waves the device keeps
-// resident.  Units are ordered position-major inside groups of sequences (all row pairs of
-// position 0, then position 1, ..., then the last target rows), so that the ratios of earlier
-// positions were published a whole round before they are needed and a unit only ever waits for
-// the other units of its own row.  A wave that has no unit left turns to whole sequences: it
-// waits until a sequence's row pairs are counted done and runs the accept tests and the
-// inverse-CDF draw.
+// sweep never touches memory: the first sweep's exponentials stay in registers until the
+// row's normalisers are known.
+//
+// A *unit* is 2048 contiguous logits of a row pair (or two such chunks of the last target row,
+// which has no draft row) and belongs to one wavefront; a workgroup is four independent waves
+// (four neighbouring units; no LDS, no barrier).  A wave
+//   1. loads its 2 x 2048 logits (32 + 32 per lane, 16-byte loads, 1 KB per load instruction),
+//   2. turns them into exp2(y - shift) with per-lane shifts and KEEPS those 2 x 32 floats per
+//      lane in registers; publishes the unit's partial normalisers (shift, sum) as two words,
+//   3. waits for the words of the other units of its row, which give L_p and L_q, and reads the
+//      ratios of the earlier rows, which give w_i (Alg. 2: w_i = min(w_{i-1} r_i, 1)),
+//   4. forms its share of S_i from the registers and publishes it.
+// Workgroups are ordered position-major inside groups of sequences (all row pairs of position
+// 0, then position 1, ..., then the last target rows), so the ratio of an earlier position was
+// published long before a later one asks for it, and a unit only ever waits for the units of
+// its own row, which start next to it.  The first unit of a sequence's last target row then
+// finishes the sequence: it waits for all of the sequence's partial sums and runs the accept
+// tests and the inverse-CDF draw.
 //
 // Everything that crosses waves is a self-announcing word: it is zero between calls and
 // non-zero once written (a packed (shift, sum) pair always has a non-zero sum or a -inf shift;
-// ratio words get their lowest mantissa bit set).  Words are written and read with agent-scope
-// atomic accesses, which go through to device memory instead of living in one XCD's L2; no
-// agent-scope fence is needed (on this part such a fence writes back / invalidates a whole L2
-// and cost more than the rest of the kernel).  Where a counter announces other stores, the
-// wave first waits for those stores to complete.
+// ratio words and partial sums get their lowest mantissa bit set).  Words are written and read
+// with agent-scope atomic accesses, which go through to device memory instead of living in one
+// XCD's L2; no agent-scope fence is needed (on this part such a fence writes back /
+// invalidates a whole L2 and cost more than the rest of the kernel).
 //
-// Progress: a unit waits only for units of its own row (waves next to its own, same round) and
-// of earlier rows of its sequence (earlier in the unit order), and publishing never waits, so by
-// induction over the unit index every word gets written as long as all G waves are resident (G
-// is taken from the occupancy query).  Every wait is also bounded by a spin limit; running into
-// it sets the workspace's error word and goes on instead of hanging.
+// Progress: the hardware starts workgroups in index order (round-robin over the XCDs, in order
+// within each).  A unit waits only for units of its own row (at most kMaxUnitsPerRow / 4
+// workgroups away, far fewer than one XCD holds) and of earlier rows of its sequence (earlier
+// workgroups), and publishing never waits: the grid always drains.  Every wait is also
+// bounded by a spin limit; running into it sets the workspace's error word and goes on
+// instead of hanging.
 #pragma once
 
 #include "common.hpp"
@@ -41,6 +42,8 @@
 namespace sv {
 
 constexpr int kWave = 64;
+constexpr int kLaneLogits = 32;                      // logits of one row that a lane holds of a unit
+constexpr int kUnitLogits = kWave * kLaneLogits;    // contiguous logits of one row in a unit
 constexpr int kMaxUnitsPerRow = 512;     // wave chunks per row the fused kernel takes (V <= 1 Mi logits)
 
 // Word 0 of an initialised workspace: a constant mixed with the shape it was initialised for.
@@ -62,32 +65,30 @@ struct FusedParams {
     double kd;            // log2(e) / T in double
     double k_eps;         // kd / k - 1: what rounding k to float left out (|k_eps| <= 2^-24)
     int algo;
-    int nu;               // units (wave chunks) per row pair = ceil(V / kWaveChunk)
-    int nuf;              // units of the last target row (two wave chunks each) = ceil(nu / 2)
-    int units_per_seq;    // gamma * nu + nuf
-    int total_units;      // B * units_per_seq
-    int group_seqs;       // sequences per group of the unit order
-    int n_waves;          // waves launched (all persistent)
+    int nu;               // units (wave chunks) per row pair = 4 * workgroups per row pair
+    int nuf;              // units of the last target row (two wave chunks each) = nu / 2 rounded up to even
+    int wgs_per_seq;      // workgroups per sequence = (gamma * nu + nuf) / 4
+    int group_seqs;       // sequences per group of the workgroup order
     int spin_limit;
     int magic;            // workspace_magic(B, gamma, V)
     int *header;
-    int *seqcnt;          // [B, 2]                   row-pair units / last-row units of the sequence that are done
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
     u64 *pstat;           // [B, gamma+1, 2 * nuf]    packed (shift, sum) per wave chunk of a target row
     u64 *qstat;           // [B, gamma, nu]           same for the draft rows
-    float *spart;         // [B, gamma, nu]           residual partial sums per wave chunk
-    float *rpart;         // [B, gamma, nu]           greedy only: partial sums of max(q - w p, 0)
+    unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
+    unsigned *rpart;      // [B, gamma, nu]           greedy only: partial sums of max(q - w p, 0), same encoding
     int32_t *accept_len, *next_token;
     float *debug_out;
-    long long *prof;      // NULL, or [units + B, 8] timestamps (100 MHz ticks) for tuning
+    long long *prof;      // NULL, or [workgroups, 8] timestamps (100 MHz ticks) for tuning
 };
 
 // ---- agent-scope accessors for words that other waves (on any XCD) write or read
-__device__ __forceinline__ void stores_done() { __builtin_amdgcn_s_waitcnt(0); }   // vmcnt(0): this wave's stores are out
 __device__ __forceinline__ int ld_i32(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void st_i32(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ float ld_f32(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void st_f32(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ unsigned ld_u32(const unsigned *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_u32(unsigned *p, unsigned v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ unsigned pack_partial(float v) { return __float_as_uint(v) | 1u; }
+__device__ __forceinline__ float unpack_partial(unsigned w) { return __uint_as_float(w & ~1u); }
 __device__ __forceinline__ u64 ld_u64(const u64 *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void st_u64(u64 *p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ u64 pack_stat(float shift, float sum)
@@ -99,32 +100,44 @@ __device__ __forceinline__ float stat_sum(u64 v) { return __uint_as_float((unsig
 __device__ __forceinline__ u64 pack_ratio(double log2r) { return (u64)__double_as_longlong(log2r) | 1ull; }
 __device__ __forceinline__ double unpack_ratio(u64 v) { return __longlong_as_double((long long)v); }
 
-// A word that is zero until its producer has written it.  Gives up after `limit` polls.
-__device__ __forceinline__ u64 wait_word(const u64 *p, int limit, bool &gave_up)
+// The value a given lane holds (lane index uniform over the wave).
+__device__ __forceinline__ u64 read_lane_u64(u64 v, int lane)
 {
-    u64 v = ld_u64(p);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v & 0xffffffffull), lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), lane);
+    return ((u64)hi << 32) | lo;
+}
+
+// A word that is zero until its producer has written it: lanes with `need` poll *p until it is
+// non-zero (`v` may already hold it).  One loop for the whole wave; gives up after `limit` polls.
+__device__ __forceinline__ u64 wait_word(const u64 *p, u64 v, bool need, int limit, bool &gave_up)
+{
     int spins = 0;
-    while (v == 0) {
+    while (__any(need && v == 0)) {
         if (++spins > limit) { gave_up = true; break; }
         __builtin_amdgcn_s_sleep(1);
-        v = ld_u64(p);
+        if (need && v == 0) v = ld_u64(p);
     }
     return v;
 }
-
-// A counter that only grows.  Lane 0 polls; every lane gets the verdict.
-__device__ __forceinline__ bool wait_count(const int *p, int target, int limit)
+__device__ __forceinline__ u64 wait_word(const u64 *p, int limit, bool &gave_up)
 {
-    int ok = 0;
-    if ((threadIdx.x & 63) == 0) {
-        int spins = 0;
-        for (;;) {
-            ok = ld_i32(p) >= target;
-            if (ok || ++spins > limit) break;
-            __builtin_amdgcn_s_sleep(4);
-        }
+    return wait_word(p, ld_u64(p), true, limit, gave_up);
+}
+
+__device__ __forceinline__ unsigned wait_word32(const unsigned *p, unsigned v, bool need, int limit, bool &gave_up)
+{
+    int spins = 0;
+    while (__any(need && v == 0)) {
+        if (++spins > limit) { gave_up = true; break; }
+        __builtin_amdgcn_s_sleep(1);
+        if (need && v == 0) v = ld_u32(p);
     }
-    return __builtin_amdgcn_readfirstlane(ok) != 0;
+    return v;
+}
+__device__ __forceinline__ unsigned wait_word32(const unsigned *p, int limit, bool &gave_up)
+{
+    return wait_word32(p, ld_u32(p), true, limit, gave_up);
 }
 
 // log2 of a positive float with an absolute error of a few 1e-8: exponent + log2(mantissa in [1,2)).
@@ -146,13 +159,19 @@ struct StatAcc {
     }
 };
 
-// Log2-normaliser of a row from the words of its n wave chunks: every lane polls entries lane,
-// lane+64, ... (in that fixed order), then the wave combines.  Returns L; M_out is the largest shift.
-__device__ __forceinline__ double row_normaliser(const u64 *words, int n, int limit, bool &gave_up, float &M_out)
+// Log2-normaliser of a row from the words of its n units: every lane takes entries lane, lane+64,
+// ... (in that fixed order), then the wave combines.  `first` is this lane's entry `lane` as the
+// caller loaded it (0: not there yet, it is polled).  WIDE: the row has more than 64 units.
+// Returns L; M_out is the largest shift.
+template <bool WIDE>
+__device__ __forceinline__ double row_normaliser(const u64 *words, int n, int limit, bool &gave_up, float &M_out, u64 first)
 {
     const int lane = threadIdx.x & 63;
     StatAcc acc;
-    for (int e = lane; e < n; e += kWave) acc.add(wait_word(words + e, limit, gave_up));
+    const u64 w0 = wait_word(words + lane, first, lane < n, limit, gave_up);
+    if (lane < n) acc.add(w0);
+    if constexpr (WIDE)
+        for (int e = lane + kWave; e < n; e += kWave) acc.add(wait_word(words + e, limit, gave_up));
     const float M = wave_max(acc.m);
     const float z = wave_sum(acc.m > -INFINITY ? acc.z * fast_exp2(acc.m - M) : 0.f);
     M_out = M;
@@ -164,38 +183,40 @@ struct Unit {
     bool last_row;
 };
 
-// Unit order: groups of `group_seqs` sequences; inside a group first the row pairs position-major
-// (position, sequence, chunk), then the units of the last target rows (sequence, chunk pair).
-__device__ __forceinline__ Unit decode_unit(const FusedParams &P, int u)
+// Workgroup order: groups of `group_seqs` sequences; inside a group first the row pairs
+// position-major (position, sequence, chunk), then the last target rows (sequence, chunk pair).
+// Wave w of workgroup g takes unit 4 * (g's chunk) + w.
+__device__ __forceinline__ Unit decode_unit(const FusedParams &P, int g, int wave)
 {
     Unit U;
-    const int per_group = P.group_seqs * P.units_per_seq;
-    const int g = u / per_group;
-    int r = u - g * per_group;
-    const int b0 = g * P.group_seqs;
+    const int wpr = P.nu / kWaves, wpl = P.nuf / kWaves;        // workgroups per row pair / per last row
+    const int per_group = P.group_seqs * P.wgs_per_seq;
+    const int grp = g / per_group;
+    int r = g - grp * per_group;
+    const int b0 = grp * P.group_seqs;
     const int nb = P.B - b0 < P.group_seqs ? P.B - b0 : P.group_seqs;   // sequences in this group
-    const int pairs = P.gamma * nb * P.nu;
+    const int pairs = P.gamma * nb * wpr;
     U.last_row = r >= pairs;
     if (!U.last_row) {
-        U.i = r / (nb * P.nu);
-        r -= U.i * nb * P.nu;
-        const int bl = r / P.nu;
+        U.i = r / (nb * wpr);
+        r -= U.i * nb * wpr;
+        const int bl = r / wpr;
         U.b = b0 + bl;
-        U.c = r - bl * P.nu;
+        U.c = (r - bl * wpr) * kWaves + wave;
     } else {
         r -= pairs;
-        const int bl = r / P.nuf;
+        const int bl = r / wpl;
         U.i = P.gamma;
         U.b = b0 + bl;
-        U.c = r - bl * P.nuf;
+        U.c = (r - bl * wpl) * kWaves + wave;
     }
     return U;
 }
 
-// The 2 x 32 logits of one lane, as loaded: raw 16-byte vectors on the aligned path.
+// The logits of one lane (both rows), as loaded: raw 16-byte vectors on the aligned path.
 template <typename T, bool ALIGNED> struct RawSlice;
 template <typename T> struct RawSlice<T, true> {
-    static constexpr int kNV = kPerThread / ElemTraits<T>::kVec;
+    static constexpr int kNV = kLaneLogits / ElemTraits<T>::kVec;
     uint4 a[kNV], b[kNV];
 };
 template <typename T> struct RawSlice<T, false> { };      // the element-wise path loads when it unpacks
@@ -219,8 +240,8 @@ __device__ __forceinline__ Stream<T> unit_streams(const FusedParams &P, const Un
     Stream<T> S;
     S.rowA = target + ((size_t)U.b * (P.gamma + 1) + U.i) * P.V;
     S.rowB = U.last_row ? S.rowA : draft + ((size_t)U.b * P.gamma + U.i) * P.V;
-    S.firstA = (U.last_row ? 2 * U.c : U.c) * kWaveChunk + lane * kVec;
-    S.firstB = (U.last_row ? 2 * U.c + 1 : U.c) * kWaveChunk + lane * kVec;
+    S.firstA = (U.last_row ? 2 * U.c : U.c) * kUnitLogits + lane * kVec;
+    S.firstB = (U.last_row ? 2 * U.c + 1 : U.c) * kUnitLogits + lane * kVec;
     return S;
 }
 
@@ -229,7 +250,7 @@ __device__ __forceinline__ void issue_loads(const Stream<T> &S, int V, RawSlice<
 {
     if constexpr (ALIGNED) {
         constexpr int kVec = ElemTraits<T>::kVec;
-        constexpr int kNV = kPerThread / kVec;
+        constexpr int kNV = kLaneLogits / kVec;
 #pragma unroll
         for (int v = 0; v < kNV; ++v) {
             const int ia = S.firstA + v * kWave * kVec, ib = S.firstB + v * kWave * kVec;
@@ -263,36 +284,52 @@ __device__ __forceinline__ void unpack_vec(const uint4 &v, bool valid, float *ou
 
 template <typename T, bool ALIGNED>
 __device__ __forceinline__ void unpack_slice(const Stream<T> &S, int V, const RawSlice<T, ALIGNED> &raw,
-                                             float (&xa)[kPerThread], float (&xb)[kPerThread])
+                                             float (&xa)[kLaneLogits], float (&xb)[kLaneLogits])
 {
     constexpr int kVec = ElemTraits<T>::kVec;
-    constexpr int kNV = kPerThread / kVec;
+    constexpr int kNV = kLaneLogits / kVec;
+    if constexpr (ALIGNED) {
 #pragma unroll
-    for (int v = 0; v < kNV; ++v) {
-        const int ia = S.firstA + v * kWave * kVec, ib = S.firstB + v * kWave * kVec;
-        if constexpr (ALIGNED) {
-            unpack_vec<T>(raw.a[v], ia < V, xa + v * kVec);
-            unpack_vec<T>(raw.b[v], ib < V, xb + v * kVec);
-        } else {
-            load_vec<T, false>(S.rowA, V, ia, xa + v * kVec);
-            load_vec<T, false>(S.rowB, V, ib, xb + v * kVec);
+        for (int v = 0; v < kNV; ++v) {
+            unpack_vec<T>(raw.a[v], true, xa + v * kVec);
+            unpack_vec<T>(raw.b[v], true, xb + v * kVec);
+        }
+        // only a row's last units reach beyond the row (wave-uniform test): blank what lies beyond
+        const int lastA = __builtin_amdgcn_readfirstlane(S.firstA) + kUnitLogits;
+        const int lastB = __builtin_amdgcn_readfirstlane(S.firstB) + kUnitLogits;
+        if (lastA > V || lastB > V) {
+#pragma unroll
+            for (int v = 0; v < kNV; ++v) {
+                const bool out_a = S.firstA + v * kWave * kVec >= V, out_b = S.firstB + v * kWave * kVec >= V;
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) {
+                    if (out_a) xa[v * kVec + e] = -INFINITY;
+                    if (out_b) xb[v * kVec + e] = -INFINITY;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < kNV; ++v) {
+            load_vec<T, false>(S.rowA, V, S.firstA + v * kWave * kVec, xa + v * kVec);
+            load_vec<T, false>(S.rowB, V, S.firstB + v * kWave * kVec, xb + v * kVec);
         }
     }
 }
 
-// First sweep over the 32 logits a lane holds of one row: x[j] becomes exp2(x[j] * k - shift)
-// with shift = k * (largest of the 32), `mk` is that shift (-inf when all 32 lie beyond the row)
-// and `s` the sum of the 32 exponentials.
-__device__ __forceinline__ void exp_sum(float (&x)[kPerThread], float k, float &shift, float &mk, float &s)
+// First sweep over the logits a lane holds of one row: x[j] becomes exp2(x[j] * k - shift) with
+// shift = k * (largest of them), `mk` is that shift (-inf when all of them lie beyond the row)
+// and `s` the sum of the exponentials.
+__device__ __forceinline__ void exp_sum(float (&x)[kLaneLogits], float k, float &shift, float &mk, float &s)
 {
     float m = x[0];
 #pragma unroll
-    for (int j = 1; j < kPerThread; ++j) m = fmaxf(m, x[j]);
+    for (int j = 1; j < kLaneLogits; ++j) m = fmaxf(m, x[j]);
     mk = m * k;
     shift = m > -INFINITY ? mk : 0.f;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};     // four partial sums: shorter chains, smaller rounding error
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
+    for (int j = 0; j < kLaneLogits; ++j) {
         x[j] = fast_exp2(__builtin_fmaf(x[j], k, -shift));
         acc[j & 3] += x[j];
     }
@@ -324,37 +361,67 @@ __device__ __forceinline__ float wave_inclusive_scan(float v, float &exclusive, 
     return v;
 }
 
-// Accept tests and inverse-CDF draw of one sequence (one wave), once its row pairs are counted done.
+// Accept tests and inverse-CDF draw of one sequence (one wave), once all of its residual partial
+// sums have been published.
 template <typename T, bool ALIGNED, bool GREEDY>
 __device__ void finalize_sequence(const FusedParams &P, int b)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
-    constexpr int kNV = kPerThread / kVec;
+    constexpr int kNV = kLaneLogits / kVec;
     const int lane = threadIdx.x & 63;
     const int gamma = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
     const T *target = static_cast<const T *>(P.target);
     const T *draft = static_cast<const T *>(P.draft);
     const size_t base = (size_t)b * (gamma + 1);
-    bool gave_up = !wait_count(P.seqcnt + 2 * b, gamma * nu, P.spin_limit);
+    bool gave_up = false;
 
     // Row results live in lane j's registers (gamma <= 64): L_p, L_q, M_p, S, rejected mass, log2 r_{j+1}.
+    // S_j = sum of the row's partial sums: lanes take entries lane, lane+64, ..., then a wave sum.
     double my_Lp = 0.0, my_Lq = 0.0, my_S = 0.0, my_R = 0.0, my_lr = 0.0;
     float my_Mp = 0.f;
-    for (int j = 0; j < gamma; ++j) {
-        float Mp, Mq;
-        const double Lp = row_normaliser(P.pstat + (base + j) * 2 * P.nuf, nu, P.spin_limit, gave_up, Mp);
-        const double Lq = row_normaliser(P.qstat + ((size_t)b * gamma + j) * nu, nu, P.spin_limit, gave_up, Mq);
-        double acc = 0.0, rej = 0.0;
-        for (int e = lane; e < nu; e += kWave) {
-            acc += (double)ld_f32(P.spart + ((size_t)b * gamma + j) * nu + e);
-            if constexpr (GREEDY) rej += (double)ld_f32(P.rpart + ((size_t)b * gamma + j) * nu + e);
-        }
-        acc = wave_sum_double(acc);
-        if constexpr (GREEDY) rej = wave_sum_double(rej);
-        if (lane == j) { my_Lp = Lp; my_Lq = Lq; my_Mp = Mp; my_S = acc; my_R = rej; }
-    }
     if (lane < gamma) my_lr = unpack_ratio(wait_word(P.ratio + (size_t)b * gamma + lane, P.spin_limit, gave_up));
+    constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
+    for (int j0 = 0; j0 < gamma; j0 += kBatch) {
+        unsigned sw[kBatch], rw[kBatch];
+        u64 pw[kBatch], qw[kBatch];
+#pragma unroll
+        for (int jj = 0; jj < kBatch; ++jj) {
+            sw[jj] = rw[jj] = 0; pw[jj] = qw[jj] = 0;
+            if (j0 + jj < gamma && lane < nu) {
+                const size_t drow = (size_t)b * gamma + j0 + jj;
+                sw[jj] = ld_u32(P.spart + drow * nu + lane);
+                if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + drow * nu + lane);
+                pw[jj] = ld_u64(P.pstat + (base + j0 + jj) * 2 * P.nuf + lane);
+                qw[jj] = ld_u64(P.qstat + drow * nu + lane);
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < kBatch; ++jj) {
+            const int j = j0 + jj;
+            if (j >= gamma) break;
+            const size_t drow = (size_t)b * gamma + j;
+            double acc = 0.0, rej = 0.0;
+            {
+                const unsigned w = wait_word32(P.spart + drow * nu + lane, sw[jj], lane < nu, P.spin_limit, gave_up);
+                if (lane < nu) acc += (double)unpack_partial(w);
+                if constexpr (GREEDY) {
+                    const unsigned r = wait_word32(P.rpart + drow * nu + lane, rw[jj], lane < nu, P.spin_limit, gave_up);
+                    if (lane < nu) rej += (double)unpack_partial(r);
+                }
+            }
+            for (int e = lane + kWave; e < nu; e += kWave) {
+                acc += (double)unpack_partial(wait_word32(P.spart + drow * nu + e, P.spin_limit, gave_up));
+                if constexpr (GREEDY) rej += (double)unpack_partial(wait_word32(P.rpart + drow * nu + e, P.spin_limit, gave_up));
+            }
+            acc = wave_sum_double(acc);
+            if constexpr (GREEDY) rej = wave_sum_double(rej);
+            float Mp, Mq;
+            const double Lp = row_normaliser<true>(P.pstat + (base + j) * 2 * P.nuf, nu, P.spin_limit, gave_up, Mp, pw[jj]);
+            const double Lq = row_normaliser<true>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw[jj]);
+            if (lane == j) { my_Lp = Lp; my_Lq = Lq; my_Mp = Mp; my_S = acc; my_R = rej; }
+        }
+    }
 
     // log2 w_j for lane j (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4 drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, lw_last = 0.0;
@@ -410,12 +477,11 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
         Mrow = __shfl(my_Mp, tau, kWave);
         rc = make_row_coef(__shfl(my_Lp, tau, kWave) - __shfl(my_lw, tau, kWave), __shfl(my_Lq, tau, kWave));
     } else {
-        // everything accepted: Y comes from p_gamma, so the last target row must be complete too
-        if (!wait_count(P.seqcnt + 2 * b + 1, P.nuf, P.spin_limit)) gave_up = true;
-        row_normaliser(P.pstat + (base + gamma) * 2 * P.nuf, 2 * P.nuf, P.spin_limit, gave_up, Mrow);
+        // everything accepted: Y comes from p_gamma; its words are polled until they are all there
+        row_normaliser<true>(P.pstat + (base + gamma) * 2 * P.nuf, 2 * P.nuf, P.spin_limit, gave_up, Mrow, 0);
     }
     const u64 *st = P.pstat + (base + tau) * 2 * P.nuf;
-    const float *sp = P.spart + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * nu;
+    const unsigned *sp = P.spart + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * nu;
     int slot = -1, last_nonzero = 0;
     double t_in = 0.0;
     for (int attempt = 0; attempt < 2 && slot < 0; ++attempt) {
@@ -427,7 +493,7 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
                 const int e = e0 + lane;
                 double part = 0.0;
                 if (e < n) {
-                    if (mode == 0) part = (double)ld_f32(sp + e);
+                    if (mode == 0) part = (double)unpack_partial(ld_u32(sp + e));
                     else {
                         const u64 v = ld_u64(st + e);
                         const float sh = stat_shift(v);
@@ -470,7 +536,7 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
         const u64 sv = ld_u64(st + slot);
         const float shift = stat_shift(sv), scale = fast_exp2(shift - Mrow);
         float t = mode == 0 ? (float)(t_in / (double)rc.cq) : (float)t_in;
-        const int first = slot * kWaveChunk + lane * kVec;
+        const int first = slot * kUnitLogits + lane * kVec;
         int y = -1, last_positive = -1;
 #pragma unroll
         for (int v = 0; v < kNV; ++v) {
@@ -522,155 +588,128 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
         if (lane == 0) P.next_token[b] = y;
     }
 
-    // ---- leave the sequence's words zero for the next call (the last row's units must be through first)
-    if (!wait_count(P.seqcnt + 2 * b + 1, P.nuf, P.spin_limit)) gave_up = true;
+    // ---- leave the sequence's words zero for the next call.  Every reader of the row-pair words has
+    // published its partial sum by now; the words of the last target row must all be written first.
+    for (int e = lane; e < 2 * P.nuf; e += kWave) wait_word(P.pstat + (base + gamma) * 2 * P.nuf + e, P.spin_limit, gave_up);
     if (gave_up && lane == 0) atomicOr(P.header + kHdrError, 1);
     for (int e = lane; e < (gamma + 1) * 2 * P.nuf; e += kWave) st_u64(P.pstat + base * 2 * P.nuf + e, 0);
-    for (int e = lane; e < gamma * nu; e += kWave) st_u64(P.qstat + (size_t)b * gamma * nu + e, 0);
+    for (int e = lane; e < gamma * nu; e += kWave) {
+        st_u64(P.qstat + (size_t)b * gamma * nu + e, 0);
+        st_u32(P.spart + (size_t)b * gamma * nu + e, 0);
+        if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * gamma * nu + e, 0);
+    }
     for (int e = lane; e < gamma; e += kWave) st_u64(P.ratio + (size_t)b * gamma + e, 0);
-    if (lane < 2) st_i32(P.seqcnt + 2 * b + lane, 0);
 }
 
 // ------------------------------------------------------------------ the kernel
-template <typename T, bool ALIGNED, bool GREEDY>
-__global__ __launch_bounds__(kWave) void fused_verify_kernel(const FusedParams P)
+template <typename T, bool ALIGNED, bool GREEDY, bool WIDE>
+__global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParams P)
 {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int gamma = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
+    const T *target = static_cast<const T *>(P.target);
+    const T *draft = static_cast<const T *>(P.draft);
 
     if (__builtin_nontemporal_load(P.header + kHdrMagic) != P.magic) {
         // the workspace was not initialised for this shape: report it through the outputs and leave
         if (blockIdx.x == 0)
-            for (int b = lane; b < P.B; b += kWave) { P.accept_len[b] = -1; P.next_token[b] = -1; }
+            for (int b = threadIdx.x; b < P.B; b += kThreads) { P.accept_len[b] = -1; P.next_token[b] = -1; }
+        return;
+    }
+#define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+    SV_STAMP(0);
+
+    const Unit U = decode_unit(P, blockIdx.x, wave);
+    const Stream<T> S = unit_streams<T>(P, U);
+    RawSlice<T, ALIGNED> raw;
+    issue_loads<T, ALIGNED>(S, V, raw);
+    const size_t trow = (size_t)U.b * (gamma + 1) + U.i, drow = (size_t)U.b * gamma + (U.last_row ? 0 : U.i);
+    // draft token X_{i+1} and its two logits: a row's first unit publishes the row's ratio from them
+    double ya = 0.0, yb = 0.0;
+    if (!U.last_row && U.c == 0) {
+        const int tok = P.tokens[(size_t)U.b * gamma + U.i];
+        ya = logit_as_double(S.rowA + tok);
+        yb = logit_as_double(S.rowB + tok);
+    }
+
+    // ---- first sweep: exponentials stay in xa / xb; the unit's two words go out
+    float xa[kLaneLogits], xb[kLaneLogits];
+    unpack_slice<T, ALIGNED>(S, V, raw, xa, xb);
+    float shiftA, mkA, sA, shiftB, mkB, sB;
+    exp_sum(xa, k, shiftA, mkA, sA);
+    exp_sum(xb, k, shiftB, mkB, sB);
+    {
+        const u64 stA = wave_stat(mkA, sA), stB = wave_stat(mkB, sB);
+        if (lane == 0) {
+            st_u64(P.pstat + trow * 2 * P.nuf + (U.last_row ? 2 * U.c : U.c), stA);
+            if (U.last_row) st_u64(P.pstat + trow * 2 * P.nuf + 2 * U.c + 1, stB);
+            else st_u64(P.qstat + drow * nu + U.c, stB);
+        }
+    }
+    SV_STAMP(1);
+
+    if (!U.last_row) {
+        // ---- the words of this row's units give L_p and L_q; the ratios of the earlier rows give w_i
+        bool gave_up = false;
+        const int e0 = lane < nu ? lane : nu - 1;
+        const u64 pw = ld_u64(P.pstat + trow * 2 * P.nuf + e0);
+        const u64 qw = ld_u64(P.qstat + drow * nu + e0);
+        u64 rt = 1;
+        if (P.algo != kToken && lane < U.i) rt = ld_u64(P.ratio + (size_t)U.b * gamma + lane);
+        float Mp, Mq;
+        const double Lp = row_normaliser<WIDE>(P.pstat + trow * 2 * P.nuf, nu, P.spin_limit, gave_up, Mp, pw);
+        const double Lq = row_normaliser<WIDE>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
+        SV_STAMP(2);
+        if (lane == 0 && U.c == 0) {
+            // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for the later rows.  The sweeps
+            // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that
+            // moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
+            // row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
+            const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
+            const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
+            st_u64(P.ratio + drow, pack_ratio(lp - lq));
+        }
+        // w_i from the ratios of the earlier rows (Alg. 2: w_i = min(w_{i-1} r_i, 1))
+        double log2w = 0.0;
+        if (P.algo != kToken) {
+            rt = wait_word(P.ratio + (size_t)U.b * gamma + (lane < gamma ? lane : gamma - 1), rt, lane < U.i, P.spin_limit, gave_up);
+            for (int j = 0; j < U.i; ++j) {
+                log2w += unpack_ratio(read_lane_u64(rt, j));
+                if (!GREEDY && log2w > 0.0) log2w = 0.0;
+            }
+            if (GREEDY) log2w = fmin(log2w, 100.0);             // keeps w p finite in float
+        }
+        if (gave_up && lane == 0) atomicOr(P.header + kHdrError, 1);
+        SV_STAMP(3);
+
+        // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq
+        const float cp = fast_exp2((float)((double)shiftA - (Lp - log2w)));
+        const float cq = fast_exp2((float)((double)shiftB - Lq));
+        float acc = 0.f, rej = 0.f;
+#pragma unroll
+        for (int j = 0; j < kLaneLogits; ++j) {
+            const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
+            if constexpr (GREEDY) { acc += fmaxf(d, 0.f); rej += fmaxf(-d, 0.f); }
+            else acc += __builtin_amdgcn_fmed3f(d, 0.f, 1.f);   // w p <= 1, so clamping to [0, 1] is max(d, 0); folds into the fma
+        }
+        acc = wave_sum(acc);
+        if constexpr (GREEDY) rej = wave_sum(rej);
+        if (lane == 0) {
+            if constexpr (GREEDY) st_u32(P.rpart + drow * nu + U.c, pack_partial(rej));
+            st_u32(P.spart + drow * nu + U.c, pack_partial(acc));
+        }
+        SV_STAMP(4);
         return;
     }
 
-#define SV_STAMP(slot) do { if (P.prof && lane == 0) P.prof[(size_t)u * 8 + (slot)] = wall_clock64(); } while (0)
-    int u = blockIdx.x;
-    Unit U = decode_unit(P, u);
-    Stream<T> S = unit_streams<T>(P, U);
-    RawSlice<T, ALIGNED> raw;
-    issue_loads<T, ALIGNED>(S, V, raw);
-    // lane j < i: log2 r_{j+1} of the earlier rows; lane 0 of a row's first unit: the two logits of
-    // draft token X_{i+1}, from which it publishes the row's own ratio
-    u64 rt = 1;
-    double ya = 0.0, yb = 0.0;
-    auto prefetch_scalars = [&](const Unit &W, const Stream<T> &SW, u64 &rt_out, double &ya_out, double &yb_out) {
-        rt_out = 1;
-        ya_out = yb_out = 0.0;
-        if (!W.last_row) {
-            if (lane < W.i && P.algo != kToken) rt_out = ld_u64(P.ratio + (size_t)W.b * gamma + lane);
-            if (lane == 0 && W.c == 0) {
-                const int tok = P.tokens[(size_t)W.b * gamma + W.i];
-                ya_out = logit_as_double(SW.rowA + tok);
-                yb_out = logit_as_double(SW.rowB + tok);
-            }
-        }
-    };
-    prefetch_scalars(U, S, rt, ya, yb);
-
-    for (;;) {
-        SV_STAMP(0);
-        float xa[kPerThread], xb[kPerThread];
-        unpack_slice<T, ALIGNED>(S, V, raw, xa, xb);
-
-        // ---- the next unit's loads go out as soon as the raw registers are free
-        const int un = u + P.n_waves;
-        const bool has_next = un < P.total_units;
-        Unit Un = U;
-        Stream<T> Sn = S;
-        u64 rt_n = 1;
-        double ya_n = 0.0, yb_n = 0.0;
-        if (has_next) {
-            Un = decode_unit(P, un);
-            Sn = unit_streams<T>(P, Un);
-            issue_loads<T, ALIGNED>(Sn, V, raw);
-            prefetch_scalars(Un, Sn, rt_n, ya_n, yb_n);
-        }
-
-        // ---- first sweep: exponentials stay in xa / xb; the unit's two words go out
-        float shiftA, mkA, sA, shiftB, mkB, sB;
-        exp_sum(xa, k, shiftA, mkA, sA);
-        exp_sum(xb, k, shiftB, mkB, sB);
-        const size_t trow = (size_t)U.b * (gamma + 1) + U.i, drow = (size_t)U.b * gamma + U.i;
-        {
-            const u64 stA = wave_stat(mkA, sA), stB = wave_stat(mkB, sB);
-            if (lane == 0) {
-                st_u64(P.pstat + trow * 2 * P.nuf + (U.last_row ? 2 * U.c : U.c), stA);
-                if (U.last_row) st_u64(P.pstat + trow * 2 * P.nuf + 2 * U.c + 1, stB);
-                else st_u64(P.qstat + drow * nu + U.c, stB);
-            }
-        }
-        SV_STAMP(1);
-
-        if (!U.last_row) {
-            // ---- the words of this row's units give L_p and L_q
-            bool gave_up = false;
-            float Mp, Mq;
-            const double Lp = row_normaliser(P.pstat + trow * 2 * P.nuf, nu, P.spin_limit, gave_up, Mp);
-            const double Lq = row_normaliser(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq);
-            SV_STAMP(2);
-            if (lane == 0 && U.c == 0) {
-                // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for the later rows.  The sweeps
-                // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that
-                // moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
-                // row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
-                const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
-                const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-                st_u64(P.ratio + drow, pack_ratio(lp - lq));
-            }
-            // ---- w_i from the ratios of the earlier rows (Alg. 2: w_i = min(w_{i-1} r_i, 1)); they were
-            // fetched a round ago and are polled only if they had not been published by then
-            double log2w = 0.0;
-            if (P.algo != kToken) {
-                if (lane < U.i && rt == 0) rt = wait_word(P.ratio + (size_t)U.b * gamma + lane, P.spin_limit, gave_up);
-                for (int j = 0; j < U.i; ++j) {
-                    log2w += unpack_ratio(__shfl(rt, j, kWave));
-                    if (!GREEDY && log2w > 0.0) log2w = 0.0;
-                }
-                if (GREEDY) log2w = fmin(log2w, 100.0);         // keeps w p finite in float
-            }
-            if (gave_up && lane == 0) atomicOr(P.header + kHdrError, 1);
-            SV_STAMP(3);
-
-            // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq
-            const float cp = fast_exp2((float)((double)shiftA - (Lp - log2w)));
-            const float cq = fast_exp2((float)((double)shiftB - Lq));
-            float acc = 0.f, rej = 0.f;
-#pragma unroll
-            for (int j = 0; j < kPerThread; ++j) {
-                const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
-                acc += fmaxf(d, 0.f);
-                if constexpr (GREEDY) rej += fmaxf(-d, 0.f);
-            }
-            acc = wave_sum(acc);
-            if constexpr (GREEDY) rej = wave_sum(rej);
-            if (lane == 0) {
-                st_f32(P.spart + drow * nu + U.c, acc);
-                if constexpr (GREEDY) st_f32(P.rpart + drow * nu + U.c, rej);
-            }
-            SV_STAMP(4);
-        }
-
-        // ---- count this unit as done, after its stores
-        if (lane == 0) {
-            stores_done();
-            __hip_atomic_fetch_add(P.seqcnt + 2 * U.b + (U.last_row ? 1 : 0), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+    // ---- the first unit of a sequence's last target row finishes the sequence
+    if (U.c == 0) {
         SV_STAMP(5);
-        if (!has_next) break;
-        u = un; U = Un; S = Sn; rt = rt_n; ya = ya_n; yb = yb_n;
+        finalize_sequence<T, ALIGNED, GREEDY>(P, U.b);
+        SV_STAMP(6);
     }
 #undef SV_STAMP
-
-    // ---- no unit left: finish whole sequences.  Waves are dealt sequences from the top index down,
-    // because those run out of units first.
-    for (int b = P.n_waves - 1 - (int)blockIdx.x; b < P.B; b += P.n_waves) {
-        if (P.prof && lane == 0) P.prof[(size_t)P.total_units * 8 + (size_t)b * 8 + 0] = wall_clock64();
-        finalize_sequence<T, ALIGNED, GREEDY>(P, b);
-        if (P.prof && lane == 0) P.prof[(size_t)P.total_units * 8 + (size_t)b * 8 + 1] = wall_clock64();
-    }
 }
 
 // Clears the control words of a workspace and marks it initialised.

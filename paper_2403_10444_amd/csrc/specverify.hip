@@ -28,9 +28,9 @@ struct Layout {
     size_t total;
     // fused path
     bool fused_ok;
-    int nu, nuf, units_per_seq;   // wave chunks per row, units of the last target row, units per sequence
-    size_t control_words;         // header, seqcnt, ratio, pstat, qstat: in ints, at offset 0, zero between calls
-    size_t off_seqcnt, off_ratio, off_pstat, off_qstat, off_spart, off_rpart;
+    int nu, nuf, wgs_per_seq;     // wave chunks per row pair / per half last row, workgroups per sequence
+    size_t control_words;         // header, ratio, pstat, qstat, spart, rpart: in ints, at offset 0, zero between calls
+    size_t off_ratio, off_pstat, off_qstat, off_spart, off_rpart;
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -45,19 +45,20 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     if (L.rows_total * (size_t)L.nchunks > 0x7fffffffull) return false;     // 1-D grids of 32-bit size
     const size_t rows_t = (size_t)B * (gamma + 1), rows_d = (size_t)B * gamma;
 
-    L.nu = (V + kWaveChunk - 1) / kWaveChunk;
-    L.nuf = (L.nu + 1) / 2;
-    L.units_per_seq = gamma * L.nu + L.nuf;
-    L.fused_ok = L.nu <= kMaxUnitsPerRow && (size_t)B * L.units_per_seq <= 0x7fffffffull;
+    // a workgroup is four waves: four neighbouring units of a row pair, or of the last target row, where a
+    // unit is two wave chunks (so a last-row workgroup covers eight)
+    L.nu = (V + kChunk - 1) / kChunk * kWaves;
+    L.nuf = (L.nu / kWaves + 1) / 2 * kWaves;
+    L.wgs_per_seq = (gamma * L.nu + L.nuf) / kWaves;
+    L.fused_ok = L.nu <= kMaxUnitsPerRow && (size_t)B * L.wgs_per_seq <= 0x7fffffffull;
     size_t off = kHdrWords * sizeof(int);
-    L.off_seqcnt = off; off = align_up(off + (size_t)B * 2 * sizeof(int), 8);
     L.off_ratio = off;  off += rows_d * sizeof(u64);
     L.off_pstat = off;  off += rows_t * 2 * L.nuf * sizeof(u64);
     L.off_qstat = off;  off += rows_d * L.nu * sizeof(u64);
+    L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
+    L.off_rpart = off;  off += rows_d * L.nu * sizeof(unsigned);
     L.control_words = off / sizeof(int);
     off = align_up(off, 256);
-    L.off_spart = off;  off = align_up(off + rows_d * L.nu * sizeof(float), 256);
-    L.off_rpart = off;  off = align_up(off + rows_d * L.nu * sizeof(float), 256);
     // the staged path's scratch follows, so that it never touches the control words
     L.off_stats = off;  off = align_up(off + L.rows_total * L.nchunks * sizeof(float2), 256);
     L.off_coef = off;   off = align_up(off + rows_t * sizeof(SeqCoef), 256);
@@ -67,15 +68,15 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     return true;
 }
 
-// One-wave workgroups of a kernel that the current device keeps resident at once (cached per kernel).
+// Workgroups of a kernel that the current device keeps resident at once (cached per kernel).
 template <typename K>
-int resident_waves(K kernel, int &cache)
+int resident_workgroups(K kernel, int &cache)
 {
     if (cache > 0) return cache;
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kWave, 0) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess) return 0;
     cache = cus * per_cu;
     return cache;
 }
@@ -119,37 +120,46 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
 {
-    static int cap_plain = 0, cap_greedy = 0;       // resident waves of the two instantiations
-    const int capacity = algo == kGreedy ? resident_waves(fused_verify_kernel<T, ALIGNED, true>, cap_greedy)
-                                         : resident_waves(fused_verify_kernel<T, ALIGNED, false>, cap_plain);
+    // resident workgroups of the four instantiations (greedy or not, rows of more than 64 units or not)
+    static int cap[4] = {0, 0, 0, 0};
+    const bool greedy = algo == kGreedy, wide = L.nu > kWave;
+    const int capacity =
+        greedy ? (wide ? resident_workgroups(fused_verify_kernel<T, ALIGNED, true, true>, cap[3])
+                       : resident_workgroups(fused_verify_kernel<T, ALIGNED, true, false>, cap[2]))
+               : (wide ? resident_workgroups(fused_verify_kernel<T, ALIGNED, false, true>, cap[1])
+                       : resident_workgroups(fused_verify_kernel<T, ALIGNED, false, false>, cap[0]));
     if (capacity < 2) return SV_ERR_HIP;
+    // a row's workgroups wait for each other and must fit on the device together, with room to spare
+    if (capacity < L.nu / kWaves * 4) return SV_ERR_UNSUPPORTED;
     FusedParams P;
     P.target = target; P.draft = draft; P.tokens = tokens; P.uniforms = uniforms;
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
-    P.nu = L.nu; P.nuf = L.nuf; P.units_per_seq = L.units_per_seq;
-    P.total_units = B * L.units_per_seq;
-    // all waves must be resident together: they wait for each other
-    P.n_waves = capacity < P.total_units ? capacity : P.total_units;
-    if (P.n_waves < P.total_units && P.n_waves < 2 * L.nu) return SV_ERR_UNSUPPORTED;   // a row's units run side by side
-    // groups of sequences so large that one position of a group fills at least one round of waves
+    P.nu = L.nu; P.nuf = L.nuf; P.wgs_per_seq = L.wgs_per_seq;
+    // groups of sequences so large that one position of a group fills the device at least once
     {
-        const int min_seqs = (P.n_waves + L.nu - 1) / L.nu;
+        const int wpr = L.nu / kWaves;
+        const int min_seqs = (capacity + wpr - 1) / wpr;
         const int groups = B / min_seqs > 1 ? B / min_seqs : 1;
         P.group_seqs = (B + groups - 1) / groups;
     }
     P.spin_limit = g_spin_limit.load();
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);
-    P.seqcnt = reinterpret_cast<int *>(ws + L.off_seqcnt);
     P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
     P.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
     P.qstat = reinterpret_cast<u64 *>(ws + L.off_qstat);
-    P.spart = reinterpret_cast<float *>(ws + L.off_spart);
-    P.rpart = reinterpret_cast<float *>(ws + L.off_rpart);
+    P.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
+    P.rpart = reinterpret_cast<unsigned *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
     P.prof = g_prof.load();
-    if (algo == kGreedy) fused_verify_kernel<T, ALIGNED, true><<<(unsigned)P.n_waves, kWave, 0, stream>>>(P);
-    else fused_verify_kernel<T, ALIGNED, false><<<(unsigned)P.n_waves, kWave, 0, stream>>>(P);
+    const unsigned grid = (unsigned)((size_t)B * L.wgs_per_seq);   // one workgroup per four units
+    if (greedy) {
+        if (wide) fused_verify_kernel<T, ALIGNED, true, true><<<grid, kThreads, 0, stream>>>(P);
+        else fused_verify_kernel<T, ALIGNED, true, false><<<grid, kThreads, 0, stream>>>(P);
+    } else {
+        if (wide) fused_verify_kernel<T, ALIGNED, false, true><<<grid, kThreads, 0, stream>>>(P);
+        else fused_verify_kernel<T, ALIGNED, false, false><<<grid, kThreads, 0, stream>>>(P);
+    }
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 

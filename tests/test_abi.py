@@ -77,9 +77,9 @@ def test_workspace_init_validates_on_the_host():
 def test_forcing_the_fused_path_refuses_vocabularies_it_cannot_take():
     try:
         sv.spec_verify_debug_config(2, -1)
-        assert _raw("spec_verify_block", V=513 * 2048) == binding.SV_ERR_UNSUPPORTED
+        assert _raw("spec_verify_block", V=128 * 8192 + 1) == binding.SV_ERR_UNSUPPORTED
         sv.spec_verify_debug_config(0, -1)
-        assert _raw("spec_verify_block", V=513 * 2048, ws_bytes=16) == binding.SV_ERR_WORKSPACE_TOO_SMALL
+        assert _raw("spec_verify_block", V=128 * 8192 + 1, ws_bytes=16) == binding.SV_ERR_WORKSPACE_TOO_SMALL
     finally:
         sv.spec_verify_debug_config(0, -1)
 
