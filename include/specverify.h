@@ -76,16 +76,19 @@ sv_status_t spec_verify_workspace_init(void *workspace, size_t workspace_bytes,
 sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_t gamma, int32_t V,
                                         void *stream);
 
-/* Testing hook, process-wide: `path` 0 = the library's default kernels, 1 = the four-launch
- * staged kernels, 2 = the single-launch fused kernel (takes V <= 128 * 8192; larger sizes
- * are then refused); `spin_limit` bounds every wait inside the fused kernel in polls
- * (negative: default).                                                                    */
+/* Testing hook, process-wide: `path` 0 = the library's choice (the fused kernel where it
+ * takes the shape, else the staged kernels), 1 = the four-launch staged kernels, 2 = the
+ * single-launch fused kernel (takes V <= 128 * 8192 and a device that keeps four rows'
+ * workgroups resident; other shapes are then refused); `spin_limit` bounds every wait
+ * inside the fused kernel in polls (negative: default).                                  */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);
 
-/* Tuning hook, process-wide: when `device_buffer` is not NULL the fused kernel stores eight
- * 64-bit timestamps (100 MHz ticks) per workgroup into it, [workgroups, 8]: start, first
- * sweep done, partials announced, wait over, second sweep done, sequence counted, accept
- * tests done, exit.  The buffer must hold 64 bytes per work unit plus 64 bytes per sequence of the largest call.  */
+/* Tuning hook, process-wide: when `device_buffer` is not NULL the fused kernel stores up to
+ * sixteen 64-bit timestamps (100 MHz ticks) per workgroup into it, [workgroups, 16], taken
+ * by the workgroup's first wave: 0 start, 1 partial normalisers announced, 2 the row's
+ * normalisers known, 3 w_i known, 4 second sweep done; for the workgroup that finishes a
+ * sequence also 5 begin, 7..12 its phases, 6 done.  The buffer must hold 128 bytes per
+ * workgroup, B * (gamma + 1) * ceil(V / 8192) workgroups, and be zeroed by the caller.    */
 void spec_verify_debug_profile(void *device_buffer);
 
 /*

@@ -65,15 +65,14 @@ struct FusedParams {
     double kd;            // log2(e) / T in double
     double k_eps;         // kd / k - 1: what rounding k to float left out (|k_eps| <= 2^-24)
     int algo;
-    int nu;               // units (wave chunks) per row pair = 4 * workgroups per row pair
-    int nuf;              // units of the last target row (two wave chunks each) = nu / 2 rounded up to even
-    int wgs_per_seq;      // workgroups per sequence = (gamma * nu + nuf) / 4
-    int group_seqs;       // sequences per group of the workgroup order
+    int nu;               // units (wave chunks) per row = 4 * workgroups per row
+    int group_seqs;       // sequences per group of the row order
     int spin_limit;
     int magic;            // workspace_magic(B, gamma, V)
     int *header;
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
-    u64 *pstat;           // [B, gamma+1, 2 * nuf]    packed (shift, sum) per wave chunk of a target row
+    u64 *rowstat;         // [B, gamma, 3]            L_p, L_q (double bits, lowest bit set), M_p (float bits << 32 | 1)
+    u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
     u64 *qstat;           // [B, gamma, nu]           same for the draft rows
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
     unsigned *rpart;      // [B, gamma, nu]           greedy only: partial sums of max(q - w p, 0), same encoding
@@ -179,101 +178,59 @@ __device__ __forceinline__ double row_normaliser(const u64 *words, int n, int li
 }
 
 struct Unit {
-    int b, i, c;          // sequence, position, wave chunk (last row: unit index, chunks 2c and 2c+1)
+    int b, i, c;          // sequence, position (gamma: the last target row, which has no draft row), wave chunk
     bool last_row;
 };
 
-// Workgroup order: groups of `group_seqs` sequences; inside a group first the row pairs
-// position-major (position, sequence, chunk), then the last target rows (sequence, chunk pair).
-// Wave w of workgroup g takes unit 4 * (g's chunk) + w.
+// Workgroup order: groups of `group_seqs` sequences; inside a group first the last target rows
+// (which have no draft row), then the row pairs position-major (position, sequence, chunk).
+// Workgroup g takes four neighbouring units of row g / (nu / 4).
 __device__ __forceinline__ Unit decode_unit(const FusedParams &P, int g, int wave)
 {
     Unit U;
-    const int wpr = P.nu / kWaves, wpl = P.nuf / kWaves;        // workgroups per row pair / per last row
-    const int per_group = P.group_seqs * P.wgs_per_seq;
-    const int grp = g / per_group;
-    int r = g - grp * per_group;
+    const int wpr = P.nu / kWaves;                          // workgroups per row
+    const int R = g / wpr;
+    U.c = (g - R * wpr) * kWaves + wave;
+    const int rows_per_group = (P.gamma + 1) * P.group_seqs;
+    const int grp = R / rows_per_group;
+    const int r = R - grp * rows_per_group;
     const int b0 = grp * P.group_seqs;
     const int nb = P.B - b0 < P.group_seqs ? P.B - b0 : P.group_seqs;   // sequences in this group
-    const int pairs = P.gamma * nb * wpr;
-    U.last_row = r >= pairs;
-    if (!U.last_row) {
-        U.i = r / (nb * wpr);
-        r -= U.i * nb * wpr;
-        const int bl = r / wpr;
-        U.b = b0 + bl;
-        U.c = (r - bl * wpr) * kWaves + wave;
-    } else {
-        r -= pairs;
-        const int bl = r / wpl;
-        U.i = P.gamma;
-        U.b = b0 + bl;
-        U.c = (r - bl * wpl) * kWaves + wave;
-    }
+    const int slot = r / nb;                                // 0: last target rows; 1 + i: position i
+    U.b = b0 + (r - slot * nb);
+    U.last_row = slot == 0;
+    U.i = U.last_row ? P.gamma : slot - 1;
     return U;
 }
 
-// The logits of one lane (both rows), as loaded: raw 16-byte vectors on the aligned path.
+// The logits a lane holds of one row, as loaded: raw 16-byte vectors on the aligned path.
 template <typename T, bool ALIGNED> struct RawSlice;
 template <typename T> struct RawSlice<T, true> {
     static constexpr int kNV = kLaneLogits / ElemTraits<T>::kVec;
-    uint4 a[kNV], b[kNV];
+    uint4 v[kNV];
 };
 template <typename T> struct RawSlice<T, false> { };      // the element-wise path loads when it unpacks
 
-template <typename T>
-struct Stream {
-    const T *rowA, *rowB;
-    int firstA, firstB;       // element index of this lane's first vector in each row
-};
-
-// Stream A: target row i, wave chunk c (last row: chunk 2c); stream B: draft row i, chunk c
-// (last row: target row gamma, chunk 2c+1).  Vector v of a lane starts at first + v * 64 * kVec,
-// so one load instruction of the wave covers 1 KB of contiguous memory.
-template <typename T>
-__device__ __forceinline__ Stream<T> unit_streams(const FusedParams &P, const Unit &U)
-{
-    constexpr int kVec = ElemTraits<T>::kVec;
-    const int lane = threadIdx.x & 63;
-    const T *target = static_cast<const T *>(P.target);
-    const T *draft = static_cast<const T *>(P.draft);
-    Stream<T> S;
-    S.rowA = target + ((size_t)U.b * (P.gamma + 1) + U.i) * P.V;
-    S.rowB = U.last_row ? S.rowA : draft + ((size_t)U.b * P.gamma + U.i) * P.V;
-    S.firstA = (U.last_row ? 2 * U.c : U.c) * kUnitLogits + lane * kVec;
-    S.firstB = (U.last_row ? 2 * U.c + 1 : U.c) * kUnitLogits + lane * kVec;
-    return S;
-}
-
+// Vector v of a lane starts at element first + v * 64 * kVec of the row, so one load instruction of
+// the wave covers 1 KB of contiguous memory.
 template <typename T, bool ALIGNED>
-__device__ __forceinline__ void issue_loads(const Stream<T> &S, int V, RawSlice<T, ALIGNED> &raw)
+__device__ __forceinline__ void issue_loads(const T *row, int first, int V, RawSlice<T, ALIGNED> &raw)
 {
     if constexpr (ALIGNED) {
         constexpr int kVec = ElemTraits<T>::kVec;
-        constexpr int kNV = kLaneLogits / kVec;
 #pragma unroll
-        for (int v = 0; v < kNV; ++v) {
-            const int ia = S.firstA + v * kWave * kVec, ib = S.firstB + v * kWave * kVec;
+        for (int v = 0; v < RawSlice<T, true>::kNV; ++v) {
+            const int idx = first + v * kWave * kVec;
             // vectors beyond the row are recognised again when the slice is unpacked; load something valid
-            raw.a[v] = *reinterpret_cast<const uint4 *>(S.rowA + (ia < V ? ia : 0));
-            raw.b[v] = *reinterpret_cast<const uint4 *>(S.rowB + (ib < V ? ib : 0));
+            raw.v[v] = *reinterpret_cast<const uint4 *>(row + (idx < V ? idx : 0));
         }
-        // the loads must be issued HERE (they are the prefetch that overlaps the work that follows);
-        // without this the compiler is free to sink them to their first use
-        asm volatile("" ::: "memory");
     }
 }
 
 template <typename T>
-__device__ __forceinline__ void unpack_vec(const uint4 &v, bool valid, float *out)
+__device__ __forceinline__ void unpack_vec(const uint4 &v, float *out)
 {
-    constexpr int kVec = ElemTraits<T>::kVec;
-    if (!valid) {
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) out[e] = -INFINITY;
-        return;
-    }
-    if constexpr (kVec == 4) {
+    if constexpr (ElemTraits<T>::kVec == 4) {
         out[0] = __uint_as_float(v.x); out[1] = __uint_as_float(v.y);
         out[2] = __uint_as_float(v.z); out[3] = __uint_as_float(v.w);
     } else {
@@ -283,37 +240,27 @@ __device__ __forceinline__ void unpack_vec(const uint4 &v, bool valid, float *ou
 }
 
 template <typename T, bool ALIGNED>
-__device__ __forceinline__ void unpack_slice(const Stream<T> &S, int V, const RawSlice<T, ALIGNED> &raw,
-                                             float (&xa)[kLaneLogits], float (&xb)[kLaneLogits])
+__device__ __forceinline__ void unpack_slice(const T *row, int first, int V, const RawSlice<T, ALIGNED> &raw,
+                                             float (&x)[kLaneLogits])
 {
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = kLaneLogits / kVec;
     if constexpr (ALIGNED) {
 #pragma unroll
-        for (int v = 0; v < kNV; ++v) {
-            unpack_vec<T>(raw.a[v], true, xa + v * kVec);
-            unpack_vec<T>(raw.b[v], true, xb + v * kVec);
-        }
+        for (int v = 0; v < kNV; ++v) unpack_vec<T>(raw.v[v], x + v * kVec);
         // only a row's last units reach beyond the row (wave-uniform test): blank what lies beyond
-        const int lastA = __builtin_amdgcn_readfirstlane(S.firstA) + kUnitLogits;
-        const int lastB = __builtin_amdgcn_readfirstlane(S.firstB) + kUnitLogits;
-        if (lastA > V || lastB > V) {
+        if (__builtin_amdgcn_readfirstlane(first) + kUnitLogits > V) {
 #pragma unroll
             for (int v = 0; v < kNV; ++v) {
-                const bool out_a = S.firstA + v * kWave * kVec >= V, out_b = S.firstB + v * kWave * kVec >= V;
+                const bool out = first + v * kWave * kVec >= V;
 #pragma unroll
-                for (int e = 0; e < kVec; ++e) {
-                    if (out_a) xa[v * kVec + e] = -INFINITY;
-                    if (out_b) xb[v * kVec + e] = -INFINITY;
-                }
+                for (int e = 0; e < kVec; ++e)
+                    if (out) x[v * kVec + e] = -INFINITY;
             }
         }
     } else {
 #pragma unroll
-        for (int v = 0; v < kNV; ++v) {
-            load_vec<T, false>(S.rowA, V, S.firstA + v * kWave * kVec, xa + v * kVec);
-            load_vec<T, false>(S.rowB, V, S.firstB + v * kWave * kVec, xb + v * kVec);
-        }
+        for (int v = 0; v < kNV; ++v) load_vec<T, false>(row, V, first + v * kWave * kVec, x + v * kVec);
     }
 }
 
@@ -346,90 +293,87 @@ __device__ __forceinline__ u64 wave_stat(float mk, float s)
 }
 
 // ------------------------------------------------------------------ whole sequences
-// Inclusive scan over the 64 lanes; `total` is the wave's sum.  exclusive = inclusive of the lane before.
-__device__ __forceinline__ float wave_inclusive_scan(float v, float &exclusive, float &total)
+// Inclusive scans over the 64 lanes through DPP: four shifts inside each row of 16 lanes (lanes
+// without a source add 0), then the two row broadcasts.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_shift(int v)
 {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const float up = __shfl_up(v, off, kWave);
-        if (lane >= off) v += up;
-    }
-    const float prev = __shfl_up(v, 1, kWave);
-    exclusive = lane ? prev : 0.f;
-    total = __shfl(v, kWave - 1, kWave);
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, true);
+}
+__device__ __forceinline__ float wave_scan(float v)
+{
+    v += __int_as_float(dpp_shift<0x111>(__float_as_int(v)));          // row_shr:1
+    v += __int_as_float(dpp_shift<0x112>(__float_as_int(v)));          // row_shr:2
+    v += __int_as_float(dpp_shift<0x114>(__float_as_int(v)));          // row_shr:4
+    v += __int_as_float(dpp_shift<0x118>(__float_as_int(v)));          // row_shr:8
+    v += __int_as_float(dpp_shift<0x142, 0xa>(__float_as_int(v)));     // row_bcast15 into rows 1 and 3
+    v += __int_as_float(dpp_shift<0x143, 0xc>(__float_as_int(v)));     // row_bcast31 into rows 2 and 3
     return v;
 }
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ double dpp_shift_double(double v)
+{
+    const long long bits = __double_as_longlong(v);
+    const unsigned lo = (unsigned)dpp_shift<CTRL, ROW_MASK>((int)(unsigned)(bits & 0xffffffffll));
+    const unsigned hi = (unsigned)dpp_shift<CTRL, ROW_MASK>((int)(unsigned)((unsigned long long)bits >> 32));
+    return __longlong_as_double((long long)(((u64)hi << 32) | lo));
+}
+__device__ __forceinline__ double wave_scan(double v)
+{
+    v += dpp_shift_double<0x111>(v);
+    v += dpp_shift_double<0x112>(v);
+    v += dpp_shift_double<0x114>(v);
+    v += dpp_shift_double<0x118>(v);
+    v += dpp_shift_double<0x142, 0xa>(v);
+    v += dpp_shift_double<0x143, 0xc>(v);
+    return v;
+}
+__device__ __forceinline__ double read_lane_double(double v, int lane)
+{
+    return __longlong_as_double((long long)read_lane_u64((u64)__double_as_longlong(v), lane));
+}
 
-// Accept tests and inverse-CDF draw of one sequence (one wave), once all of its residual partial
-// sums have been published.
+// Accept tests and inverse-CDF draw of one sequence (one wave).  What does not need the residual
+// sums (normalisers, ratios, w) is done first, while the sequence's last units are still at work.
 template <typename T, bool ALIGNED, bool GREEDY>
-__device__ void finalize_sequence(const FusedParams &P, int b)
+__device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = kLaneLogits / kVec;
+    constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
     const int lane = threadIdx.x & 63;
     const int gamma = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
     const T *target = static_cast<const T *>(P.target);
     const T *draft = static_cast<const T *>(P.draft);
     const size_t base = (size_t)b * (gamma + 1);
+    const int e_lane = lane < nu ? lane : nu - 1;
     bool gave_up = false;
+#define FSTAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
 
-    // Row results live in lane j's registers (gamma <= 64): L_p, L_q, M_p, S, rejected mass, log2 r_{j+1}.
-    // S_j = sum of the row's partial sums: lanes take entries lane, lane+64, ..., then a wave sum.
-    double my_Lp = 0.0, my_Lq = 0.0, my_S = 0.0, my_R = 0.0, my_lr = 0.0;
+    // ---- row results live in lane j's registers (gamma <= 64): log2 r_{j+1}, L_p, L_q and M_p as the
+    // row's first unit published them
+    double my_Lp = 0.0, my_Lq = 0.0, my_lr = 0.0;
     float my_Mp = 0.f;
-    if (lane < gamma) my_lr = unpack_ratio(wait_word(P.ratio + (size_t)b * gamma + lane, P.spin_limit, gave_up));
-    constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
-    for (int j0 = 0; j0 < gamma; j0 += kBatch) {
-        unsigned sw[kBatch], rw[kBatch];
-        u64 pw[kBatch], qw[kBatch];
-#pragma unroll
-        for (int jj = 0; jj < kBatch; ++jj) {
-            sw[jj] = rw[jj] = 0; pw[jj] = qw[jj] = 0;
-            if (j0 + jj < gamma && lane < nu) {
-                const size_t drow = (size_t)b * gamma + j0 + jj;
-                sw[jj] = ld_u32(P.spart + drow * nu + lane);
-                if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + drow * nu + lane);
-                pw[jj] = ld_u64(P.pstat + (base + j0 + jj) * 2 * P.nuf + lane);
-                qw[jj] = ld_u64(P.qstat + drow * nu + lane);
-            }
-        }
-#pragma unroll
-        for (int jj = 0; jj < kBatch; ++jj) {
-            const int j = j0 + jj;
-            if (j >= gamma) break;
-            const size_t drow = (size_t)b * gamma + j;
-            double acc = 0.0, rej = 0.0;
-            {
-                const unsigned w = wait_word32(P.spart + drow * nu + lane, sw[jj], lane < nu, P.spin_limit, gave_up);
-                if (lane < nu) acc += (double)unpack_partial(w);
-                if constexpr (GREEDY) {
-                    const unsigned r = wait_word32(P.rpart + drow * nu + lane, rw[jj], lane < nu, P.spin_limit, gave_up);
-                    if (lane < nu) rej += (double)unpack_partial(r);
-                }
-            }
-            for (int e = lane + kWave; e < nu; e += kWave) {
-                acc += (double)unpack_partial(wait_word32(P.spart + drow * nu + e, P.spin_limit, gave_up));
-                if constexpr (GREEDY) rej += (double)unpack_partial(wait_word32(P.rpart + drow * nu + e, P.spin_limit, gave_up));
-            }
-            acc = wave_sum_double(acc);
-            if constexpr (GREEDY) rej = wave_sum_double(rej);
-            float Mp, Mq;
-            const double Lp = row_normaliser<true>(P.pstat + (base + j) * 2 * P.nuf, nu, P.spin_limit, gave_up, Mp, pw[jj]);
-            const double Lq = row_normaliser<true>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw[jj]);
-            if (lane == j) { my_Lp = Lp; my_Lq = Lq; my_Mp = Mp; my_S = acc; my_R = rej; }
-        }
+    {
+        const size_t drow = (size_t)b * gamma + (lane < gamma ? lane : gamma - 1);
+        u64 w0 = ld_u64(P.ratio + drow), w1 = ld_u64(P.rowstat + drow * 3), w2 = ld_u64(P.rowstat + drow * 3 + 1),
+            w3 = ld_u64(P.rowstat + drow * 3 + 2);
+        w0 = wait_word(P.ratio + drow, w0, lane < gamma, P.spin_limit, gave_up);
+        w1 = wait_word(P.rowstat + drow * 3, w1, lane < gamma, P.spin_limit, gave_up);
+        w2 = wait_word(P.rowstat + drow * 3 + 1, w2, lane < gamma, P.spin_limit, gave_up);
+        w3 = wait_word(P.rowstat + drow * 3 + 2, w3, lane < gamma, P.spin_limit, gave_up);
+        my_lr = unpack_ratio(w0); my_Lp = unpack_ratio(w1); my_Lq = unpack_ratio(w2);
+        my_Mp = __uint_as_float((unsigned)(w3 >> 32));
     }
-
+    FSTAMP(7);
     // log2 w_j for lane j (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4 drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, lw_last = 0.0;
     {
         double cur = 0.0;
         for (int j = 0; j < gamma; ++j) {
             if (lane == j) my_lw = cur;
-            cur += __shfl(my_lr, j, kWave);
+            cur += read_lane_double(my_lr, j);
             if (!GREEDY && cur > 0.0) cur = 0.0;
         }
         lw_last = cur;
@@ -437,12 +381,49 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
         if (GREEDY) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
     }
 
-    // accept tests eta_j < h_j: lane l tests position j = l + 1, whose row values sit in lane j
+    FSTAMP(8);
+    // ---- S_j (and, greedy, the rejected mass) = sum of row j's partial sums, into lane j.  kept[jj]
+    // holds this lane's partial sum of row jj when gamma <= kBatch (used again for the draw).
+    float my_S = 0.f, my_R = 0.f, kept[kBatch];
+    for (int j0 = 0; j0 < gamma; j0 += kBatch) {
+        unsigned sw[kBatch], rw[kBatch];
+#pragma unroll
+        for (int jj = 0; jj < kBatch; ++jj) {
+            const int j = j0 + jj < gamma ? j0 + jj : gamma - 1;
+            sw[jj] = ld_u32(P.spart + ((size_t)b * gamma + j) * nu + e_lane);
+            if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + ((size_t)b * gamma + j) * nu + e_lane);
+        }
+#pragma unroll
+        for (int jj = 0; jj < kBatch; ++jj) {
+            const int j = j0 + jj;
+            kept[jj] = 0.f;
+            if (j >= gamma) continue;
+            const size_t drow = (size_t)b * gamma + j;
+            float acc = 0.f, rej = 0.f;
+            const unsigned w = wait_word32(P.spart + drow * nu + e_lane, sw[jj], lane < nu, P.spin_limit, gave_up);
+            if (lane < nu) acc = unpack_partial(w);
+            kept[jj] = acc;
+            if constexpr (GREEDY) {
+                const unsigned r = wait_word32(P.rpart + drow * nu + e_lane, rw[jj], lane < nu, P.spin_limit, gave_up);
+                if (lane < nu) rej = unpack_partial(r);
+            }
+            for (int e = lane + kWave; e < nu; e += kWave) {
+                acc += unpack_partial(wait_word32(P.spart + drow * nu + e, P.spin_limit, gave_up));
+                if constexpr (GREEDY) rej += unpack_partial(wait_word32(P.rpart + drow * nu + e, P.spin_limit, gave_up));
+            }
+            acc = wave_sum(acc);
+            if constexpr (GREEDY) rej = wave_sum(rej);
+            if (lane == j) { my_S = acc; my_R = rej; }
+        }
+    }
+
+    FSTAMP(9);
+    // ---- accept tests eta_j < h_j: lane l tests position j = l + 1, whose row values sit in lane j
     const float *eta = P.uniforms + (size_t)b * (gamma + 1);
     const int j = lane + 1;
     const double lw_next = __shfl_down(my_lw, 1, kWave);
     const double lw_j = j < gamma ? lw_next : lw_last;
-    const double S_row = __shfl_down(my_S, 1, kWave), R_row = __shfl_down(my_R, 1, kWave);
+    const double S_row = (double)__shfl_down(my_S, 1, kWave), R_row = (double)__shfl_down(my_R, 1, kWave);
     bool pass = false;
     if (j <= gamma) {
         const double w = exp2(lw_j);
@@ -460,7 +441,7 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
     }
     if (lane == 0 && P.debug_out) {
         float *d = P.debug_out + base * 3;
-        d[0] = 1.f; d[1] = (float)my_S; d[2] = 1.f;
+        d[0] = 1.f; d[1] = my_S; d[2] = 1.f;
     }
     const u64 passed = __ballot(pass);
     int tau;
@@ -468,56 +449,56 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
     else tau = passed ? 64 - __clzll((long long)passed) : 0;                               // last passing sub-block
     if (lane == 0) P.accept_len[b] = tau;
 
+    FSTAMP(10);
     // ---- inverse-CDF draw of Y: first the wave chunk of row tau that holds t = u * total ...
     const float u = eta[gamma];
     int mode = tau < gamma ? 0 : 1;                     // 0: residual weights; 1: p_tau itself
     float Mrow = 0.f;
     RowCoef rc = {};
+    float part0 = 0.f;                                  // this lane's entry `lane` of the row's partial sums
+    const u64 *st = P.pstat + (base + tau) * nu;
+    const unsigned *sp = P.spart + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * nu;
     if (tau < gamma) {
         Mrow = __shfl(my_Mp, tau, kWave);
         rc = make_row_coef(__shfl(my_Lp, tau, kWave) - __shfl(my_lw, tau, kWave), __shfl(my_Lq, tau, kWave));
+        if (gamma <= kBatch) {
+#pragma unroll
+            for (int jj = 0; jj < kBatch; ++jj)
+                if (jj == tau) part0 = kept[jj];
+        } else if (lane < nu) part0 = unpack_partial(ld_u32(sp + lane));
     } else {
         // everything accepted: Y comes from p_gamma; its words are polled until they are all there
-        row_normaliser<true>(P.pstat + (base + gamma) * 2 * P.nuf, 2 * P.nuf, P.spin_limit, gave_up, Mrow, 0);
+        row_normaliser<true>(st, nu, P.spin_limit, gave_up, Mrow, 0);
     }
-    const u64 *st = P.pstat + (base + tau) * 2 * P.nuf;
-    const unsigned *sp = P.spart + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * nu;
     int slot = -1, last_nonzero = 0;
     double t_in = 0.0;
     for (int attempt = 0; attempt < 2 && slot < 0; ++attempt) {
-        const int n = tau < gamma ? nu : 2 * P.nuf;
         double total = 0.0, t = 0.0;
         for (int pass_no = 0; pass_no < 2; ++pass_no) {           // pass 0: total; pass 1: locate t = u * total
             double carry = 0.0;
-            for (int e0 = 0; e0 < n; e0 += kWave) {
+            for (int e0 = 0; e0 < nu; e0 += kWave) {
                 const int e = e0 + lane;
                 double part = 0.0;
-                if (e < n) {
-                    if (mode == 0) part = (double)unpack_partial(ld_u32(sp + e));
+                if (e < nu) {
+                    if (mode == 0) part = e0 == 0 ? (double)part0 : (double)unpack_partial(ld_u32(sp + e));
                     else {
                         const u64 v = ld_u64(st + e);
                         const float sh = stat_shift(v);
                         part = sh > -INFINITY ? (double)(stat_sum(v) * fast_exp2(sh - Mrow)) : 0.0;
                     }
                 }
-                double inc = part;
-#pragma unroll
-                for (int off = 1; off < kWave; off <<= 1) {
-                    const double up = __shfl_up(inc, off, kWave);
-                    if (lane >= off) inc += up;
-                }
-                inc += carry;
+                const double inc = wave_scan(part) + carry;
                 if (pass_no == 1 && slot < 0) {
-                    const u64 hit = __ballot(e < n && inc > t);
-                    const u64 nz = __ballot(e < n && part > 0.0);
+                    const u64 hit = __ballot(e < nu && inc > t);
+                    const u64 nz = __ballot(e < nu && part > 0.0);
                     if (nz) last_nonzero = e0 + 63 - __clzll((long long)nz);
                     if (hit) {
                         const int first = __ffsll((long long)hit) - 1;
                         slot = e0 + first;
-                        t_in = t - __shfl(inc - part, first, kWave);
+                        t_in = t - read_lane_double(inc - part, first);
                     }
                 }
-                carry = __shfl(inc, kWave - 1, kWave);
+                carry = read_lane_double(inc, kWave - 1);
             }
             if (pass_no == 0) { total = carry; t = (double)u * total; }
         }
@@ -528,28 +509,33 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
     }
     if (slot < 0) { slot = 0; t_in = INFINITY; }
 
+    FSTAMP(11);
     // ---- ... then the token inside that chunk: weights recomputed from the logits, walked in
     // vocabulary order (vector, lane, element)
     {
         const T *prow = target + (base + tau) * V;
         const T *qrow = draft + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * V;
         const u64 sv = ld_u64(st + slot);
+        const int first = slot * kUnitLogits + lane * kVec;
+        float xp[kNV][kVec], xq[kNV][kVec];
+#pragma unroll
+        for (int v = 0; v < kNV; ++v) {
+            load_vec<T, ALIGNED>(prow, V, first + v * kWave * kVec, xp[v]);
+            if (mode == 0) load_vec<T, ALIGNED>(qrow, V, first + v * kWave * kVec, xq[v]);
+        }
         const float shift = stat_shift(sv), scale = fast_exp2(shift - Mrow);
         float t = mode == 0 ? (float)(t_in / (double)rc.cq) : (float)t_in;
-        const int first = slot * kUnitLogits + lane * kVec;
         int y = -1, last_positive = -1;
 #pragma unroll
         for (int v = 0; v < kNV; ++v) {
             const int idx = first + v * kWave * kVec;
-            float xp[kVec], xq[kVec], wgt[kVec];
-            load_vec<T, ALIGNED>(prow, V, idx, xp);
+            float wgt[kVec];
             if (mode == 0) {
-                load_vec<T, ALIGNED>(qrow, V, idx, xq);
 #pragma unroll
-                for (int e = 0; e < kVec; ++e) wgt[e] = fmaxf(residual_term(xp[e], xq[e], k, rc), 0.f);
+                for (int e = 0; e < kVec; ++e) wgt[e] = fmaxf(residual_term(xp[v][e], xq[v][e], k, rc), 0.f);
             } else {
 #pragma unroll
-                for (int e = 0; e < kVec; ++e) wgt[e] = fast_exp2(__builtin_fmaf(xp[e], k, -shift)) * scale;
+                for (int e = 0; e < kVec; ++e) wgt[e] = fast_exp2(__builtin_fmaf(xp[v][e], k, -shift)) * scale;
             }
             float mine = 0.f;
 #pragma unroll
@@ -557,14 +543,14 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
                 mine += wgt[e];
                 if (wgt[e] > 0.f) last_positive = idx + e;
             }
-            float exc, total;
-            const float inc = wave_inclusive_scan(mine, exc, total);
+            const float inc = wave_scan(mine);
+            const float total = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(inc), kWave - 1));
             const u64 hit = __ballot(inc > t);
             if (y < 0 && hit) {
                 const int first_lane = __ffsll((long long)hit) - 1;
                 int cand = -1;
                 if (lane == first_lane) {
-                    float run = exc;
+                    float run = inc - mine;
                     int lastpos = 0;
 #pragma unroll
                     for (int e = 0; e < kVec; ++e) {
@@ -575,7 +561,7 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
                     if (cand < 0) cand = lastpos;     // scan and walk rounded differently: last positive weight
                     cand += idx;
                 }
-                y = __shfl(cand, first_lane, kWave);
+                y = __builtin_amdgcn_readlane(cand, first_lane);
             }
             t -= total;
         }
@@ -588,28 +574,30 @@ __device__ void finalize_sequence(const FusedParams &P, int b)
         if (lane == 0) P.next_token[b] = y;
     }
 
+    FSTAMP(12);
     // ---- leave the sequence's words zero for the next call.  Every reader of the row-pair words has
     // published its partial sum by now; the words of the last target row must all be written first.
-    for (int e = lane; e < 2 * P.nuf; e += kWave) wait_word(P.pstat + (base + gamma) * 2 * P.nuf + e, P.spin_limit, gave_up);
-    if (gave_up && lane == 0) atomicOr(P.header + kHdrError, 1);
-    for (int e = lane; e < (gamma + 1) * 2 * P.nuf; e += kWave) st_u64(P.pstat + base * 2 * P.nuf + e, 0);
+    for (int e = lane; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
+    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
+    for (int e = lane; e < (gamma + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
     for (int e = lane; e < gamma * nu; e += kWave) {
         st_u64(P.qstat + (size_t)b * gamma * nu + e, 0);
         st_u32(P.spart + (size_t)b * gamma * nu + e, 0);
         if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * gamma * nu + e, 0);
     }
     for (int e = lane; e < gamma; e += kWave) st_u64(P.ratio + (size_t)b * gamma + e, 0);
+    for (int e = lane; e < 3 * gamma; e += kWave) st_u64(P.rowstat + (size_t)b * gamma * 3 + e, 0);
 }
 
 // ------------------------------------------------------------------ the kernel
 template <typename T, bool ALIGNED, bool GREEDY, bool WIDE>
-__global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParams P)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ElemTraits<T>::kVec == 8 ? 5 : 4)))
+void fused_verify_kernel(const FusedParams P)
 {
+    constexpr int kVec = ElemTraits<T>::kVec;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int gamma = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
-    const T *target = static_cast<const T *>(P.target);
-    const T *draft = static_cast<const T *>(P.draft);
 
     if (__builtin_nontemporal_load(P.header + kHdrMagic) != P.magic) {
         // the workspace was not initialised for this shape: report it through the outputs and leave
@@ -617,94 +605,102 @@ __global__ __launch_bounds__(kThreads) void fused_verify_kernel(const FusedParam
             for (int b = threadIdx.x; b < P.B; b += kThreads) { P.accept_len[b] = -1; P.next_token[b] = -1; }
         return;
     }
-#define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
+    const Unit U = decode_unit(P, blockIdx.x, wave);
     SV_STAMP(0);
 
-    const Unit U = decode_unit(P, blockIdx.x, wave);
-    const Stream<T> S = unit_streams<T>(P, U);
-    RawSlice<T, ALIGNED> raw;
-    issue_loads<T, ALIGNED>(S, V, raw);
+    // stream A: the unit's chunk of target row i; stream B: the same chunk of draft row i (none for the last row)
     const size_t trow = (size_t)U.b * (gamma + 1) + U.i, drow = (size_t)U.b * gamma + (U.last_row ? 0 : U.i);
+    const T *rowA = static_cast<const T *>(P.target) + trow * V;
+    const T *rowB = static_cast<const T *>(P.draft) + drow * V;
+    const int first = U.c * kUnitLogits + lane * kVec;
+    RawSlice<T, ALIGNED> rawA, rawB;
+    issue_loads<T, ALIGNED>(rowA, first, V, rawA);
+    if (!U.last_row) issue_loads<T, ALIGNED>(rowB, first, V, rawB);
     // draft token X_{i+1} and its two logits: a row's first unit publishes the row's ratio from them
     double ya = 0.0, yb = 0.0;
     if (!U.last_row && U.c == 0) {
-        const int tok = P.tokens[(size_t)U.b * gamma + U.i];
-        ya = logit_as_double(S.rowA + tok);
-        yb = logit_as_double(S.rowB + tok);
+        const int tok = P.tokens[drow];
+        ya = logit_as_double(rowA + tok);
+        yb = logit_as_double(rowB + tok);
     }
 
-    // ---- first sweep: exponentials stay in xa / xb; the unit's two words go out
+    // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     float xa[kLaneLogits], xb[kLaneLogits];
-    unpack_slice<T, ALIGNED>(S, V, raw, xa, xb);
     float shiftA, mkA, sA, shiftB, mkB, sB;
+    unpack_slice<T, ALIGNED>(rowA, first, V, rawA, xa);
     exp_sum(xa, k, shiftA, mkA, sA);
+    {
+        const u64 stA = wave_stat(mkA, sA);
+        if (lane == 0) st_u64(P.pstat + trow * nu + U.c, stA);
+    }
+    if (U.last_row) return;          // the last target row has no draft row and no residual
+    unpack_slice<T, ALIGNED>(rowB, first, V, rawB, xb);
     exp_sum(xb, k, shiftB, mkB, sB);
     {
-        const u64 stA = wave_stat(mkA, sA), stB = wave_stat(mkB, sB);
-        if (lane == 0) {
-            st_u64(P.pstat + trow * 2 * P.nuf + (U.last_row ? 2 * U.c : U.c), stA);
-            if (U.last_row) st_u64(P.pstat + trow * 2 * P.nuf + 2 * U.c + 1, stB);
-            else st_u64(P.qstat + drow * nu + U.c, stB);
-        }
+        const u64 stB = wave_stat(mkB, sB);
+        if (lane == 0) st_u64(P.qstat + drow * nu + U.c, stB);
     }
     SV_STAMP(1);
 
-    if (!U.last_row) {
-        // ---- the words of this row's units give L_p and L_q; the ratios of the earlier rows give w_i
-        bool gave_up = false;
-        const int e0 = lane < nu ? lane : nu - 1;
-        const u64 pw = ld_u64(P.pstat + trow * 2 * P.nuf + e0);
-        const u64 qw = ld_u64(P.qstat + drow * nu + e0);
-        u64 rt = 1;
-        if (P.algo != kToken && lane < U.i) rt = ld_u64(P.ratio + (size_t)U.b * gamma + lane);
-        float Mp, Mq;
-        const double Lp = row_normaliser<WIDE>(P.pstat + trow * 2 * P.nuf, nu, P.spin_limit, gave_up, Mp, pw);
-        const double Lq = row_normaliser<WIDE>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
-        SV_STAMP(2);
-        if (lane == 0 && U.c == 0) {
-            // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for the later rows.  The sweeps
-            // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that
-            // moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
-            // row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
-            const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
-            const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-            st_u64(P.ratio + drow, pack_ratio(lp - lq));
-        }
-        // w_i from the ratios of the earlier rows (Alg. 2: w_i = min(w_{i-1} r_i, 1))
-        double log2w = 0.0;
-        if (P.algo != kToken) {
-            rt = wait_word(P.ratio + (size_t)U.b * gamma + (lane < gamma ? lane : gamma - 1), rt, lane < U.i, P.spin_limit, gave_up);
-            for (int j = 0; j < U.i; ++j) {
-                log2w += unpack_ratio(read_lane_u64(rt, j));
-                if (!GREEDY && log2w > 0.0) log2w = 0.0;
-            }
-            if (GREEDY) log2w = fmin(log2w, 100.0);             // keeps w p finite in float
-        }
-        if (gave_up && lane == 0) atomicOr(P.header + kHdrError, 1);
-        SV_STAMP(3);
-
-        // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq
-        const float cp = fast_exp2((float)((double)shiftA - (Lp - log2w)));
-        const float cq = fast_exp2((float)((double)shiftB - Lq));
-        float acc = 0.f, rej = 0.f;
-#pragma unroll
-        for (int j = 0; j < kLaneLogits; ++j) {
-            const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
-            if constexpr (GREEDY) { acc += fmaxf(d, 0.f); rej += fmaxf(-d, 0.f); }
-            else acc += __builtin_amdgcn_fmed3f(d, 0.f, 1.f);   // w p <= 1, so clamping to [0, 1] is max(d, 0); folds into the fma
-        }
-        acc = wave_sum(acc);
-        if constexpr (GREEDY) rej = wave_sum(rej);
-        if (lane == 0) {
-            if constexpr (GREEDY) st_u32(P.rpart + drow * nu + U.c, pack_partial(rej));
-            st_u32(P.spart + drow * nu + U.c, pack_partial(acc));
-        }
-        SV_STAMP(4);
-        return;
+    // ---- the words of this row's units give L_p and L_q; the ratios of the earlier rows give w_i
+    bool gave_up = false;
+    const int e0 = lane < nu ? lane : nu - 1;
+    const u64 pw = ld_u64(P.pstat + trow * nu + e0);
+    const u64 qw = ld_u64(P.qstat + drow * nu + e0);
+    u64 rt = 1;
+    if (P.algo != kToken && lane < U.i) rt = ld_u64(P.ratio + (size_t)U.b * gamma + lane);
+    float Mp, Mq;
+    const double Lp = row_normaliser<WIDE>(P.pstat + trow * nu, nu, P.spin_limit, gave_up, Mp, pw);
+    const double Lq = row_normaliser<WIDE>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
+    SV_STAMP(2);
+    if (lane == 0 && U.c == 0) {
+        // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for the later rows.  The sweeps
+        // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that
+        // moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
+        // row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
+        const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
+        const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
+        st_u64(P.ratio + drow, pack_ratio(lp - lq));
+        // the row's normalisers, for whoever finishes the sequence
+        st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
+        st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
+        st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
     }
+    // w_i from the ratios of the earlier rows (Alg. 2: w_i = min(w_{i-1} r_i, 1))
+    double log2w = 0.0;
+    if (P.algo != kToken) {
+        rt = wait_word(P.ratio + (size_t)U.b * gamma + (lane < gamma ? lane : gamma - 1), rt, lane < U.i, P.spin_limit, gave_up);
+        for (int j = 0; j < U.i; ++j) {
+            log2w += unpack_ratio(read_lane_u64(rt, j));
+            if (!GREEDY && log2w > 0.0) log2w = 0.0;
+        }
+        if (GREEDY) log2w = fmin(log2w, 100.0);             // keeps w p finite in float
+    }
+    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
+    SV_STAMP(3);
 
-    // ---- the first unit of a sequence's last target row finishes the sequence
-    if (U.c == 0) {
+    // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq
+    const float cp = fast_exp2((float)((double)shiftA - (Lp - log2w)));
+    const float cq = fast_exp2((float)((double)shiftB - Lq));
+    float acc = 0.f, rej = 0.f;
+#pragma unroll
+    for (int j = 0; j < kLaneLogits; ++j) {
+        const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
+        if constexpr (GREEDY) { acc += fmaxf(d, 0.f); rej += fmaxf(-d, 0.f); }
+        else acc += __builtin_amdgcn_fmed3f(d, 0.f, 1.f);   // w p <= 1, so clamping to [0, 1] is max(d, 0); folds into the fma
+    }
+    acc = wave_sum(acc);
+    if constexpr (GREEDY) rej = wave_sum(rej);
+    if (lane == 0) {
+        if constexpr (GREEDY) st_u32(P.rpart + drow * nu + U.c, pack_partial(rej));
+        st_u32(P.spart + drow * nu + U.c, pack_partial(acc));
+    }
+    SV_STAMP(4);
+
+    // the first unit of a sequence's last row pair finishes the sequence: the earlier positions and the
+    // last target row come before it in the workgroup order
+    if (U.i == gamma - 1 && U.c == 0) {
         SV_STAMP(5);
         finalize_sequence<T, ALIGNED, GREEDY>(P, U.b);
         SV_STAMP(6);

@@ -28,9 +28,10 @@ struct Layout {
     size_t total;
     // fused path
     bool fused_ok;
-    int nu, nuf, wgs_per_seq;     // wave chunks per row pair / per half last row, workgroups per sequence
+    int nu;                       // wave chunks per row = 4 * workgroups per row
+    size_t fused_grid;            // workgroups of the fused kernel
     size_t control_words;         // header, ratio, pstat, qstat, spart, rpart: in ints, at offset 0, zero between calls
-    size_t off_ratio, off_pstat, off_qstat, off_spart, off_rpart;
+    size_t off_ratio, off_rowstat, off_pstat, off_qstat, off_spart, off_rpart;
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -45,15 +46,14 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     if (L.rows_total * (size_t)L.nchunks > 0x7fffffffull) return false;     // 1-D grids of 32-bit size
     const size_t rows_t = (size_t)B * (gamma + 1), rows_d = (size_t)B * gamma;
 
-    // a workgroup is four waves: four neighbouring units of a row pair, or of the last target row, where a
-    // unit is two wave chunks (so a last-row workgroup covers eight)
+    // a workgroup is four waves, each with one wave chunk of a row
     L.nu = (V + kChunk - 1) / kChunk * kWaves;
-    L.nuf = (L.nu / kWaves + 1) / 2 * kWaves;
-    L.wgs_per_seq = (gamma * L.nu + L.nuf) / kWaves;
-    L.fused_ok = L.nu <= kMaxUnitsPerRow && (size_t)B * L.wgs_per_seq <= 0x7fffffffull;
+    L.fused_grid = rows_t * (size_t)(L.nu / kWaves);
+    L.fused_ok = L.nu <= kMaxUnitsPerRow && L.fused_grid <= 0x7fffffffull;
     size_t off = kHdrWords * sizeof(int);
     L.off_ratio = off;  off += rows_d * sizeof(u64);
-    L.off_pstat = off;  off += rows_t * 2 * L.nuf * sizeof(u64);
+    L.off_rowstat = off; off += rows_d * 3 * sizeof(u64);
+    L.off_pstat = off;  off += rows_t * L.nu * sizeof(u64);
     L.off_qstat = off;  off += rows_d * L.nu * sizeof(u64);
     L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
     L.off_rpart = off;  off += rows_d * L.nu * sizeof(unsigned);
@@ -128,16 +128,15 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                        : resident_workgroups(fused_verify_kernel<T, ALIGNED, true, false>, cap[2]))
                : (wide ? resident_workgroups(fused_verify_kernel<T, ALIGNED, false, true>, cap[1])
                        : resident_workgroups(fused_verify_kernel<T, ALIGNED, false, false>, cap[0]));
-    if (capacity < 2) return SV_ERR_HIP;
+    const int wpr = L.nu / kWaves;
     // a row's workgroups wait for each other and must fit on the device together, with room to spare
-    if (capacity < L.nu / kWaves * 4) return SV_ERR_UNSUPPORTED;
+    if (capacity < 4 * wpr) return capacity < 1 ? SV_ERR_HIP : SV_ERR_UNSUPPORTED;
     FusedParams P;
     P.target = target; P.draft = draft; P.tokens = tokens; P.uniforms = uniforms;
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
-    P.nu = L.nu; P.nuf = L.nuf; P.wgs_per_seq = L.wgs_per_seq;
+    P.nu = L.nu;
     // groups of sequences so large that one position of a group fills the device at least once
     {
-        const int wpr = L.nu / kWaves;
         const int min_seqs = (capacity + wpr - 1) / wpr;
         const int groups = B / min_seqs > 1 ? B / min_seqs : 1;
         P.group_seqs = (B + groups - 1) / groups;
@@ -146,13 +145,14 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);
     P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
+    P.rowstat = reinterpret_cast<u64 *>(ws + L.off_rowstat);
     P.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
     P.qstat = reinterpret_cast<u64 *>(ws + L.off_qstat);
     P.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
     P.rpart = reinterpret_cast<unsigned *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
     P.prof = g_prof.load();
-    const unsigned grid = (unsigned)((size_t)B * L.wgs_per_seq);   // one workgroup per four units
+    const unsigned grid = (unsigned)L.fused_grid;
     if (greedy) {
         if (wide) fused_verify_kernel<T, ALIGNED, true, true><<<grid, kThreads, 0, stream>>>(P);
         else fused_verify_kernel<T, ALIGNED, true, false><<<grid, kThreads, 0, stream>>>(P);
@@ -187,7 +187,6 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
     char *ws = static_cast<char *>(workspace);
     const int path = g_path.load();
     if (path == 2 && !L.fused_ok) return SV_ERR_UNSUPPORTED;
-    const bool fused = path == 2;       // the staged path is the default until the fused kernel is faster
 
 #define SV_DISPATCH(FN)                                                                                      \
     (dtype == SV_DTYPE_F32                                                                                   \
@@ -199,7 +198,12 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
                                        accept_len, next_token, debug_out, stream)                            \
                     : FN<bf16_t, false>(algo, target, draft, tokens, uniforms, B, gamma, V, k, kd, L, ws,        \
                                         accept_len, next_token, debug_out, stream)))
-    return fused ? SV_DISPATCH(launch_fused) : SV_DISPATCH(launch_staged);
+    // the fused kernel is the default; sizes it does not take go to the staged kernels
+    if (path != 1 && L.fused_ok) {
+        const sv_status_t st = SV_DISPATCH(launch_fused);
+        if (st != SV_ERR_UNSUPPORTED || path == 2) return st;
+    }
+    return SV_DISPATCH(launch_staged);
 #undef SV_DISPATCH
 }
 
