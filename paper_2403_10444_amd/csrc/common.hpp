@@ -108,34 +108,31 @@ __device__ __forceinline__ void load_vec(const T *row, int V, int idx, float *ou
 // ------------------------------------------------------------------ wavefront reductions
 // All cross-lane moves go through DPP (no LDS crossbar): four steps inside each row of 16 lanes,
 // two row broadcasts that leave the result in lane 63, one readlane.  Every lane gets the same
-// value; the order of the operations is fixed.
-template <int CTRL, int ROW_MASK = 0xf>
-__device__ __forceinline__ float dpp_move(float v, float fill = 0.f)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
-}
+// value; the order of the operations is fixed.  Each step is ONE instruction, v = op(dpp(v), v)
+// in place: lanes that a broadcast step does not address keep their value.  The compiler does not
+// form these from the DPP builtin for max nor for the broadcast steps, hence the assembly; the
+// s_nop before each step covers the two wait states a DPP read needs after a VALU write.
+#define SV_DPP_REDUCE(OP)                                                                       \
+    "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"          \
+    "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"          \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"              \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"                   \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"                 \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"                 \
+    "s_nop 1"
 
 __device__ __forceinline__ float wave_sum(float v)
 {
-    v += dpp_move<0xB1>(v);              // quad_perm [1,0,3,2]
-    v += dpp_move<0x4E>(v);              // quad_perm [2,3,0,1]
-    v += dpp_move<0x141>(v);             // row_half_mirror
-    v += dpp_move<0x140>(v);             // row_mirror: every lane holds its row's sum
-    v += dpp_move<0x142, 0xa>(v);        // row_bcast15 into rows 1 and 3
-    v += dpp_move<0x143, 0xc>(v);        // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    asm volatile(SV_DPP_REDUCE("v_add_f32_dpp") : "+v"(v));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ float wave_max(float v)
 {
-    v = fmaxf(v, dpp_move<0xB1>(v, v));
-    v = fmaxf(v, dpp_move<0x4E>(v, v));
-    v = fmaxf(v, dpp_move<0x141>(v, v));
-    v = fmaxf(v, dpp_move<0x140>(v, v));
-    v = fmaxf(v, dpp_move<0x142, 0xa>(v, v));
-    v = fmaxf(v, dpp_move<0x143, 0xc>(v, v));
+    asm volatile(SV_DPP_REDUCE("v_max_f32_dpp") : "+v"(v));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
+#undef SV_DPP_REDUCE
 
 __device__ __forceinline__ double wave_sum_double(double v)
 {

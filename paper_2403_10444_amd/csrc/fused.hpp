@@ -68,6 +68,7 @@ struct FusedParams {
     int nu;               // units (wave chunks) per row = 4 * workgroups per row
     int group_seqs;       // sequences per group of the row order
     int spin_limit;
+    int nozero;
     int magic;            // workspace_magic(B, gamma, V)
     int *header;
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
@@ -184,23 +185,18 @@ struct Unit {
 
 // Workgroup order: groups of `group_seqs` sequences; inside a group first the last target rows
 // (which have no draft row), then the row pairs position-major (position, sequence, chunk).
-// Workgroup g takes four neighbouring units of row g / (nu / 4).
-__device__ __forceinline__ Unit decode_unit(const FusedParams &P, int g, int wave)
+// The grid spells this out, (x, y, z) = (chunk / 4, sequence in group, group * (gamma + 1) + slot)
+// with slot 0 for the last target row and 1 + i for position i; x runs fastest in the start order.
+// Returns false for the padding of a last, smaller group.
+__device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit &U)
 {
-    Unit U;
-    const int wpr = P.nu / kWaves;                          // workgroups per row
-    const int R = g / wpr;
-    U.c = (g - R * wpr) * kWaves + wave;
-    const int rows_per_group = (P.gamma + 1) * P.group_seqs;
-    const int grp = R / rows_per_group;
-    const int r = R - grp * rows_per_group;
-    const int b0 = grp * P.group_seqs;
-    const int nb = P.B - b0 < P.group_seqs ? P.B - b0 : P.group_seqs;   // sequences in this group
-    const int slot = r / nb;                                // 0: last target rows; 1 + i: position i
-    U.b = b0 + (r - slot * nb);
+    int grp = 0, slot = blockIdx.z;
+    if (P.B > P.group_seqs) { grp = blockIdx.z / (P.gamma + 1); slot = blockIdx.z - grp * (P.gamma + 1); }
+    U.b = grp * P.group_seqs + blockIdx.y;
+    U.c = blockIdx.x * kWaves + wave;
     U.last_row = slot == 0;
     U.i = U.last_row ? P.gamma : slot - 1;
-    return U;
+    return U.b < P.B;
 }
 
 // The logits a lane holds of one row, as loaded: raw 16-byte vectors on the aligned path.
@@ -214,15 +210,23 @@ template <typename T> struct RawSlice<T, false> { };      // the element-wise pa
 // Vector v of a lane starts at element first + v * 64 * kVec of the row, so one load instruction of
 // the wave covers 1 KB of contiguous memory.
 template <typename T, bool ALIGNED>
-__device__ __forceinline__ void issue_loads(const T *row, int first, int V, RawSlice<T, ALIGNED> &raw)
+__device__ __forceinline__ void issue_loads(const T *row, int unit_first, int V, RawSlice<T, ALIGNED> &raw)
 {
     if constexpr (ALIGNED) {
         constexpr int kVec = ElemTraits<T>::kVec;
+        const char *base = reinterpret_cast<const char *>(row);
+        const unsigned lane_off = (unsigned)(unit_first + (int)(threadIdx.x & 63) * kVec) * (unsigned)sizeof(T);
+        if (unit_first + kUnitLogits <= V) {                   // wave-uniform: the whole unit lies inside the row
 #pragma unroll
-        for (int v = 0; v < RawSlice<T, true>::kNV; ++v) {
-            const int idx = first + v * kWave * kVec;
-            // vectors beyond the row are recognised again when the slice is unpacked; load something valid
-            raw.v[v] = *reinterpret_cast<const uint4 *>(row + (idx < V ? idx : 0));
+            for (int v = 0; v < RawSlice<T, true>::kNV; ++v)
+                raw.v[v] = *reinterpret_cast<const uint4 *>(base + (lane_off + (unsigned)(v * kWave * 16)));
+        } else {
+#pragma unroll
+            for (int v = 0; v < RawSlice<T, true>::kNV; ++v) {
+                const unsigned off = lane_off + (unsigned)(v * kWave * 16);
+                // vectors beyond the row are recognised again when the slice is unpacked; load something valid
+                raw.v[v] = *reinterpret_cast<const uint4 *>(base + (off < (unsigned)V * (unsigned)sizeof(T) ? off : 0u));
+            }
         }
     }
 }
@@ -240,16 +244,17 @@ __device__ __forceinline__ void unpack_vec(const uint4 &v, float *out)
 }
 
 template <typename T, bool ALIGNED>
-__device__ __forceinline__ void unpack_slice(const T *row, int first, int V, const RawSlice<T, ALIGNED> &raw,
+__device__ __forceinline__ void unpack_slice(const T *row, int unit_first, int V, const RawSlice<T, ALIGNED> &raw,
                                              float (&x)[kLaneLogits])
 {
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = kLaneLogits / kVec;
+    const int first = unit_first + (int)(threadIdx.x & 63) * kVec;
     if constexpr (ALIGNED) {
 #pragma unroll
         for (int v = 0; v < kNV; ++v) unpack_vec<T>(raw.v[v], x + v * kVec);
         // only a row's last units reach beyond the row (wave-uniform test): blank what lies beyond
-        if (__builtin_amdgcn_readfirstlane(first) + kUnitLogits > V) {
+        if (unit_first + kUnitLogits > V) {
 #pragma unroll
             for (int v = 0; v < kNV; ++v) {
                 const bool out = first + v * kWave * kVec >= V;
@@ -264,31 +269,23 @@ __device__ __forceinline__ void unpack_slice(const T *row, int first, int V, con
     }
 }
 
-// First sweep over the logits a lane holds of one row: x[j] becomes exp2(x[j] * k - shift) with
-// shift = k * (largest of them), `mk` is that shift (-inf when all of them lie beyond the row)
-// and `s` the sum of the exponentials.
-__device__ __forceinline__ void exp_sum(float (&x)[kLaneLogits], float k, float &shift, float &mk, float &s)
+// First sweep over the logits the wave holds of one row: x[j] becomes exp2(x[j] * k - shift) with
+// the wave-uniform shift = k * (largest logit of the unit), or 0 when the whole unit lies beyond
+// the row.  Returns the unit's word: (k * largest logit, sum of the exponentials); (-inf, 0) beyond.
+__device__ __forceinline__ u64 first_sweep_row(float (&x)[kLaneLogits], float k, float &shift)
 {
     float m = x[0];
 #pragma unroll
     for (int j = 1; j < kLaneLogits; ++j) m = fmaxf(m, x[j]);
-    mk = m * k;
-    shift = m > -INFINITY ? mk : 0.f;
+    const float Mw = wave_max(m * k);
+    shift = Mw > -INFINITY ? Mw : 0.f;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};     // four partial sums: shorter chains, smaller rounding error
 #pragma unroll
     for (int j = 0; j < kLaneLogits; ++j) {
         x[j] = fast_exp2(__builtin_fmaf(x[j], k, -shift));
         acc[j & 3] += x[j];
     }
-    s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-}
-
-// Wave-level combination of the per-lane (shift, sum) pairs.
-__device__ __forceinline__ u64 wave_stat(float mk, float s)
-{
-    const float Mw = wave_max(mk);
-    const float scale = Mw > -INFINITY ? fast_exp2(mk - Mw) : 0.f;
-    const float sw = wave_sum(s * scale);
+    const float sw = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
     return pack_stat(Mw, sw);
 }
 
@@ -349,7 +346,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     const size_t base = (size_t)b * (gamma + 1);
     const int e_lane = lane < nu ? lane : nu - 1;
     bool gave_up = false;
-#define FSTAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
+#define FSTAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
 
     // ---- row results live in lane j's registers (gamma <= 64): log2 r_{j+1}, L_p, L_q and M_p as the
     // row's first unit published them
@@ -577,6 +574,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     FSTAMP(12);
     // ---- leave the sequence's words zero for the next call.  Every reader of the row-pair words has
     // published its partial sum by now; the words of the last target row must all be written first.
+    if (P.nozero) return;
     for (int e = lane; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     for (int e = lane; e < (gamma + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
@@ -595,28 +593,29 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ElemTr
 void fused_verify_kernel(const FusedParams P)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int gamma = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
 
     if (__builtin_nontemporal_load(P.header + kHdrMagic) != P.magic) {
         // the workspace was not initialised for this shape: report it through the outputs and leave
-        if (blockIdx.x == 0)
+        if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
             for (int b = threadIdx.x; b < P.B; b += kThreads) { P.accept_len[b] = -1; P.next_token[b] = -1; }
         return;
     }
-#define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
-    const Unit U = decode_unit(P, blockIdx.x, wave);
+#define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
+    Unit U;
+    if (!decode_unit(P, wave, U)) return;
     SV_STAMP(0);
 
     // stream A: the unit's chunk of target row i; stream B: the same chunk of draft row i (none for the last row)
     const size_t trow = (size_t)U.b * (gamma + 1) + U.i, drow = (size_t)U.b * gamma + (U.last_row ? 0 : U.i);
     const T *rowA = static_cast<const T *>(P.target) + trow * V;
     const T *rowB = static_cast<const T *>(P.draft) + drow * V;
-    const int first = U.c * kUnitLogits + lane * kVec;
+    const int unit_first = U.c * kUnitLogits;
     RawSlice<T, ALIGNED> rawA, rawB;
-    issue_loads<T, ALIGNED>(rowA, first, V, rawA);
-    if (!U.last_row) issue_loads<T, ALIGNED>(rowB, first, V, rawB);
+    issue_loads<T, ALIGNED>(rowA, unit_first, V, rawA);
+    if (!U.last_row) issue_loads<T, ALIGNED>(rowB, unit_first, V, rawB);
     // draft token X_{i+1} and its two logits: a row's first unit publishes the row's ratio from them
     double ya = 0.0, yb = 0.0;
     if (!U.last_row && U.c == 0) {
@@ -627,18 +626,16 @@ void fused_verify_kernel(const FusedParams P)
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     float xa[kLaneLogits], xb[kLaneLogits];
-    float shiftA, mkA, sA, shiftB, mkB, sB;
-    unpack_slice<T, ALIGNED>(rowA, first, V, rawA, xa);
-    exp_sum(xa, k, shiftA, mkA, sA);
+    float shiftA, shiftB;
+    unpack_slice<T, ALIGNED>(rowA, unit_first, V, rawA, xa);
     {
-        const u64 stA = wave_stat(mkA, sA);
+        const u64 stA = first_sweep_row(xa, k, shiftA);
         if (lane == 0) st_u64(P.pstat + trow * nu + U.c, stA);
     }
     if (U.last_row) return;          // the last target row has no draft row and no residual
-    unpack_slice<T, ALIGNED>(rowB, first, V, rawB, xb);
-    exp_sum(xb, k, shiftB, mkB, sB);
+    unpack_slice<T, ALIGNED>(rowB, unit_first, V, rawB, xb);
     {
-        const u64 stB = wave_stat(mkB, sB);
+        const u64 stB = first_sweep_row(xb, k, shiftB);
         if (lane == 0) st_u64(P.qstat + drow * nu + U.c, stB);
     }
     SV_STAMP(1);
@@ -680,18 +677,35 @@ void fused_verify_kernel(const FusedParams P)
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     SV_STAMP(3);
 
-    // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq
-    const float cp = fast_exp2((float)((double)shiftA - (Lp - log2w)));
-    const float cq = fast_exp2((float)((double)shiftB - Lq));
+    // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq with wave-uniform cp, cq
+    const double log2cp = (double)shiftA - (Lp - log2w), log2cq = (double)shiftB - Lq;
     float acc = 0.f, rej = 0.f;
+    if constexpr (GREEDY) {
+        const float cp = fast_exp2((float)log2cp), cq = fast_exp2((float)log2cq);
 #pragma unroll
-    for (int j = 0; j < kLaneLogits; ++j) {
-        const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
-        if constexpr (GREEDY) { acc += fmaxf(d, 0.f); rej += fmaxf(-d, 0.f); }
-        else acc += __builtin_amdgcn_fmed3f(d, 0.f, 1.f);   // w p <= 1, so clamping to [0, 1] is max(d, 0); folds into the fma
+        for (int j = 0; j < kLaneLogits; ++j) {
+            const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
+            acc += fmaxf(d, 0.f);
+            rej += fmaxf(-d, 0.f);
+        }
+        rej = wave_sum(rej);
+    } else {
+        // sum of max(xa cp - xb cq, 0) with the larger factor taken out, so that every term lies in [0, 1]
+        // (xa, xb <= 1) and the clamp of the fma is the max: two instructions per pair
+        const double log2rho = log2cp - log2cq;
+        if (log2rho <= 0.0) {
+            const float rho = fast_exp2((float)log2rho);
+#pragma unroll
+            for (int j = 0; j < kLaneLogits; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xa[j], rho, -xb[j]), 0.f, 1.f);
+            acc *= fast_exp2((float)log2cq);
+        } else {
+            const float nrho = -fast_exp2((float)-log2rho);
+#pragma unroll
+            for (int j = 0; j < kLaneLogits; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xb[j], nrho, xa[j]), 0.f, 1.f);
+            acc *= fast_exp2((float)log2cp);
+        }
     }
     acc = wave_sum(acc);
-    if constexpr (GREEDY) rej = wave_sum(rej);
     if (lane == 0) {
         if constexpr (GREEDY) st_u32(P.rpart + drow * nu + U.c, pack_partial(rej));
         st_u32(P.spart + drow * nu + U.c, pack_partial(acc));

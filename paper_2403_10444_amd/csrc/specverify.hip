@@ -8,6 +8,7 @@
 #include <stdint.h>
 #include <math.h>
 #include <atomic>
+#include <stdlib.h>
 
 #include "../../include/specverify.h"
 #include "common.hpp"
@@ -136,12 +137,14 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
     P.nu = L.nu;
     // groups of sequences so large that one position of a group fills the device at least once
-    {
-        const int min_seqs = (capacity + wpr - 1) / wpr;
-        const int groups = B / min_seqs > 1 ? B / min_seqs : 1;
-        P.group_seqs = (B + groups - 1) / groups;
-    }
+    const int min_seqs = (capacity + wpr - 1) / wpr;
+    const int groups = B / min_seqs > 1 ? B / min_seqs : 1;
+    P.group_seqs = (B + groups - 1) / groups;
+    const int n_groups = (B + P.group_seqs - 1) / P.group_seqs;
+    if ((size_t)n_groups * (gamma + 1) > 65535u || P.group_seqs > 65535) return SV_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)wpr, (unsigned)P.group_seqs, (unsigned)(n_groups * (gamma + 1)));
     P.spin_limit = g_spin_limit.load();
+    P.nozero = getenv("SV_NOZERO") ? 1 : 0;
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);
     P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
@@ -152,7 +155,6 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.rpart = reinterpret_cast<unsigned *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
     P.prof = g_prof.load();
-    const unsigned grid = (unsigned)L.fused_grid;
     if (greedy) {
         if (wide) fused_verify_kernel<T, ALIGNED, true, true><<<grid, kThreads, 0, stream>>>(P);
         else fused_verify_kernel<T, ALIGNED, true, false><<<grid, kThreads, 0, stream>>>(P);
