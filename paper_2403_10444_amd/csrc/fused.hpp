@@ -44,7 +44,7 @@ namespace sv {
 constexpr int kWave = 64;
 constexpr int kLaneLogits = 32;                      // logits of one row that a lane holds of a unit
 constexpr int kUnitLogits = kWave * kLaneLogits;    // contiguous logits of one row in a unit
-constexpr int kMaxUnitsPerRow = 512;     // wave chunks per row the fused kernel takes (V <= 1 Mi logits)
+constexpr int kMaxUnitsPerRow = 512;     // wave chunks per row the fused kernel takes (V <= 1 Mi logits): 8 words per lane
 
 // Word 0 of an initialised workspace: a constant mixed with the shape it was initialised for.
 __host__ __device__ inline int workspace_magic(int B, int gamma, int V)
@@ -68,7 +68,6 @@ struct FusedParams {
     int nu;               // units (wave chunks) per row = 4 * workgroups per row
     int group_seqs;       // sequences per group of the row order
     int spin_limit;
-    int nozero;
     int magic;            // workspace_magic(B, gamma, V)
     int *header;
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
@@ -159,23 +158,53 @@ struct StatAcc {
     }
 };
 
-// Log2-normaliser of a row from the words of its n units: every lane takes entries lane, lane+64,
-// ... (in that fixed order), then the wave combines.  `first` is this lane's entry `lane` as the
-// caller loaded it (0: not there yet, it is polled).  WIDE: the row has more than 64 units.
-// Returns L; M_out is the largest shift.
-template <bool WIDE>
-__device__ __forceinline__ double row_normaliser(const u64 *words, int n, int limit, bool &gave_up, float &M_out, u64 first)
+// The words of a row's n units as a wave holds them: lane l has entries l, l + 64, ... (NW of them).
+template <int NW> struct RowWords { u64 w[NW]; };
+
+// Issues the loads of a row's words (an entry that is still 0 is polled later).
+template <int NW>
+__device__ __forceinline__ void load_row_words(const u64 *words, int n, RowWords<NW> &r)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+        const int e = lane + q * kWave;
+        r.w[q] = ld_u64(words + (e < n ? e : n - 1));
+    }
+}
+
+// Log2-normaliser of a row from the words of its n <= 64 NW units: every lane combines its entries
+// (in that fixed order), then the wave combines.  Returns L; M_out is the largest shift.
+template <int NW>
+__device__ __forceinline__ double row_normaliser(const u64 *words, int n, int limit, bool &gave_up, float &M_out, const RowWords<NW> &r)
 {
     const int lane = threadIdx.x & 63;
     StatAcc acc;
-    const u64 w0 = wait_word(words + lane, first, lane < n, limit, gave_up);
-    if (lane < n) acc.add(w0);
-    if constexpr (WIDE)
-        for (int e = lane + kWave; e < n; e += kWave) acc.add(wait_word(words + e, limit, gave_up));
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+        const int e = lane + q * kWave;
+        if (q * kWave < n) {
+            const u64 w = wait_word(words + (e < n ? e : n - 1), r.w[q], e < n, limit, gave_up);
+            if (e < n) acc.add(w);
+        }
+    }
     const float M = wave_max(acc.m);
     const float z = wave_sum(acc.m > -INFINITY ? acc.z * fast_exp2(acc.m - M) : 0.f);
     M_out = M;
     return (double)M + log2_precise(z);
+}
+
+// Largest shift among a row's words, once all of them are there.
+__device__ __forceinline__ float row_max_shift(const u64 *words, int n, int limit, bool &gave_up)
+{
+    const int lane = threadIdx.x & 63;
+    float m = -INFINITY;
+    for (int e0 = 0; e0 < n; e0 += kWave) {
+        const int e = e0 + lane;
+        const u64 w = wait_word(words + (e < n ? e : n - 1), 0, e < n, limit, gave_up);
+        if (e < n) m = fmaxf(m, stat_shift(w));
+    }
+    return wave_max(m);
 }
 
 struct Unit {
@@ -465,7 +494,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
         } else if (lane < nu) part0 = unpack_partial(ld_u32(sp + lane));
     } else {
         // everything accepted: Y comes from p_gamma; its words are polled until they are all there
-        row_normaliser<true>(st, nu, P.spin_limit, gave_up, Mrow, 0);
+        Mrow = row_max_shift(st, nu, P.spin_limit, gave_up);
     }
     int slot = -1, last_nonzero = 0;
     double t_in = 0.0;
@@ -574,7 +603,6 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     FSTAMP(12);
     // ---- leave the sequence's words zero for the next call.  Every reader of the row-pair words has
     // published its partial sum by now; the words of the last target row must all be written first.
-    if (P.nozero) return;
     for (int e = lane; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     for (int e = lane; e < (gamma + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
@@ -588,7 +616,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
 }
 
 // ------------------------------------------------------------------ the kernel
-template <typename T, bool ALIGNED, bool GREEDY, bool WIDE>
+template <typename T, bool ALIGNED, bool GREEDY, int NW>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ElemTraits<T>::kVec == 8 ? 5 : 4)))
 void fused_verify_kernel(const FusedParams P)
 {
@@ -604,6 +632,9 @@ void fused_verify_kernel(const FusedParams P)
         return;
     }
 #define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
+    // the short serial stretches (issuing the loads; everything after the first sweep) run at high wave
+    // priority, the long first sweep, which has plenty of independent work, at low priority
+    __builtin_amdgcn_s_setprio(3);
     Unit U;
     if (!decode_unit(P, wave, U)) return;
     SV_STAMP(0);
@@ -627,6 +658,7 @@ void fused_verify_kernel(const FusedParams P)
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     float xa[kLaneLogits], xb[kLaneLogits];
     float shiftA, shiftB;
+    __builtin_amdgcn_s_setprio(0);
     unpack_slice<T, ALIGNED>(rowA, unit_first, V, rawA, xa);
     {
         const u64 stA = first_sweep_row(xa, k, shiftA);
@@ -638,18 +670,19 @@ void fused_verify_kernel(const FusedParams P)
         const u64 stB = first_sweep_row(xb, k, shiftB);
         if (lane == 0) st_u64(P.qstat + drow * nu + U.c, stB);
     }
+    __builtin_amdgcn_s_setprio(3);
     SV_STAMP(1);
 
     // ---- the words of this row's units give L_p and L_q; the ratios of the earlier rows give w_i
     bool gave_up = false;
-    const int e0 = lane < nu ? lane : nu - 1;
-    const u64 pw = ld_u64(P.pstat + trow * nu + e0);
-    const u64 qw = ld_u64(P.qstat + drow * nu + e0);
+    RowWords<NW> pw, qw;
+    load_row_words<NW>(P.pstat + trow * nu, nu, pw);
+    load_row_words<NW>(P.qstat + drow * nu, nu, qw);
     u64 rt = 1;
     if (P.algo != kToken && lane < U.i) rt = ld_u64(P.ratio + (size_t)U.b * gamma + lane);
     float Mp, Mq;
-    const double Lp = row_normaliser<WIDE>(P.pstat + trow * nu, nu, P.spin_limit, gave_up, Mp, pw);
-    const double Lq = row_normaliser<WIDE>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
+    const double Lp = row_normaliser<NW>(P.pstat + trow * nu, nu, P.spin_limit, gave_up, Mp, pw);
+    const double Lq = row_normaliser<NW>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
     SV_STAMP(2);
     if (lane == 0 && U.c == 0) {
         // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for the later rows.  The sweeps

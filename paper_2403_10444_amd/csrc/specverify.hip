@@ -8,7 +8,6 @@
 #include <stdint.h>
 #include <math.h>
 #include <atomic>
-#include <stdlib.h>
 
 #include "../../include/specverify.h"
 #include "common.hpp"
@@ -121,14 +120,17 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
 {
-    // resident workgroups of the four instantiations (greedy or not, rows of more than 64 units or not)
-    static int cap[4] = {0, 0, 0, 0};
-    const bool greedy = algo == kGreedy, wide = L.nu > kWave;
-    const int capacity =
-        greedy ? (wide ? resident_workgroups(fused_verify_kernel<T, ALIGNED, true, true>, cap[3])
-                       : resident_workgroups(fused_verify_kernel<T, ALIGNED, true, false>, cap[2]))
-               : (wide ? resident_workgroups(fused_verify_kernel<T, ALIGNED, false, true>, cap[1])
-                       : resident_workgroups(fused_verify_kernel<T, ALIGNED, false, false>, cap[0]));
+    // the instantiation for this row width (1, 2, 4 or 8 words of a row per lane) and its resident workgroups
+    static int cap[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    const bool greedy = algo == kGreedy;
+    const int nw_log = L.nu <= kWave ? 0 : L.nu <= 2 * kWave ? 1 : L.nu <= 4 * kWave ? 2 : 3;
+    void (*kernel)(const FusedParams) = nullptr;
+#define SV_PICK(G)                                                                     \
+    (nw_log == 0 ? fused_verify_kernel<T, ALIGNED, G, 1> : nw_log == 1 ? fused_verify_kernel<T, ALIGNED, G, 2> \
+     : nw_log == 2 ? fused_verify_kernel<T, ALIGNED, G, 4> : fused_verify_kernel<T, ALIGNED, G, 8>)
+    kernel = greedy ? SV_PICK(true) : SV_PICK(false);
+#undef SV_PICK
+    const int capacity = resident_workgroups(kernel, cap[greedy ? 1 : 0][nw_log]);
     const int wpr = L.nu / kWaves;
     // a row's workgroups wait for each other and must fit on the device together, with room to spare
     if (capacity < 4 * wpr) return capacity < 1 ? SV_ERR_HIP : SV_ERR_UNSUPPORTED;
@@ -144,7 +146,6 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     if ((size_t)n_groups * (gamma + 1) > 65535u || P.group_seqs > 65535) return SV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)wpr, (unsigned)P.group_seqs, (unsigned)(n_groups * (gamma + 1)));
     P.spin_limit = g_spin_limit.load();
-    P.nozero = getenv("SV_NOZERO") ? 1 : 0;
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);
     P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
@@ -155,13 +156,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.rpart = reinterpret_cast<unsigned *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
     P.prof = g_prof.load();
-    if (greedy) {
-        if (wide) fused_verify_kernel<T, ALIGNED, true, true><<<grid, kThreads, 0, stream>>>(P);
-        else fused_verify_kernel<T, ALIGNED, true, false><<<grid, kThreads, 0, stream>>>(P);
-    } else {
-        if (wide) fused_verify_kernel<T, ALIGNED, false, true><<<grid, kThreads, 0, stream>>>(P);
-        else fused_verify_kernel<T, ALIGNED, false, false><<<grid, kThreads, 0, stream>>>(P);
-    }
+    kernel<<<grid, kThreads, 0, stream>>>(P);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
@@ -200,8 +195,11 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
                                        accept_len, next_token, debug_out, stream)                            \
                     : FN<bf16_t, false>(algo, target, draft, tokens, uniforms, B, gamma, V, k, kd, L, ws,        \
                                         accept_len, next_token, debug_out, stream)))
-    // the fused kernel is the default; sizes it does not take go to the staged kernels
-    if (path != 1 && L.fused_ok) {
+    // the fused kernel (every logit read once, but units wait for their row) is the default up to 2 GiB of
+    // logits; beyond that the staged kernels (every logit read twice, at streaming speed) are as fast or
+    // faster, and they also take the sizes the fused kernel does not
+    const size_t logit_bytes = (size_t)B * (2 * (size_t)gamma + 1) * (size_t)V * esize;
+    if (path == 2 || (path == 0 && L.fused_ok && logit_bytes <= ((size_t)2 << 30))) {
         const sv_status_t st = SV_DISPATCH(launch_fused);
         if (st != SV_ERR_UNSUPPORTED || path == 2) return st;
     }
