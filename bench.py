@@ -18,6 +18,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+COPY_PROBE_BYTES = 256 << 20
+
+
+def measured_traffic(workload, algo):
+    """HBM bytes per call as measured with hardware counters (profiles/traffic_<workload>_<algo>.txt,
+    written from two `rocprofv3 --pmc` runs of this script), or None when no such measurement is stored."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}_{algo}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_call:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(cfg, inputs, budget_s=12.0):
@@ -55,6 +69,9 @@ def main():
                     help="kernel path (testing hook of the library)")
     ap.add_argument("--spin-limit", type=int, default=-1,
                     help="bound of the fused kernel's waits in polls (testing hook; 0 makes results invalid)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="N",
+                    help="also launch the library's plain copy kernel N times on 256 MiB (untimed): the "
+                         "reference that hardware traffic counters of a profiler run are scaled against")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (sequences are independent; more GPUs "
@@ -84,6 +101,14 @@ def main():
         fn(s["target_logits"], s["draft_logits"], s["draft_tokens"], s["uniforms"], cfg.temperature,
            workspace=ws, accept_len=tau, next_token=y, stream=stream.cuda_stream)
 
+    if args.copy_probe > 0:
+        src = torch.full((COPY_PROBE_BYTES,), 1, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_probe):
+            sv.spec_verify_debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -110,8 +135,10 @@ def main():
         "seq_verifications_per_s": calls_per_s * cfg.B,
         "mean_accept_len": float(tau.float().mean().item()),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "whole call (all kernels of one verification)",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(cfg.name, args.algo) if args.path == "default" else None,
+                     "kernel": "whole call: fused_verify_kernel, the call's only kernel, on the default path up to "
+                               "2 GiB of logits; four staged kernels beyond or with --path staged",
                      "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms},
     }
     if not args.no_cpu_baseline:

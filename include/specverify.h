@@ -91,6 +91,12 @@ void spec_verify_debug_config(int32_t path, int32_t spin_limit);
  * workgroup, B * (gamma + 1) * ceil(V / 8192) workgroups, and be zeroed by the caller.    */
 void spec_verify_debug_profile(void *device_buffer);
 
+/* Measurement hook: copies `bytes` (a multiple of 16, both pointers 16-byte aligned device
+ * memory, not overlapping) from `src` to `dst` with a plain copy kernel on `stream`.  It reads
+ * and writes exactly `bytes` each, which is what hardware counters of memory traffic are
+ * scaled against.  SV_ERR_INVALID_ARG for null, misaligned or ragged arguments.            */
+sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 /*
  * Block verification (Alg. 2).
  *   target_logits  [B, gamma+1, V]  dtype, V contiguous, rows dense (stride V)

@@ -29,6 +29,7 @@ EXPORTED = (
     "spec_verify_workspace_check",
     "spec_verify_debug_config",
     "spec_verify_debug_profile",
+    "spec_verify_debug_copy",
     "spec_verify_block",
     "spec_verify_token",
     "spec_verify_greedy",
@@ -76,6 +77,8 @@ def load() -> ctypes.CDLL:
         lib.spec_verify_debug_config.argtypes = [ctypes.c_int32, ctypes.c_int32]
         lib.spec_verify_debug_profile.restype = None
         lib.spec_verify_debug_profile.argtypes = [ctypes.c_void_p]
+        lib.spec_verify_debug_copy.restype = ctypes.c_int
+        lib.spec_verify_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         lib.spec_verify_status_string.restype = ctypes.c_char_p
         lib.spec_verify_status_string.argtypes = [ctypes.c_int]
         _lib = lib
@@ -108,6 +111,24 @@ def spec_verify_workspace_check(workspace: torch.Tensor, B: int, gamma: int, V: 
 
 def spec_verify_debug_config(path: int = 0, spin_limit: int = -1) -> None:
     load().spec_verify_debug_config(int(path), int(spin_limit))
+
+
+def spec_verify_debug_profile(buffer) -> None:
+    """Per-workgroup timestamps of the fused kernel go to `buffer` (a zeroed int64 device tensor) until
+    called again with None."""
+    load().spec_verify_debug_profile(buffer.data_ptr() if buffer is not None else None)
+
+
+def spec_verify_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """The library's plain copy kernel (what memory-traffic counters are scaled against)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src must have the same size in bytes")
+    if stream is None:
+        stream = torch.cuda.current_stream(src.device).cuda_stream
+    code = load().spec_verify_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream)
+    if code != SV_OK:
+        raise SpecVerifyError(code, status_string(code))
 
 
 def alloc_workspace(B: int, gamma: int, V: int, device="cuda") -> torch.Tensor:

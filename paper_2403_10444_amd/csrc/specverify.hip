@@ -248,6 +248,23 @@ void spec_verify_debug_config(int32_t path, int32_t spin_limit)
     g_spin_limit.store(spin_limit >= 0 ? spin_limit : kDefaultSpinLimit);
 }
 
+// Plain copy, 16 bytes per thread and step: what the HBM traffic counters are calibrated against.
+namespace { __global__ __launch_bounds__(256) void copy_probe_kernel(uint4 *dst, const uint4 *src, size_t nvec)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+} }
+
+sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || bytes == 0 || bytes % 16 != 0) return SV_ERR_INVALID_ARG;
+    if (((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) != 0) return SV_ERR_INVALID_ARG;
+    const size_t nvec = bytes / 16;
+    const size_t blocks = (nvec + 255) / 256;
+    copy_probe_kernel<<<(unsigned)(blocks < 65536 ? blocks : 65536), 256, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), nvec);
+    return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
 void spec_verify_debug_profile(void *device_buffer)
 {
     g_prof.store(static_cast<long long *>(device_buffer));
