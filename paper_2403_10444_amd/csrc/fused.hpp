@@ -6,21 +6,24 @@
 // sweep never touches memory: the first sweep's exponentials stay in registers until the
 // row's normalisers are known.
 //
-// A *unit* is 2048 contiguous logits of a row pair (or two such chunks of the last target row,
-// which has no draft row) and belongs to one wavefront; a workgroup is four independent waves
-// (four neighbouring units; no LDS, no barrier).  A wave
+// A *unit* is 2048 contiguous logits of a (target row i, draft row i) pair - the last target
+// row, which has no draft row, counts as a pair without its second half - and belongs to one
+// wavefront; a workgroup is four independent waves (four neighbouring units; no LDS, no
+// barrier).  A wave
 //   1. loads its 2 x 2048 logits (32 + 32 per lane, 16-byte loads, 1 KB per load instruction),
-//   2. turns them into exp2(y - shift) with per-lane shifts and KEEPS those 2 x 32 floats per
-//      lane in registers; publishes the unit's partial normalisers (shift, sum) as two words,
+//   2. turns them into exp2(y - shift) with a wave-uniform shift per row and KEEPS those 2 x 32
+//      floats per lane in registers; publishes the unit's partial normalisers (shift, sum) as
+//      two words,
 //   3. waits for the words of the other units of its row, which give L_p and L_q, and reads the
-//      ratios of the earlier rows, which give w_i (Alg. 2: w_i = min(w_{i-1} r_i, 1)),
+//      ratios of the earlier rows, which give w_i (Alg. 2: w_i = min(w_{i-1} r_i, 1)); the row's
+//      first unit publishes the row's ratio and normalisers,
 //   4. forms its share of S_i from the registers and publishes it.
-// Workgroups are ordered position-major inside groups of sequences (all row pairs of position
-// 0, then position 1, ..., then the last target rows), so the ratio of an earlier position was
+// Workgroups start position-major inside groups of sequences (the last target rows, then all
+// row pairs of position 0, then position 1, ...), so the ratio of an earlier position was
 // published long before a later one asks for it, and a unit only ever waits for the units of
-// its own row, which start next to it.  The first unit of a sequence's last target row then
-// finishes the sequence: it waits for all of the sequence's partial sums and runs the accept
-// tests and the inverse-CDF draw.
+// its own row, which start next to it.  The first unit of a sequence's last row pair then
+// finishes the sequence in the same wave: it waits for all of the sequence's partial sums and
+// runs the accept tests and the inverse-CDF draw.
 //
 // Everything that crosses waves is a self-announcing word: it is zero between calls and
 // non-zero once written (a packed (shift, sum) pair always has a non-zero sum or a -inf shift;
@@ -31,10 +34,10 @@
 //
 // Progress: the hardware starts workgroups in index order (round-robin over the XCDs, in order
 // within each).  A unit waits only for units of its own row (at most kMaxUnitsPerRow / 4
-// workgroups away, far fewer than one XCD holds) and of earlier rows of its sequence (earlier
-// workgroups), and publishing never waits: the grid always drains.  Every wait is also
-// bounded by a spin limit; running into it sets the workspace's error word and goes on
-// instead of hanging.
+// workgroups away; the host refuses rows that do not fit four times into the resident set)
+// and of earlier positions of its sequence (earlier workgroups), and publishing never waits:
+// the grid always drains.  Every wait is also bounded by a spin limit; running into it sets
+// the workspace's error word and goes on instead of hanging.
 #pragma once
 
 #include "common.hpp"
@@ -72,6 +75,7 @@ struct FusedParams {
     int *header;
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
     u64 *rowstat;         // [B, gamma, 3]            L_p, L_q (double bits, lowest bit set), M_p (float bits << 32 | 1)
+    u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy), same encoding; not for token verification
     u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
     u64 *qstat;           // [B, gamma, nu]           same for the draft rows
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
@@ -393,20 +397,17 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
         my_Mp = __uint_as_float((unsigned)(w3 >> 32));
     }
     FSTAMP(7);
-    // log2 w_j for lane j (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4 drops the min); lw_last is log2 w_gamma
+    // log2 w_j for lane j as the rows' first units published it (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4
+    // drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, lw_last = 0.0;
-    {
-        double cur = 0.0;
-        for (int j = 0; j < gamma; ++j) {
-            if (lane == j) my_lw = cur;
-            cur += read_lane_double(my_lr, j);
-            if (!GREEDY && cur > 0.0) cur = 0.0;
-        }
-        lw_last = cur;
-        if (P.algo == kToken) { my_lw = 0.0; lw_last = 0.0; }
+    if (P.algo != kToken) {
+        const u64 *word = P.lw + (size_t)b * gamma + (lane < gamma ? lane : gamma - 1);
+        const double next = unpack_ratio(wait_word(word, ld_u64(word), lane < gamma, P.spin_limit, gave_up));   // log2 w_{lane+1}
+        const double prev = __shfl_up(next, 1, kWave);
+        my_lw = lane ? prev : 0.0;
+        lw_last = read_lane_double(next, gamma - 1);
         if (GREEDY) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
     }
-
     FSTAMP(8);
     // ---- S_j (and, greedy, the rejected mass) = sum of row j's partial sums, into lane j.  kept[jj]
     // holds this lane's partial sum of row jj when gamma <= kBatch (used again for the draw).
@@ -611,7 +612,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
         st_u32(P.spart + (size_t)b * gamma * nu + e, 0);
         if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * gamma * nu + e, 0);
     }
-    for (int e = lane; e < gamma; e += kWave) st_u64(P.ratio + (size_t)b * gamma + e, 0);
+    for (int e = lane; e < gamma; e += kWave) { st_u64(P.ratio + (size_t)b * gamma + e, 0); st_u64(P.lw + (size_t)b * gamma + e, 0); }
     for (int e = lane; e < 3 * gamma; e += kWave) st_u64(P.rowstat + (size_t)b * gamma * 3 + e, 0);
 }
 
@@ -678,35 +679,41 @@ void fused_verify_kernel(const FusedParams P)
     RowWords<NW> pw, qw;
     load_row_words<NW>(P.pstat + trow * nu, nu, pw);
     load_row_words<NW>(P.qstat + drow * nu, nu, qw);
-    u64 rt = 1;
-    if (P.algo != kToken && lane < U.i) rt = ld_u64(P.ratio + (size_t)U.b * gamma + lane);
+    // log2 w_i as the first unit of the previous position published it (Alg. 2: w_i = min(w_{i-1} r_i, 1))
+    const bool need_w = P.algo != kToken && U.i > 0;
+    const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
+    u64 wt = 1;
+    if (need_w) wt = ld_u64(lw_word);
     float Mp, Mq;
     const double Lp = row_normaliser<NW>(P.pstat + trow * nu, nu, P.spin_limit, gave_up, Mp, pw);
     const double Lq = row_normaliser<NW>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
     SV_STAMP(2);
-    if (lane == 0 && U.c == 0) {
-        // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for the later rows.  The sweeps
-        // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that
+    double lr = 0.0;
+    if (U.c == 0) {
+        // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for whoever finishes the sequence.  The
+        // sweeps scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that
         // moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
         // row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
         const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
         const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-        st_u64(P.ratio + drow, pack_ratio(lp - lq));
-        // the row's normalisers, for whoever finishes the sequence
-        st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
-        st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
-        st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
-    }
-    // w_i from the ratios of the earlier rows (Alg. 2: w_i = min(w_{i-1} r_i, 1))
-    double log2w = 0.0;
-    if (P.algo != kToken) {
-        rt = wait_word(P.ratio + (size_t)U.b * gamma + (lane < gamma ? lane : gamma - 1), rt, lane < U.i, P.spin_limit, gave_up);
-        for (int j = 0; j < U.i; ++j) {
-            log2w += unpack_ratio(read_lane_u64(rt, j));
-            if (!GREEDY && log2w > 0.0) log2w = 0.0;
+        lr = lp - lq;
+        if (lane == 0) {
+            st_u64(P.ratio + drow, pack_ratio(lr));
+            // the row's normalisers, also for the finisher
+            st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
+            st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
+            st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
         }
-        if (GREEDY) log2w = fmin(log2w, 100.0);             // keeps w p finite in float
     }
+    double log2w = 0.0;
+    if (need_w) log2w = unpack_ratio(wait_word(lw_word, wt, true, P.spin_limit, gave_up));
+    if (U.c == 0 && P.algo != kToken) {
+        // w_{i+1} for the units of the next position
+        double next = log2w + lr;
+        if (!GREEDY && next > 0.0) next = 0.0;
+        if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
+    }
+    if (GREEDY) log2w = fmin(log2w, 100.0);                 // keeps w p finite in float
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     SV_STAMP(3);
 

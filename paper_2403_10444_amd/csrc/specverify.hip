@@ -31,7 +31,7 @@ struct Layout {
     int nu;                       // wave chunks per row = 4 * workgroups per row
     size_t fused_grid;            // workgroups of the fused kernel
     size_t control_words;         // header, ratio, pstat, qstat, spart, rpart: in ints, at offset 0, zero between calls
-    size_t off_ratio, off_rowstat, off_pstat, off_qstat, off_spart, off_rpart;
+    size_t off_ratio, off_lw, off_rowstat, off_pstat, off_qstat, off_spart, off_rpart;
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -52,6 +52,7 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.fused_ok = L.nu <= kMaxUnitsPerRow && L.fused_grid <= 0x7fffffffull;
     size_t off = kHdrWords * sizeof(int);
     L.off_ratio = off;  off += rows_d * sizeof(u64);
+    L.off_lw = off;     off += rows_d * sizeof(u64);
     L.off_rowstat = off; off += rows_d * 3 * sizeof(u64);
     L.off_pstat = off;  off += rows_t * L.nu * sizeof(u64);
     L.off_qstat = off;  off += rows_d * L.nu * sizeof(u64);
@@ -150,6 +151,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.header = reinterpret_cast<int *>(ws);
     P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
     P.rowstat = reinterpret_cast<u64 *>(ws + L.off_rowstat);
+    P.lw = reinterpret_cast<u64 *>(ws + L.off_lw);
     P.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
     P.qstat = reinterpret_cast<u64 *>(ws + L.off_qstat);
     P.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);

@@ -118,6 +118,9 @@ SHAPES = [
     (7, 64, 1000, "f32"),        # the longest draft block the library takes
     (1, 8, 128256, "bf16"),      # one sequence of the headline shape
     (33, 6, 32000, "bf16"),
+    (2, 2, 140001, "bf16"),      # rows of more than 64 wave chunks (two row words per lane), unaligned
+    (1, 2, 300000, "f32"),       # more than 128 wave chunks (four row words per lane)
+    (1, 1, 600008, "bf16"),      # more than 256 wave chunks (eight row words per lane)
 ]
 
 
