@@ -18,8 +18,8 @@
 //      ratios of the earlier rows, which give w_i (Alg. 2: w_i = min(w_{i-1} r_i, 1)); the row's
 //      first unit publishes the row's ratio and normalisers,
 //   4. forms its share of S_i from the registers and publishes it.
-// Workgroups start position-major inside groups of sequences (the last target rows, then all
-// row pairs of position 0, then position 1, ...), so the ratio of an earlier position was
+// Workgroups start position-major inside groups of sequences (all row pairs of position 0, then
+// position 1, ..., then the last target rows), so the ratio of an earlier position was
 // published long before a later one asks for it, and a unit only ever waits for the units of
 // its own row, which start next to it.  The first unit of a sequence's last row pair then
 // finishes the sequence in the same wave: it waits for all of the sequence's partial sums and
@@ -216,10 +216,11 @@ struct Unit {
     bool last_row;
 };
 
-// Workgroup order: groups of `group_seqs` sequences; inside a group first the last target rows
-// (which have no draft row), then the row pairs position-major (position, sequence, chunk).
+// Workgroup order: groups of `group_seqs` sequences; inside a group the row pairs position-major
+// (position, sequence, chunk), then the last target rows (which have no draft row and wait for
+// nothing: a light last generation while the sequences are being finished).
 // The grid spells this out, (x, y, z) = (chunk / 4, sequence in group, group * (gamma + 1) + slot)
-// with slot 0 for the last target row and 1 + i for position i; x runs fastest in the start order.
+// with slot i for position i and slot gamma for the last target row; x runs fastest in the start order.
 // Returns false for the padding of a last, smaller group.
 __device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit &U)
 {
@@ -227,8 +228,8 @@ __device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit
     if (P.B > P.group_seqs) { grp = blockIdx.z / (P.gamma + 1); slot = blockIdx.z - grp * (P.gamma + 1); }
     U.b = grp * P.group_seqs + blockIdx.y;
     U.c = blockIdx.x * kWaves + wave;
-    U.last_row = slot == 0;
-    U.i = U.last_row ? P.gamma : slot - 1;
+    U.last_row = slot == P.gamma;
+    U.i = slot;
     return U.b < P.B;
 }
 
@@ -752,8 +753,8 @@ void fused_verify_kernel(const FusedParams P)
     }
     SV_STAMP(4);
 
-    // the first unit of a sequence's last row pair finishes the sequence: the earlier positions and the
-    // last target row come before it in the workgroup order
+    // the first unit of a sequence's last row pair finishes the sequence: the earlier positions come before
+    // it in the workgroup order, the last target row (needed only if every token is accepted) right after
     if (U.i == gamma - 1 && U.c == 0) {
         SV_STAMP(5);
         finalize_sequence<T, ALIGNED, GREEDY>(P, U.b);
