@@ -675,45 +675,55 @@ void fused_verify_kernel(const FusedParams P)
     __builtin_amdgcn_s_setprio(3);
     SV_STAMP(1);
 
-    // ---- the words of this row's units give L_p and L_q; the ratios of the earlier rows give w_i
+    // ---- L_p, L_q and w_i.  The row's first unit collects the words of all units of the row, combines them
+    // and publishes the normalisers (and the row's ratio and w_{i+1}); the other units wait for those two
+    // words instead of repeating the combination.  log2 w_i comes from the first unit of the previous
+    // position (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
     bool gave_up = false;
-    RowWords<NW> pw, qw;
-    load_row_words<NW>(P.pstat + trow * nu, nu, pw);
-    load_row_words<NW>(P.qstat + drow * nu, nu, qw);
-    // log2 w_i as the first unit of the previous position published it (Alg. 2: w_i = min(w_{i-1} r_i, 1))
     const bool need_w = P.algo != kToken && U.i > 0;
     const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
-    u64 wt = 1;
-    if (need_w) wt = ld_u64(lw_word);
-    float Mp, Mq;
-    const double Lp = row_normaliser<NW>(P.pstat + trow * nu, nu, P.spin_limit, gave_up, Mp, pw);
-    const double Lq = row_normaliser<NW>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
-    SV_STAMP(2);
-    double lr = 0.0;
+    double Lp, Lq, log2w = 0.0;
     if (U.c == 0) {
-        // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), published for whoever finishes the sequence.  The
-        // sweeps scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that
-        // moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
-        // row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
+        RowWords<NW> pw, qw;
+        load_row_words<NW>(P.pstat + trow * nu, nu, pw);
+        load_row_words<NW>(P.qstat + drow * nu, nu, qw);
+        u64 wt = 1;
+        if (need_w) wt = ld_u64(lw_word);
+        float Mp, Mq;
+        Lp = row_normaliser<NW>(P.pstat + trow * nu, nu, P.spin_limit, gave_up, Mp, pw);
+        Lq = row_normaliser<NW>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
+        // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for whoever finishes the sequence.  The sweeps
+        // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that moves a
+        // row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the row
+        // maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
         const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
         const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-        lr = lp - lq;
+        const double lr = lp - lq;
         if (lane == 0) {
-            st_u64(P.ratio + drow, pack_ratio(lr));
-            // the row's normalisers, also for the finisher
             st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
             st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
             st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
+            st_u64(P.ratio + drow, pack_ratio(lr));
         }
+        if (need_w) log2w = unpack_ratio(wait_word(lw_word, wt, true, P.spin_limit, gave_up));
+        if (P.algo != kToken) {
+            // w_{i+1} for the units of the next position
+            double next = log2w + lr;
+            if (!GREEDY && next > 0.0) next = 0.0;
+            if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
+        }
+    } else {
+        // lanes 0, 1: the row's two normalisers; lane 2: log2 w_i
+        const u64 *word = lane == 0 ? P.rowstat + drow * 3 : lane == 1 ? P.rowstat + drow * 3 + 1 : lw_word;
+        const bool need = lane < 2 || (lane == 2 && need_w);
+        u64 v = 1;
+        if (need) v = ld_u64(word);
+        v = wait_word(word, v, need, P.spin_limit, gave_up);
+        Lp = unpack_ratio(read_lane_u64(v, 0));
+        Lq = unpack_ratio(read_lane_u64(v, 1));
+        if (need_w) log2w = unpack_ratio(read_lane_u64(v, 2));
     }
-    double log2w = 0.0;
-    if (need_w) log2w = unpack_ratio(wait_word(lw_word, wt, true, P.spin_limit, gave_up));
-    if (U.c == 0 && P.algo != kToken) {
-        // w_{i+1} for the units of the next position
-        double next = log2w + lr;
-        if (!GREEDY && next > 0.0) next = 0.0;
-        if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
-    }
+    SV_STAMP(2);
     if (GREEDY) log2w = fmin(log2w, 100.0);                 // keeps w p finite in float
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     SV_STAMP(3);
