@@ -649,9 +649,10 @@ void fused_verify_kernel(const FusedParams P)
     RawSlice<T, ALIGNED> rawA, rawB;
     issue_loads<T, ALIGNED>(rowA, unit_first, V, rawA);
     if (!U.last_row) issue_loads<T, ALIGNED>(rowB, unit_first, V, rawB);
-    // draft token X_{i+1} and its two logits: a row's first unit publishes the row's ratio from them
+    // draft token X_{i+1} and its two logits: the row's leader publishes the row's ratio from them
     double ya = 0.0, yb = 0.0;
-    if (!U.last_row && U.c == 0) {
+    const bool leader = U.c == nu - 1;   // the row's last unit has the fewest logits (often none): it leads the row
+    if (!U.last_row && leader) {
         const int tok = P.tokens[drow];
         ya = logit_as_double(rowA + tok);
         yb = logit_as_double(rowB + tok);
@@ -675,15 +676,15 @@ void fused_verify_kernel(const FusedParams P)
     __builtin_amdgcn_s_setprio(3);
     SV_STAMP(1);
 
-    // ---- L_p, L_q and w_i.  The row's first unit collects the words of all units of the row, combines them
+    // ---- L_p, L_q and w_i.  The row's leader collects the words of all units of the row, combines them
     // and publishes the normalisers (and the row's ratio and w_{i+1}); the other units wait for those two
-    // words instead of repeating the combination.  log2 w_i comes from the first unit of the previous
+    // words instead of repeating the combination.  log2 w_i comes from the leader of the previous
     // position (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
     bool gave_up = false;
     const bool need_w = P.algo != kToken && U.i > 0;
     const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
     double Lp, Lq, log2w = 0.0;
-    if (U.c == 0) {
+    if (leader) {
         RowWords<NW> pw, qw;
         load_row_words<NW>(P.pstat + trow * nu, nu, pw);
         load_row_words<NW>(P.qstat + drow * nu, nu, qw);
