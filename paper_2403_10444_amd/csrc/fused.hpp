@@ -77,7 +77,7 @@ struct FusedParams {
     u64 *rowstat;         // [B, gamma, 3]            L_p, L_q (double bits, lowest bit set), M_p (float bits << 32 | 1)
     u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy), same encoding; not for token verification
     u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
-    u64 *qstat;           // [B, gamma, nu]           same for the draft rows
+    u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
     unsigned *rpart;      // [B, gamma, nu]           greedy only: partial sums of max(q - w p, 0), same encoding
     int32_t *accept_len, *next_token;
@@ -609,10 +609,10 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     for (int e = lane; e < (gamma + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
     for (int e = lane; e < gamma * nu; e += kWave) {
-        st_u64(P.qstat + (size_t)b * gamma * nu + e, 0);
         st_u32(P.spart + (size_t)b * gamma * nu + e, 0);
         if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * gamma * nu + e, 0);
     }
+    for (int e = lane; e < gamma * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * gamma * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * gamma * (nu / kWaves) + e, 0); }
     for (int e = lane; e < gamma; e += kWave) { st_u64(P.ratio + (size_t)b * gamma + e, 0); st_u64(P.lw + (size_t)b * gamma + e, 0); }
     for (int e = lane; e < 3 * gamma; e += kWave) st_u64(P.rowstat + (size_t)b * gamma * 3 + e, 0);
 }
@@ -634,9 +634,6 @@ void fused_verify_kernel(const FusedParams P)
         return;
     }
 #define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
-    // the short serial stretches (issuing the loads; everything after the first sweep) run at high wave
-    // priority, the long first sweep, which has plenty of independent work, at low priority
-    __builtin_amdgcn_s_setprio(3);
     Unit U;
     if (!decode_unit(P, wave, U)) return;
     SV_STAMP(0);
@@ -649,9 +646,11 @@ void fused_verify_kernel(const FusedParams P)
     RawSlice<T, ALIGNED> rawA, rawB;
     issue_loads<T, ALIGNED>(rowA, unit_first, V, rawA);
     if (!U.last_row) issue_loads<T, ALIGNED>(rowB, unit_first, V, rawB);
-    // draft token X_{i+1} and its two logits: the row's leader publishes the row's ratio from them
+    // draft token X_{i+1} and its two logits: the first wave of the row's last workgroup (the one with the
+    // fewest logits) publishes the row's ratio from them
     double ya = 0.0, yb = 0.0;
-    const bool leader = U.c == nu - 1;   // the row's last unit has the fewest logits (often none): it leads the row
+    const int nwg = nu / kWaves;
+    const bool leader = wave == 0 && (int)blockIdx.x == nwg - 1;
     if (!U.last_row && leader) {
         const int tok = P.tokens[drow];
         ya = logit_as_double(rowA + tok);
@@ -659,74 +658,80 @@ void fused_verify_kernel(const FusedParams P)
     }
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
+    __shared__ u64 wave_words[2][kWaves];
+    __shared__ double row_values[3];
     float xa[kLaneLogits], xb[kLaneLogits];
     float shiftA, shiftB;
-    __builtin_amdgcn_s_setprio(0);
     unpack_slice<T, ALIGNED>(rowA, unit_first, V, rawA, xa);
     {
         const u64 stA = first_sweep_row(xa, k, shiftA);
-        if (lane == 0) st_u64(P.pstat + trow * nu + U.c, stA);
+        if (lane == 0) { st_u64(P.pstat + trow * nu + U.c, stA); wave_words[0][wave] = stA; }
     }
-    if (U.last_row) return;          // the last target row has no draft row and no residual
+    if (U.last_row) return;          // the last target row has no draft row and no residual (whole workgroup)
     unpack_slice<T, ALIGNED>(rowB, unit_first, V, rawB, xb);
     {
         const u64 stB = first_sweep_row(xb, k, shiftB);
-        if (lane == 0) st_u64(P.qstat + drow * nu + U.c, stB);
+        if (lane == 0) wave_words[1][wave] = stB;
     }
-    __builtin_amdgcn_s_setprio(3);
-    SV_STAMP(1);
+    __syncthreads();
 
-    // ---- L_p, L_q and w_i.  The row's leader collects the words of all units of the row, combines them
-    // and publishes the normalisers (and the row's ratio and w_{i+1}); the other units wait for those two
-    // words instead of repeating the combination.  log2 w_i comes from the leader of the previous
-    // position (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
-    bool gave_up = false;
-    const bool need_w = P.algo != kToken && U.i > 0;
-    const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
-    double Lp, Lq, log2w = 0.0;
-    if (leader) {
+    // ---- L_p, L_q and w_i.  The workgroup's first wave combines the four waves' words into the
+    // workgroup's two words, publishes them, collects the words of all workgroups of the row and combines
+    // those; the other three waves sleep at the barrier meanwhile.  The row's leader also publishes the
+    // row's ratio, normalisers and w_{i+1}.  log2 w_i comes from the leader of the previous position
+    // (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
+    if (wave == 0) {
+        SV_STAMP(1);
+        bool gave_up = false;
+        StatAcc ga, gb;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) { ga.add(wave_words[0][w]); gb.add(wave_words[1][w]); }
+        if (lane == 0) {
+            st_u64(P.pgrp + drow * nwg + blockIdx.x, pack_stat(ga.m, ga.z));
+            st_u64(P.qgrp + drow * nwg + blockIdx.x, pack_stat(gb.m, gb.z));
+        }
+        const bool need_w = P.algo != kToken && U.i > 0;
+        const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
         RowWords<NW> pw, qw;
-        load_row_words<NW>(P.pstat + trow * nu, nu, pw);
-        load_row_words<NW>(P.qstat + drow * nu, nu, qw);
+        load_row_words<NW>(P.pgrp + drow * nwg, nwg, pw);
+        load_row_words<NW>(P.qgrp + drow * nwg, nwg, qw);
         u64 wt = 1;
         if (need_w) wt = ld_u64(lw_word);
         float Mp, Mq;
-        Lp = row_normaliser<NW>(P.pstat + trow * nu, nu, P.spin_limit, gave_up, Mp, pw);
-        Lq = row_normaliser<NW>(P.qstat + drow * nu, nu, P.spin_limit, gave_up, Mq, qw);
-        // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for whoever finishes the sequence.  The sweeps
-        // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that moves a
-        // row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the row
-        // maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
-        const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
-        const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-        const double lr = lp - lq;
-        if (lane == 0) {
-            st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
-            st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
-            st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
-            st_u64(P.ratio + drow, pack_ratio(lr));
+        const double Lp = row_normaliser<NW>(P.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
+        const double Lq = row_normaliser<NW>(P.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
+        double lr = 0.0;
+        if (leader) {
+            // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for whoever finishes the sequence.  The sweeps
+            // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that moves a
+            // row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the row
+            // maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
+            const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
+            const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
+            lr = lp - lq;
+            if (lane == 0) {
+                st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
+                st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
+                st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
+                st_u64(P.ratio + drow, pack_ratio(lr));
+            }
         }
+        double log2w = 0.0;
         if (need_w) log2w = unpack_ratio(wait_word(lw_word, wt, true, P.spin_limit, gave_up));
-        if (P.algo != kToken) {
-            // w_{i+1} for the units of the next position
+        if (leader && P.algo != kToken) {
+            // w_{i+1} for the workgroups of the next position
             double next = log2w + lr;
             if (!GREEDY && next > 0.0) next = 0.0;
             if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
         }
-    } else {
-        // lanes 0, 1: the row's two normalisers; lane 2: log2 w_i
-        const u64 *word = lane == 0 ? P.rowstat + drow * 3 : lane == 1 ? P.rowstat + drow * 3 + 1 : lw_word;
-        const bool need = lane < 2 || (lane == 2 && need_w);
-        u64 v = 1;
-        if (need) v = ld_u64(word);
-        v = wait_word(word, v, need, P.spin_limit, gave_up);
-        Lp = unpack_ratio(read_lane_u64(v, 0));
-        Lq = unpack_ratio(read_lane_u64(v, 1));
-        if (need_w) log2w = unpack_ratio(read_lane_u64(v, 2));
+        if (lane == 0) { row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w; }
+        if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
+        SV_STAMP(2);
     }
-    SV_STAMP(2);
+    __syncthreads();
+    const double Lp = row_values[0], Lq = row_values[1];
+    double log2w = row_values[2];
     if (GREEDY) log2w = fmin(log2w, 100.0);                 // keeps w p finite in float
-    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     SV_STAMP(3);
 
     // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq with wave-uniform cp, cq

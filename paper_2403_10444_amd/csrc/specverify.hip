@@ -30,8 +30,8 @@ struct Layout {
     bool fused_ok;
     int nu;                       // wave chunks per row = 4 * workgroups per row
     size_t fused_grid;            // workgroups of the fused kernel
-    size_t control_words;         // header, ratio, pstat, qstat, spart, rpart: in ints, at offset 0, zero between calls
-    size_t off_ratio, off_lw, off_rowstat, off_pstat, off_qstat, off_spart, off_rpart;
+    size_t control_words;         // header and all words that cross waves: in ints, at offset 0, zero between calls
+    size_t off_ratio, off_lw, off_rowstat, off_pstat, off_pgrp, off_qgrp, off_spart, off_rpart;
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -55,7 +55,8 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.off_lw = off;     off += rows_d * sizeof(u64);
     L.off_rowstat = off; off += rows_d * 3 * sizeof(u64);
     L.off_pstat = off;  off += rows_t * L.nu * sizeof(u64);
-    L.off_qstat = off;  off += rows_d * L.nu * sizeof(u64);
+    L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
+    L.off_qgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
     L.off_rpart = off;  off += rows_d * L.nu * sizeof(unsigned);
     L.control_words = off / sizeof(int);
@@ -122,13 +123,12 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                          hipStream_t stream)
 {
     // the instantiation for this row width (1, 2, 4 or 8 words of a row per lane) and its resident workgroups
-    static int cap[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    static int cap[2][2] = {{0, 0}, {0, 0}};
     const bool greedy = algo == kGreedy;
-    const int nw_log = L.nu <= kWave ? 0 : L.nu <= 2 * kWave ? 1 : L.nu <= 4 * kWave ? 2 : 3;
+    const int nwg = L.nu / kWaves;                // a row's workgroup words: one or two per lane of the collecting wave
+    const int nw_log = nwg <= kWave ? 0 : 1;
     void (*kernel)(const FusedParams) = nullptr;
-#define SV_PICK(G)                                                                     \
-    (nw_log == 0 ? fused_verify_kernel<T, ALIGNED, G, 1> : nw_log == 1 ? fused_verify_kernel<T, ALIGNED, G, 2> \
-     : nw_log == 2 ? fused_verify_kernel<T, ALIGNED, G, 4> : fused_verify_kernel<T, ALIGNED, G, 8>)
+#define SV_PICK(G) (nw_log == 0 ? fused_verify_kernel<T, ALIGNED, G, 1> : fused_verify_kernel<T, ALIGNED, G, 2>)
     kernel = greedy ? SV_PICK(true) : SV_PICK(false);
 #undef SV_PICK
     const int capacity = resident_workgroups(kernel, cap[greedy ? 1 : 0][nw_log]);
@@ -153,7 +153,8 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.rowstat = reinterpret_cast<u64 *>(ws + L.off_rowstat);
     P.lw = reinterpret_cast<u64 *>(ws + L.off_lw);
     P.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
-    P.qstat = reinterpret_cast<u64 *>(ws + L.off_qstat);
+    P.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
+    P.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
     P.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
     P.rpart = reinterpret_cast<unsigned *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
