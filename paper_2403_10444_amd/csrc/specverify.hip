@@ -198,13 +198,14 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
                                        accept_len, next_token, debug_out, stream)                            \
                     : FN<bf16_t, false>(algo, target, draft, tokens, uniforms, B, gamma, V, k, kd, L, ws,        \
                                         accept_len, next_token, debug_out, stream)))
-    // the fused kernel (every logit read once, but units wait for their row) is the default up to 2 GiB of
-    // logits; beyond that the staged kernels (every logit read twice, at streaming speed) are as fast or
-    // faster, and they also take the sizes the fused kernel does not
-    const size_t logit_bytes = (size_t)B * (2 * (size_t)gamma + 1) * (size_t)V * esize;
-    if (path == 2 || (path == 0 && L.fused_ok && logit_bytes <= ((size_t)2 << 30))) {
+    // the fused kernel (every logit read once) is the default; the staged kernels (every logit read twice)
+    // take the shapes it does not: rows of more than kMaxUnitsPerRow wave chunks, or rows too wide to fit
+    // four times into the device's resident set
+    if (path != 1 && L.fused_ok) {
         const sv_status_t st = SV_DISPATCH(launch_fused);
         if (st != SV_ERR_UNSUPPORTED || path == 2) return st;
+    } else if (path == 2) {
+        return SV_ERR_UNSUPPORTED;
     }
     return SV_DISPATCH(launch_staged);
 #undef SV_DISPATCH

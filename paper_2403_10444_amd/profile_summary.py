@@ -24,10 +24,10 @@ def _ours(name: str) -> bool:
 
 
 def _short(name: str) -> str:
-    m = re.search(r"(\w+_kernel)", name)
-    base = m.group(1) if m else name[:40]
-    t = name.split("<", 1)[1].rsplit(">", 1)[0] if "<" in name else ""
-    return base + ("<" + t.replace("sv::", "") + ">" if t else "")
+    m = re.search(r"(\w+_kernel)(<[^(]*>)?", name)
+    if not m:
+        return name[:40]
+    return m.group(1) + (m.group(2) or "").replace("sv::", "").replace("(anonymous namespace)::", "")
 
 
 def stats(path: str, command: str) -> str:
