@@ -137,8 +137,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(cfg.name, args.algo) if args.path == "default" else None,
-                     "kernel": "whole call: fused_verify_kernel, the call's only kernel, on the default path up to "
-                               "2 GiB of logits; four staged kernels beyond or with --path staged",
+                     "kernel": "whole call: fused_verify_kernel, the call's only kernel on the default path "
+                               "(four staged kernels with --path staged)",
                      "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms},
     }
     if not args.no_cpu_baseline:

@@ -8,24 +8,25 @@
 //
 // A *unit* is 2048 contiguous logits of a (target row i, draft row i) pair - the last target
 // row, which has no draft row, counts as a pair without its second half - and belongs to one
-// wavefront; a workgroup is four independent waves (four neighbouring units; no LDS, no
-// barrier).  A wave
+// wavefront; a workgroup is four waves (four neighbouring units).  A wave
 //   1. loads its 2 x 2048 logits (32 + 32 per lane, 16-byte loads, 1 KB per load instruction),
 //   2. turns them into exp2(y - shift) with a wave-uniform shift per row and KEEPS those 2 x 32
-//      floats per lane in registers; publishes the unit's partial normalisers (shift, sum) as
-//      two words,
-//   3. waits for the words of the other units of its row, which give L_p and L_q, and reads the
-//      ratios of the earlier rows, which give w_i (Alg. 2: w_i = min(w_{i-1} r_i, 1)); the row's
-//      first unit publishes the row's ratio and normalisers,
+//      floats per lane in registers; its partial normalisers (shift, sum) meet those of the
+//      workgroup's other waves in LDS,
+//   3. sleeps at a barrier while the workgroup's first wave publishes the workgroup's two words,
+//      waits for the words of the other workgroups of the row, which give L_p and L_q, and for
+//      log2 w_i, which the previous position's leader published (Alg. 2: w_i = min(w_{i-1} r_i, 1));
+//      the first wave of the row's last workgroup is the row's leader: it also publishes the
+//      row's ratio, normalisers and log2 w_{i+1},
 //   4. forms its share of S_i from the registers and publishes it.
 // Workgroups start position-major inside groups of sequences (all row pairs of position 0, then
-// position 1, ..., then the last target rows), so the ratio of an earlier position was
-// published long before a later one asks for it, and a unit only ever waits for the units of
-// its own row, which start next to it.  The first unit of a sequence's last row pair then
-// finishes the sequence in the same wave: it waits for all of the sequence's partial sums and
-// runs the accept tests and the inverse-CDF draw.
+// position 1, ..., then the last target rows), so what an earlier position publishes is there
+// long before a later one asks for it, and a workgroup only ever waits for the workgroups of
+// its own row, which start next to it.  The first wave of a sequence's last row pair then
+// finishes the sequence: it waits for all of the sequence's partial sums and runs the accept
+// tests and the inverse-CDF draw.
 //
-// Everything that crosses waves is a self-announcing word: it is zero between calls and
+// Everything that crosses workgroups is a self-announcing word: it is zero between calls and
 // non-zero once written (a packed (shift, sum) pair always has a non-zero sum or a -inf shift;
 // ratio words and partial sums get their lowest mantissa bit set).  Words are written and read
 // with agent-scope atomic accesses, which go through to device memory instead of living in one
