@@ -132,6 +132,29 @@ __device__ __forceinline__ float wave_max(float v)
     asm volatile(SV_DPP_REDUCE("v_max_f32_dpp") : "+v"(v));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
+
+// The same over each half of the wave (lanes 0..31 and 32..63) at once: five steps; lane 31 ends up with
+// the first half's result, lane 63 with the second half's.
+#define SV_DPP_REDUCE_HALVES(OP)                                                                \
+    "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"          \
+    "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"          \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"              \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"                   \
+    "s_nop 1\n\t" OP " %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"                 \
+    "s_nop 1"
+__device__ __forceinline__ void halves_sum(float v, float &first, float &second)
+{
+    asm volatile(SV_DPP_REDUCE_HALVES("v_add_f32_dpp") : "+v"(v));
+    first = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+    second = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ void halves_max(float v, float &first, float &second)
+{
+    asm volatile(SV_DPP_REDUCE_HALVES("v_max_f32_dpp") : "+v"(v));
+    first = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+    second = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+#undef SV_DPP_REDUCE_HALVES
 #undef SV_DPP_REDUCE
 
 __device__ __forceinline__ double wave_sum_double(double v)

@@ -693,14 +693,40 @@ void fused_verify_kernel(const FusedParams P)
         }
         const bool need_w = P.algo != kToken && U.i > 0;
         const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
-        RowWords<NW> pw, qw;
-        load_row_words<NW>(P.pgrp + drow * nwg, nwg, pw);
-        load_row_words<NW>(P.qgrp + drow * nwg, nwg, qw);
         u64 wt = 1;
-        if (need_w) wt = ld_u64(lw_word);
         float Mp, Mq;
-        const double Lp = row_normaliser<NW>(P.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
-        const double Lq = row_normaliser<NW>(P.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
+        double Lp, Lq;
+        if (nwg <= kWave / 2) {
+            // one poll covers the row: the target row's words in lanes 0.., the draft row's in lanes 32..,
+            // log2 w_i beside them; the two halves of the wave are then combined side by side
+            const int e = lane & 31;
+            const bool need = e < nwg;
+            const u64 *word = (lane < 32 ? P.pgrp : P.qgrp) + drow * nwg + (need ? e : nwg - 1);
+            u64 v = ld_u64(word);
+            if (need_w) wt = ld_u64(lw_word);
+            int spins = 0;
+            while (__any((need && v == 0) || wt == 0)) {
+                if (++spins > P.spin_limit) { gave_up = true; break; }
+                __builtin_amdgcn_s_sleep(1);
+                if (need && v == 0) v = ld_u64(word);
+                if (wt == 0) wt = ld_u64(lw_word);
+            }
+            StatAcc acc;
+            if (need) acc.add(v);
+            halves_max(acc.m, Mp, Mq);
+            const float Mh = lane < 32 ? Mp : Mq;
+            float zp, zq;
+            halves_sum(acc.m > -INFINITY ? acc.z * fast_exp2(acc.m - Mh) : 0.f, zp, zq);
+            Lp = (double)Mp + log2_precise(zp);
+            Lq = (double)Mq + log2_precise(zq);
+        } else {
+            RowWords<NW> pw, qw;
+            load_row_words<NW>(P.pgrp + drow * nwg, nwg, pw);
+            load_row_words<NW>(P.qgrp + drow * nwg, nwg, qw);
+            if (need_w) wt = ld_u64(lw_word);
+            Lp = row_normaliser<NW>(P.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
+            Lq = row_normaliser<NW>(P.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
+        }
         double lr = 0.0;
         if (leader) {
             // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for whoever finishes the sequence.  The sweeps
