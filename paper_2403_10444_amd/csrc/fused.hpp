@@ -411,6 +411,17 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
         if (GREEDY) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
     }
     FSTAMP(8);
+    // what the accept tests need of w_j is formed now, before the wait for the partial sums: lane l tests
+    // position j = l + 1, whose row values sit in lane j
+    const float *eta = P.uniforms + (size_t)b * (gamma + 1);
+    const int j = lane + 1;
+    const double lw_below = __shfl_down(my_lw, 1, kWave);
+    const double lw_j = j < gamma ? lw_below : lw_last;
+    const double w_j = exp2(lw_j);
+    const double one_minus_w = -expm1(lw_j * 0.69314718055994530942);
+    const double h_token = exp2(fmin(my_lr, 0.0));      // min(r_j, 1); lane l holds log2 r_{l+1}
+    const float eta_j = eta[j <= gamma ? j - 1 : 0];
+
     // ---- S_j (and, greedy, the rejected mass) = sum of row j's partial sums, into lane j.  kept[jj]
     // holds this lane's partial sum of row jj when gamma <= kBatch (used again for the draw).
     float my_S = 0.f, my_R = 0.f, kept[kBatch];
@@ -447,25 +458,20 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     }
 
     FSTAMP(9);
-    // ---- accept tests eta_j < h_j: lane l tests position j = l + 1, whose row values sit in lane j
-    const float *eta = P.uniforms + (size_t)b * (gamma + 1);
-    const int j = lane + 1;
-    const double lw_next = __shfl_down(my_lw, 1, kWave);
-    const double lw_j = j < gamma ? lw_next : lw_last;
+    // ---- accept tests eta_j < h_j
     const double S_row = (double)__shfl_down(my_S, 1, kWave), R_row = (double)__shfl_down(my_R, 1, kWave);
     bool pass = false;
     if (j <= gamma) {
-        const double w = exp2(lw_j);
-        const double S = j < gamma ? S_row : w;          // q_gamma == 0: S_gamma = w_gamma
+        const double S = j < gamma ? S_row : w_j;        // q_gamma == 0: S_gamma = w_gamma
         double h;
-        if (P.algo == kToken) h = exp2(fmin(my_lr, 0.0));                                  // min(r_j, 1); lane l holds log2 r_{l+1}
-        else if (j == gamma) h = fmin(w, 1.0);                                             // h_gamma = w_gamma
+        if (P.algo == kToken) h = h_token;
+        else if (j == gamma) h = fmin(w_j, 1.0);                                           // h_gamma = w_gamma
         else if (GREEDY) h = R_row > 0.0 ? fmin(S / R_row, 1.0) : 1.0;                     // p_remain / p_rej
-        else h = lw_j >= 0.0 ? 1.0 : S / (S - expm1(lw_j * 0.69314718055994530942));       // S / (S + 1 - w)
-        pass = (double)eta[j - 1] < h;
+        else h = lw_j >= 0.0 ? 1.0 : S / (S + one_minus_w);                                // S / (S + 1 - w)
+        pass = (double)eta_j < h;
         if (P.debug_out) {
             float *d = P.debug_out + (base + j) * 3;
-            d[0] = (float)w; d[1] = (float)S; d[2] = (float)h;
+            d[0] = (float)w_j; d[1] = (float)S; d[2] = (float)h;
         }
     }
     if (lane == 0 && P.debug_out) {
