@@ -223,12 +223,16 @@ struct Unit {
 // The grid spells this out, (x, y, z) = (chunk / 4, sequence in group, group * (gamma + 1) + slot)
 // with slot i for position i and slot gamma for the last target row; x runs fastest in the start order.
 // Returns false for the padding of a last, smaller group.
-__device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit &U)
+__device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit &U, int &x)
 {
     int grp = 0, slot = blockIdx.z;
     if (P.B > P.group_seqs) { grp = blockIdx.z / (P.gamma + 1); slot = blockIdx.z - grp * (P.gamma + 1); }
     U.b = grp * P.group_seqs + blockIdx.y;
-    U.c = blockIdx.x * kWaves + wave;
+    // which of the row's workgroups takes which chunk rotates from row to row: a row's workgroups go to the
+    // XCDs round-robin, and the last chunk (fewest logits, leader's duties) must not always meet the same XCD
+    const int wpr = gridDim.x;
+    x = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % wpr);
+    U.c = x * kWaves + wave;
     U.last_row = slot == P.gamma;
     U.i = slot;
     return U.b < P.B;
@@ -642,7 +646,8 @@ void fused_verify_kernel(const FusedParams P)
     }
 #define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
     Unit U;
-    if (!decode_unit(P, wave, U)) return;
+    int wg_x;
+    if (!decode_unit(P, wave, U, wg_x)) return;
     SV_STAMP(0);
 
     // stream A: the unit's chunk of target row i; stream B: the same chunk of draft row i (none for the last row)
@@ -655,14 +660,10 @@ void fused_verify_kernel(const FusedParams P)
     if (!U.last_row) issue_loads<T, ALIGNED>(rowB, unit_first, V, rawB);
     // draft token X_{i+1} and its two logits: the first wave of the row's last workgroup (the one with the
     // fewest logits) publishes the row's ratio from them
-    double ya = 0.0, yb = 0.0;
     const int nwg = nu / kWaves;
-    const bool leader = wave == 0 && (int)blockIdx.x == nwg - 1;
-    if (!U.last_row && leader) {
-        const int tok = P.tokens[drow];
-        ya = logit_as_double(rowA + tok);
-        yb = logit_as_double(rowB + tok);
-    }
+    const bool leader = wave == 0 && wg_x == nwg - 1;
+    int tok = 0;
+    if (!U.last_row && leader) tok = P.tokens[drow];
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     __shared__ u64 wave_words[2][kWaves];
@@ -675,6 +676,9 @@ void fused_verify_kernel(const FusedParams P)
         if (lane == 0) { st_u64(P.pstat + trow * nu + U.c, stA); wave_words[0][wave] = stA; }
     }
     if (U.last_row) return;          // the last target row has no draft row and no residual (whole workgroup)
+    // the two logits of the draft token, asked for only now so that the streams above did not queue behind them
+    double ya = 0.0, yb = 0.0;
+    if (leader) { ya = logit_as_double(rowA + tok); yb = logit_as_double(rowB + tok); }
     unpack_slice<T, ALIGNED>(rowB, unit_first, V, rawB, xb);
     {
         const u64 stB = first_sweep_row(xb, k, shiftB);
@@ -694,8 +698,8 @@ void fused_verify_kernel(const FusedParams P)
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) { ga.add(wave_words[0][w]); gb.add(wave_words[1][w]); }
         if (lane == 0) {
-            st_u64(P.pgrp + drow * nwg + blockIdx.x, pack_stat(ga.m, ga.z));
-            st_u64(P.qgrp + drow * nwg + blockIdx.x, pack_stat(gb.m, gb.z));
+            st_u64(P.pgrp + drow * nwg + wg_x, pack_stat(ga.m, ga.z));
+            st_u64(P.qgrp + drow * nwg + wg_x, pack_stat(gb.m, gb.z));
         }
         const bool need_w = P.algo != kToken && U.i > 0;
         const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
