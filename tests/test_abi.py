@@ -95,3 +95,12 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros((1, 2, 8))
     with pytest.raises(ValueError):
         sv.spec_verify_block(t, t[:, :1], torch.zeros((1, 1), dtype=torch.int32), torch.zeros((1, 2)), 1.0)
+
+
+def test_copy_probe_validates_its_arguments():
+    lib = sv.load()
+    assert lib.spec_verify_debug_copy(None, 0x1000, 256, None) == binding.SV_ERR_INVALID_ARG
+    assert lib.spec_verify_debug_copy(0x1000, None, 256, None) == binding.SV_ERR_INVALID_ARG
+    assert lib.spec_verify_debug_copy(0x1000, 0x2000, 0, None) == binding.SV_ERR_INVALID_ARG
+    assert lib.spec_verify_debug_copy(0x1000, 0x2000, 24, None) == binding.SV_ERR_INVALID_ARG      # not a multiple of 16
+    assert lib.spec_verify_debug_copy(0x1008, 0x2000, 256, None) == binding.SV_ERR_INVALID_ARG    # misaligned

@@ -220,6 +220,37 @@ def test_runs_on_a_side_stream():
     assert np.array_equal(tau.cpu().numpy(), ref["accept_len"]) and np.array_equal(y.cpu().numpy(), ref["next_token"])
 
 
+def test_captured_in_a_graph_and_replayed():
+    """A call is kernel launches only (no allocation, no memset), so it can be captured; every replay, with
+    eager calls and synchronisations in between, must give what the eager call gives on the same inputs."""
+    cfg = _custom(6, 5, 40000, "bf16")
+    sets = [workloads.generate(cfg, seed=200 + i, device=DEV) for i in range(3)]
+    static = {k: v.clone() for k, v in sets[0].items() if torch.is_tensor(v)}
+    ws = sv.alloc_workspace(cfg.B, cfg.gamma, cfg.V, DEV)
+    tau = torch.empty(cfg.B, dtype=torch.int32, device=DEV)
+    y = torch.empty(cfg.B, dtype=torch.int32, device=DEV)
+
+    def call():
+        sv.spec_verify_block(static["target_logits"], static["draft_logits"], static["draft_tokens"],
+                             static["uniforms"], 0.9, workspace=ws, accept_len=tau, next_token=y)
+
+    call()                                   # warm-up outside the capture (one-time occupancy query)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(5):
+        inp = sets[rep % len(sets)]
+        for k in static:
+            static[k].copy_(inp[k])
+        graph.replay()
+        torch.cuda.synchronize()
+        got_tau, got_y = tau.cpu().numpy().copy(), y.cpu().numpy().copy()
+        ref = parity.run_gpu("block", inp, 0.9)          # eager call (own workspace) between the replays
+        assert np.array_equal(got_tau, ref["accept_len"]) and np.array_equal(got_y, ref["next_token"]), rep
+    assert sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V) == 0
+
+
 def test_workspace_must_be_initialised_for_the_shape(path):
     if path != "fused":
         pytest.skip("only the fused kernel synchronises through the workspace")
