@@ -101,3 +101,24 @@ def verify(algo: int, target_logits, draft_logits, draft_tokens, uniforms,
         raise RuntimeError(f"oracle_spec_verify failed with code {rc}")
     return {"accept_len": tau, "next_token": y, "dbg": dbg, "margins": margins,
             "n_fallback": int(nfb.value)}
+
+
+def sample_rows(logits, uniforms, temperature: float, dtype: int = F32):
+    """One token per row of ``logits`` [R, V] from softmax(logits / T) by the inverse-CDF walk at
+    ``uniforms`` [R] (the drafting step of the outer loop, Alg. 3).  Returns (tokens, margins)."""
+    lib = _load()
+    lg = _as_logits(logits, dtype)
+    uni = np.ascontiguousarray(uniforms, dtype=np.float32)
+    R, V = lg.shape
+    if uni.shape != (R,):
+        raise ValueError("one uniform per row")
+    tok = np.empty(R, dtype=np.int32)
+    margins = np.empty(R, dtype=np.float64)
+    lib.oracle_sample_rows.restype = ctypes.c_int
+    lib.oracle_sample_rows.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    rc = lib.oracle_sample_rows(lg.ctypes.data, R, V, int(dtype), float(temperature), uni.ctypes.data,
+                                tok.ctypes.data, margins.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_sample_rows failed with code {rc}")
+    return tok, margins

@@ -333,6 +333,37 @@ int oracle_spec_verify(int algo, const void *target_logits, const void *draft_lo
     return 0;
 }
 
+/*
+ * The drafting step of the outer loop of speculative decoding (Alg. 3: "sample X_1..X_gamma from
+ * M_s"), for a model whose conditional distributions are handed over as rows of logits: one token
+ * per row from softmax(logits / T), by the same inverse-CDF walk as the draw of Y (index order,
+ * strict ">", t = u * total).
+ *   logits    [rows, V]  dtype
+ *   uniforms  [rows]     float32 in [0,1)
+ *   tokens    [rows]     out
+ *   margins   [rows]     out or NULL: distance of t to the nearest edge of the token's cell / total
+ * Returns 0, or -1 on a bad argument, -2 when memory runs out.
+ */
+int oracle_sample_rows(const void *logits, long long rows, int V, int dtype, double temperature,
+                       const float *uniforms, int32_t *tokens, double *margins)
+{
+    if (!logits || !uniforms || !tokens) return -1;
+    if (rows < 1 || V < 1 || !(temperature > 0.0) || !isfinite(temperature)) return -1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return -1;
+    double *scaled = (double *)malloc(sizeof(double) * (size_t)V);
+    double *prob = (double *)malloc(sizeof(double) * (size_t)V);
+    if (!scaled || !prob) { free(scaled); free(prob); return -2; }
+    for (long long r = 0; r < rows; ++r) {
+        softmax_row(logits, dtype, (size_t)r * (size_t)V, V, temperature, scaled, prob);
+        double m = 0.0;
+        tokens[r] = inverse_cdf(prob, V, (double)uniforms[r], &m);
+        if (margins) margins[r] = m;
+    }
+    free(scaled);
+    free(prob);
+    return 0;
+}
+
 /* Threads the batched entry point would use for `requested` (<=0: default). */
 int oracle_num_threads(int requested)
 {
