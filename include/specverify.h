@@ -91,6 +91,21 @@ void spec_verify_debug_config(int32_t path, int32_t spin_limit);
  * workgroup, B * (gamma + 1) * ceil(V / 8192) workgroups, and be zeroed by the caller.    */
 void spec_verify_debug_profile(void *device_buffer);
 
+/*
+ * The drafting step of the outer loop of speculative decoding (Alg. 3: "sample X_1 .. X_gamma from
+ * M_s") for a model whose conditional distributions are rows of logits: one token per row from
+ * softmax(logits / temperature) by the inverse CDF in vocabulary order, tokens[r] =
+ * min{x : C_x > uniforms[r] * C_total} (the convention of the correction token's draw).
+ *   logits    [rows, V]  dtype, device, rows dense
+ *   uniforms  [rows]     float32 in [0,1), device
+ *   tokens    [rows]     int32 out, device
+ * Asynchronous on `stream`, allocates nothing.  SV_ERR_INVALID_ARG for null pointers, rows < 1,
+ * V < 1, a temperature that is not positive and finite or an unknown dtype; SV_ERR_UNSUPPORTED
+ * for more than 2^31 - 1 rows.  Meant for toy and test drafters, not tuned.
+ */
+sv_status_t spec_sample_tokens(const void *logits, int64_t rows, int32_t V, sv_dtype_t dtype,
+                               float temperature, const float *uniforms, int32_t *tokens, void *stream);
+
 /* Measurement hook: copies `bytes` (a multiple of 16, both pointers 16-byte aligned device
  * memory, not overlapping) from `src` to `dst` with a plain copy kernel on `stream`.  It reads
  * and writes exactly `bytes` each, which is what hardware counters of memory traffic are

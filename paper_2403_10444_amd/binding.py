@@ -30,6 +30,7 @@ EXPORTED = (
     "spec_verify_debug_config",
     "spec_verify_debug_profile",
     "spec_verify_debug_copy",
+    "spec_sample_tokens",
     "spec_verify_block",
     "spec_verify_token",
     "spec_verify_greedy",
@@ -79,6 +80,9 @@ def load() -> ctypes.CDLL:
         lib.spec_verify_debug_profile.argtypes = [ctypes.c_void_p]
         lib.spec_verify_debug_copy.restype = ctypes.c_int
         lib.spec_verify_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        lib.spec_sample_tokens.restype = ctypes.c_int
+        lib.spec_sample_tokens.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_float,
+                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.spec_verify_status_string.restype = ctypes.c_char_p
         lib.spec_verify_status_string.argtypes = [ctypes.c_int]
         _lib = lib
@@ -129,6 +133,26 @@ def spec_verify_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) ->
     code = load().spec_verify_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream)
     if code != SV_OK:
         raise SpecVerifyError(code, status_string(code))
+
+
+def spec_sample_tokens(logits: torch.Tensor, uniforms: torch.Tensor, temperature: float, tokens=None, stream=None):
+    """One token per row of ``logits`` [..., V] from softmax(logits / T) by the inverse CDF at ``uniforms``
+    [...] (the drafting step of Alg. 3).  Returns int32 tokens of the shape of ``uniforms``."""
+    V = logits.shape[-1]
+    rows = logits.numel() // V
+    if logits.device.type != "cuda" or not logits.is_contiguous() or not uniforms.is_contiguous():
+        raise ValueError("logits and uniforms must be contiguous cuda tensors")
+    if uniforms.numel() != rows or uniforms.dtype != torch.float32:
+        raise ValueError("one float32 uniform per row")
+    if tokens is None:
+        tokens = torch.empty(uniforms.shape, dtype=torch.int32, device=logits.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(logits.device).cuda_stream
+    code = load().spec_sample_tokens(logits.data_ptr(), rows, V, _dtype_code(logits), float(temperature),
+                                     uniforms.data_ptr(), tokens.data_ptr(), stream)
+    if code != SV_OK:
+        raise SpecVerifyError(code, status_string(code))
+    return tokens
 
 
 def alloc_workspace(B: int, gamma: int, V: int, device="cuda") -> torch.Tensor:

@@ -12,6 +12,7 @@
 #include "../../include/specverify.h"
 #include "common.hpp"
 #include "fused.hpp"
+#include "sample.hpp"
 #include "staged.hpp"
 
 namespace {
@@ -266,6 +267,24 @@ sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, voi
     const size_t blocks = (nvec + 255) / 256;
     copy_probe_kernel<<<(unsigned)(blocks < 65536 ? blocks : 65536), 256, 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), nvec);
+    return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
+sv_status_t spec_sample_tokens(const void *logits, int64_t rows, int32_t V, sv_dtype_t dtype, float temperature,
+                               const float *uniforms, int32_t *tokens, void *stream_v)
+{
+    if (!logits || !uniforms || !tokens) return SV_ERR_INVALID_ARG;
+    if (rows < 1 || V < 1) return SV_ERR_INVALID_ARG;
+    if (!(temperature > 0.f) || !isfinite(temperature)) return SV_ERR_INVALID_ARG;
+    if (dtype != SV_DTYPE_F32 && dtype != SV_DTYPE_BF16) return SV_ERR_INVALID_ARG;
+    if (rows > 0x7fffffffll) return SV_ERR_UNSUPPORTED;
+    const float k = (float)(1.4426950408889634074 / (double)temperature);
+    const unsigned threads = V > 8192 ? kThreads : kWave;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (dtype == SV_DTYPE_F32)
+        sample_rows_kernel<float><<<(unsigned)rows, threads, 0, stream>>>(static_cast<const float *>(logits), V, k, uniforms, tokens);
+    else
+        sample_rows_kernel<bf16_t><<<(unsigned)rows, threads, 0, stream>>>(static_cast<const bf16_t *>(logits), V, k, uniforms, tokens);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "specverify.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spec_verify_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(spec_(?:verify|sample)_\w+)\s*\(", text)))
 
 
 def test_header_and_library_agree_on_exports():
@@ -104,3 +104,22 @@ def test_copy_probe_validates_its_arguments():
     assert lib.spec_verify_debug_copy(0x1000, 0x2000, 0, None) == binding.SV_ERR_INVALID_ARG
     assert lib.spec_verify_debug_copy(0x1000, 0x2000, 24, None) == binding.SV_ERR_INVALID_ARG      # not a multiple of 16
     assert lib.spec_verify_debug_copy(0x1008, 0x2000, 256, None) == binding.SV_ERR_INVALID_ARG    # misaligned
+
+
+def test_sample_tokens_validates_its_arguments():
+    lib = sv.load()
+    ok = dict(logits=0x1000, rows=4, V=10, dtype=0, T=1.0, uniforms=0x1000, tokens=0x1000)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lib.spec_sample_tokens(a["logits"], a["rows"], a["V"], a["dtype"], a["T"], a["uniforms"], a["tokens"], None)
+
+    assert call(logits=None) == binding.SV_ERR_INVALID_ARG
+    assert call(uniforms=None) == binding.SV_ERR_INVALID_ARG
+    assert call(tokens=None) == binding.SV_ERR_INVALID_ARG
+    assert call(rows=0) == binding.SV_ERR_INVALID_ARG
+    assert call(V=0) == binding.SV_ERR_INVALID_ARG
+    assert call(T=0.0) == binding.SV_ERR_INVALID_ARG
+    assert call(T=float("nan")) == binding.SV_ERR_INVALID_ARG
+    assert call(dtype=5) == binding.SV_ERR_INVALID_ARG
+    assert call(rows=1 << 31) == binding.SV_ERR_UNSUPPORTED
