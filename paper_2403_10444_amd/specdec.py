@@ -47,3 +47,35 @@ def toy_speculative_decoding(algo: str, target_logits, draft_logits, gamma: int,
         _VERIFY[algo](tl, dl, x, uv, temperature, workspace=ws, accept_len=tau, next_token=y)
         taus.append(tau.cpu().numpy().copy()); ys.append(y.cpu().numpy().copy()); xs.append(x.cpu().numpy().copy())
     return {"tau": np.stack(taus), "y": np.stack(ys), "x": np.stack(xs)}
+
+
+def _main():
+    """Prints the block efficiency E[tau] + 1 against gamma and the complementary CDF of tau at gamma = 10 for the
+    toy models of Sec. 2 (M_b = (1/3, 2/3), M_s = (2/3, 1/3)), measured on the device."""
+    import workloads
+    mb, ms = np.log(np.array([1 / 3, 2 / 3])), np.log(np.array([2 / 3, 1 / 3]))
+    B, iters = 8192, 32
+
+    def uniforms_for(gamma, seed):
+        def f(it):
+            u = workloads.philox_uniforms(seed * 100003 + it, (B, 2 * gamma + 1))
+            return np.ascontiguousarray(u[:, :gamma]), np.ascontiguousarray(u[:, gamma:])
+        return f
+
+    print(f"toy models of Sec. 2, {B * iters} draws per cell")
+    print("gamma   token   block   greedy   (block efficiency E[tau] + 1)")
+    keep = {}
+    for gamma in (4, 6, 8, 10):
+        row = []
+        for algo in ("token", "block", "greedy"):
+            r = toy_speculative_decoding(algo, mb, ms, gamma, B, iters, 1.0, uniforms_for(gamma, 17))
+            row.append(1.0 + r["tau"].mean())
+            keep[algo, gamma] = r["tau"].reshape(-1)
+        print(f"{gamma:5d}  {row[0]:.4f}  {row[1]:.4f}  {row[2]:.4f}")
+    print("Pr(tau >= k) at gamma = 10, k = 0 .. 10")
+    for algo in ("token", "block"):
+        print(f"{algo:6s}", " ".join(f"{(keep[algo, 10] >= k).mean():.4f}" for k in range(11)))
+
+
+if __name__ == "__main__":
+    _main()
