@@ -13,6 +13,9 @@ namespace sv {
 
 constexpr int kThreads = 256;             // threads per workgroup: 4 wavefronts of 64
 constexpr int kWaves = kThreads / 64;
+// log2 of the ratio r_i never goes below this: a drafted token whose target logit is -inf (masked out by
+// top-k / top-p warping) has r_i = 0, and exp2 of this is exactly 0 in double while sums of it stay finite
+constexpr double kLog2RatioFloor = -1.0e6;
 constexpr int kChunk = 8192;              // logits of one row handled by one workgroup
 constexpr int kWaveChunk = kChunk / kWaves;   // contiguous logits of one row handled by one wavefront
 constexpr int kPerThread = kChunk / kThreads; // logits of one row held by one thread

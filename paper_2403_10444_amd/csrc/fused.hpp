@@ -744,7 +744,7 @@ void fused_verify_kernel(const FusedParams P)
             // maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
             const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
             const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-            lr = lp - lq;
+            lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
             if (lane == 0) {
                 st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
                 st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));

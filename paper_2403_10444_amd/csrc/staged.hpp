@@ -49,12 +49,13 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
         for (int e = 0; e < kVec; ++e) m = fmaxf(m, x[u][e]);
     m = block_max(m, lds);
     const float mk = m * k;
+    const float shift = m > -INFINITY ? mk : 0.f;       // a chunk without a finite logit (masked out, or beyond the row)
 
     float s = 0.f;
 #pragma unroll
     for (int u = 0; u < kU; ++u)
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) s += fast_exp2(__builtin_fmaf(x[u][e], k, -mk));
+        for (int e = 0; e < kVec; ++e) s += fast_exp2(__builtin_fmaf(x[u][e], k, -shift));
     s = block_sum(s, lds);
     if (tid == 0) stats[(size_t)r * nchunks + c] = make_float2(mk, s);
 }
@@ -109,6 +110,7 @@ __global__ __launch_bounds__(64) void prefix_weights_kernel(
             const double ya = logit_as_double(target + ((size_t)b * (gamma + 1) + i) * V + tok) * kd;
             const double yb = logit_as_double(draft + ((size_t)b * gamma + i) * V + tok) * kd;
             log2r = (ya - (L_p[i] + k_eps * (double)M_p[i])) - (yb - (L_q[i] + k_eps * (double)M_q[i]));
+            log2r = fmax(log2r, kLog2RatioFloor);   // a drafted token the target masks out (logit -inf): r = 0, kept finite
             log2w += log2r;
             if (algo != kGreedy && log2w > 0.0) log2w = 0.0;  // the min{., 1}; greedy block verification omits it
         }

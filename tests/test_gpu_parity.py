@@ -220,6 +220,20 @@ def test_runs_on_a_side_stream():
     assert np.array_equal(tau.cpu().numpy(), ref["accept_len"]) and np.array_equal(y.cpu().numpy(), ref["next_token"])
 
 
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+@pytest.mark.parametrize("kt,kd", [(50, 50), (20, 200), (500, 5), (1, 40)])
+def test_masked_logits_top_k(algo, kt, kd):
+    """Rows warped by top-k: everything but the k largest logits is -inf, independently for target and draft,
+    so drafted tokens fall outside the target's support (ratio 0) and units, even whole workgroups, of a
+    row hold no finite logit."""
+    cfg = _custom(16, 6, 20000, "bf16", sigma_t=3.0, sigma_d=1.0, T=0.9)
+    inp = workloads.generate(cfg, seed=300 + kt + kd, device=DEV, top_k_target=kt, top_k_draft=kd)
+    assert torch.isinf(inp["target_logits"]).any() and torch.isinf(inp["draft_logits"]).any()
+    rep = parity.compare(parity.run_gpu(algo, inp, cfg.temperature), parity.run_oracle(algo, inp, cfg.temperature),
+                         label=f"top-k {kt}/{kd}/{algo}", greedy=(algo == "greedy"))
+    _say(rep)
+
+
 def test_captured_in_a_graph_and_replayed():
     """A call is kernel launches only (no allocation, no memset), so it can be captured; every replay, with
     eager calls and synchronisations in between, must give what the eager call gives on the same inputs."""

@@ -112,6 +112,28 @@ def test_lossless_by_enumeration(V, gamma, algo):
     assert worst < 1e-12 + skipped
 
 
+@pytest.mark.parametrize("V,gamma", [(3, 2), (4, 2), (3, 3), (4, 3)])
+@pytest.mark.parametrize("algo", [oracle.BLOCK, oracle.TOKEN])
+def test_lossless_with_masked_tokens(V, gamma, algo):
+    """The same with conditionals in which tokens are masked out (logit -inf, as top-k / top-p warping
+    leaves them), independently in the two models: a drafted token the target excludes has ratio 0 and
+    must never survive, and the output law must still be M_b^{gamma+1}."""
+    rng = np.random.default_rng(77 * V + gamma)
+    Mb = tiny.sparse_tables(rng, V, gamma)
+    Ms = tiny.sparse_tables(rng, V, gamma)
+    law, _, skipped = tiny.output_law(algo, Mb, Ms, V, gamma)
+    assert skipped < 1e-9
+    out = tiny.emitted_law(law, Mb, V, gamma)
+    worst = 0.0
+    for seq in itertools.product(range(V), repeat=gamma + 1):
+        worst = max(worst, abs(out.get(seq, 0.0) - tiny.joint(Mb, seq)))
+    assert worst < 1e-12 + skipped
+    # no accepted prefix contains a token of target probability zero
+    for (xs, tau, y), pr in law.items():
+        if pr > 0:
+            assert all(Mb[xs[:i]][xs[i]] > 0 for i in range(tau)) and Mb[xs[:tau]][y] > 0
+
+
 # ------------------------------------------- Lemma "accept_prob": Pr(tau >= i | X^i) = w_i(x^i)
 def _w_from_definition(Mb, Ms, xs):
     """eq. (def_as) evaluated on the tables: the quantity the lemma speaks about."""

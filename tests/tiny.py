@@ -33,7 +33,8 @@ class TinyModel:
         self.logits, self.prob = {}, {}
         for L in range(depth + 1):
             for prefix in itertools.product(range(V), repeat=L):
-                lg = np.log(np.asarray(requested(prefix), dtype=np.float64)).astype(np.float32)
+                with np.errstate(divide="ignore"):          # a probability of zero is a logit of -inf (a masked token)
+                    lg = np.log(np.asarray(requested(prefix), dtype=np.float64)).astype(np.float32)
                 e = np.exp(lg.astype(np.float64) - float(lg.max()))
                 self.logits[prefix] = lg
                 self.prob[prefix] = e / e.sum()
@@ -45,6 +46,19 @@ class TinyModel:
 def random_tables(rng, V, depth, concentration=0.7):
     """Context-dependent random conditionals (Dirichlet, kept away from zero)."""
     return TinyModel(V, depth, lambda prefix: rng.dirichlet(np.full(V, concentration)) * 0.98 + 0.02 / V)
+
+
+def sparse_tables(rng, V, depth, p_zero=0.35):
+    """Context-dependent random conditionals in which tokens are masked out (probability exactly zero,
+    logit -inf) at random, as top-k / top-p warping does; every conditional keeps at least one token."""
+    def requested(prefix):
+        p = rng.dirichlet(np.full(V, 0.7)) * 0.98 + 0.02 / V
+        keep = rng.random(V) >= p_zero
+        if not keep.any():
+            keep[rng.integers(V)] = True
+        p = np.where(keep, p, 0.0)
+        return p / p.sum()
+    return TinyModel(V, depth, requested)
 
 
 def constant_tables(probs, V, depth):
@@ -79,6 +93,8 @@ def output_law(algo, Mb, Ms, V, gamma):
     dbg_by_draft = {}
     skipped = 0.0
     for xs in itertools.product(range(V), repeat=gamma):
+        if joint(Ms, xs) == 0.0:
+            continue                                        # a draft the drafter never produces
         tl, dl = _rows(Mb, Ms, xs, gamma)
         tok = np.asarray(xs, dtype=np.int32)[None]
         probe = oracle.verify(algo, tl[None], dl[None], tok,

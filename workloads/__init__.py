@@ -81,12 +81,16 @@ def _zipf_bias(cfg: Config, seed: int, device) -> torch.Tensor:
     return bias.to(torch.float32).to(device)
 
 
-def generate(cfg: Config, seed: int, device="cpu", chunk_bytes: int = 1 << 30) -> dict:
+def generate(cfg: Config, seed: int, device="cpu", chunk_bytes: int = 1 << 30,
+             top_k_target: int = 0, top_k_draft: int = 0) -> dict:
     """One call's inputs as torch tensors on `device`.
 
     Returns ``target_logits`` [B, gamma+1, V], ``draft_logits`` [B, gamma, V] (cfg dtype),
     ``draft_tokens`` [B, gamma] int32, ``uniforms`` [B, gamma+1] float32.
     The same (cfg, seed, device type) always gives the same tensors.
+    `top_k_target` / `top_k_draft` > 0 keep only that many largest logits of every target / draft row and
+    set the rest to -inf, the way top-k warping masks a distribution (draft tokens are then drawn from
+    the masked draft rows; a drafted token may fall outside the target's support).
     """
     device = torch.device(device)
     B, g, V = cfg.B, cfg.gamma, cfg.V
@@ -113,6 +117,10 @@ def generate(cfg: Config, seed: int, device="cpu", chunk_bytes: int = 1 << 30) -
         target[b0:b1] = t32.to(dt)
         draft[b0:b1] = d32.to(dt)
         del t32, d32
+        for rows, keep in ((target[b0:b1], top_k_target), (draft[b0:b1], top_k_draft)):
+            if 0 < keep < V:
+                kth = torch.topk(rows.float(), keep, dim=-1).values[..., -1:]
+                rows.masked_fill_(rows.float() < kth, float("-inf"))
         # X_i ~ softmax(draft row i-1 / T), inverse CDF in float64 on the rounded logits
         z = draft[b0:b1].to(torch.float64) / cfg.temperature
         z = torch.softmax(z, dim=-1)
