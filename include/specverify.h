@@ -157,6 +157,24 @@ sv_status_t spec_verify_greedy(const void *target_logits, const void *draft_logi
                                int32_t *accept_len, int32_t *next_token, float *debug_out,
                                void *stream);
 
+/*
+ * The same three algorithms for a batch whose sequences carry drafts of different lengths (what a
+ * serving stack hands over when drafters stop early).  Sequence b uses its first draft_lens[b]
+ * draft positions, 1 <= draft_lens[b] <= gamma: target rows 0 .. draft_lens[b], draft rows and
+ * tokens 0 .. draft_lens[b] - 1, uniforms[b][0 .. draft_lens[b] - 1] for the accept tests and
+ * uniforms[b][draft_lens[b]] for the draw of Y - exactly the result of a call with gamma =
+ * draft_lens[b] on that sequence's leading rows.  `gamma` remains the stride of every array; rows
+ * beyond a sequence's length are never read.  draft_lens is device memory, [B] int32; values
+ * outside 1 .. gamma are the caller's error and are clamped into that range on the device.
+ * accept_len[b] lies in 0 .. draft_lens[b].  Everything else as for spec_verify_block.
+ */
+typedef enum { SV_ALGO_BLOCK = 0, SV_ALGO_TOKEN = 1, SV_ALGO_GREEDY = 2 } sv_algo_t;
+sv_status_t spec_verify_ragged(sv_algo_t algo, const void *target_logits, const void *draft_logits,
+                               const int32_t *draft_tokens, const int32_t *draft_lens, const float *uniforms,
+                               int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                               float temperature, void *workspace, size_t workspace_bytes,
+                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream);
+
 const char *spec_verify_status_string(sv_status_t status);
 
 #ifdef __cplusplus

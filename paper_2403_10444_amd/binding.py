@@ -34,6 +34,7 @@ EXPORTED = (
     "spec_verify_block",
     "spec_verify_token",
     "spec_verify_greedy",
+    "spec_verify_ragged",
     "spec_verify_status_string",
 )
 
@@ -68,6 +69,8 @@ def load() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.restype = ctypes.c_int
             fn.argtypes = _VERIFY_ARGTYPES
+        lib.spec_verify_ragged.restype = ctypes.c_int
+        lib.spec_verify_ragged.argtypes = [ctypes.c_int] + _VERIFY_ARGTYPES[:3] + [ctypes.c_void_p] + _VERIFY_ARGTYPES[3:]
         lib.spec_verify_workspace_init.restype = ctypes.c_int
         lib.spec_verify_workspace_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
                                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
@@ -174,8 +177,11 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
 
 
+SV_ALGO = {"block": 0, "token": 1, "greedy": 2}
+
+
 def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature,
-          workspace=None, accept_len=None, next_token=None, debug_out=None, stream=None):
+          workspace=None, accept_len=None, next_token=None, debug_out=None, stream=None, draft_lens=None, algo=None):
     lib = load()
     B, g1, V = target_logits.shape
     gamma = g1 - 1
@@ -201,8 +207,16 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
         next_token = torch.empty(B, dtype=torch.int32, device=dev)
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
+    head = ()
+    tokens_and_lens = (draft_tokens.data_ptr(),)
+    if draft_lens is not None:
+        if tuple(draft_lens.shape) != (B,) or draft_lens.dtype != torch.int32 or draft_lens.device != dev \
+                or not draft_lens.is_contiguous():
+            raise ValueError("draft_lens must be a contiguous int32 tensor [B] on the inputs' device")
+        head = (SV_ALGO[algo],)
+        tokens_and_lens = (draft_tokens.data_ptr(), draft_lens.data_ptr())
     code = getattr(lib, name)(
-        target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), uniforms.data_ptr(),
+        *head, target_logits.data_ptr(), draft_logits.data_ptr(), *tokens_and_lens, uniforms.data_ptr(),
         B, gamma, V, _dtype_code(target_logits), float(temperature),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         accept_len.data_ptr(), next_token.data_ptr(),
@@ -210,6 +224,13 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
     if code != SV_OK:
         raise SpecVerifyError(code, status_string(code))
     return accept_len, next_token
+
+
+def spec_verify_ragged(algo, target_logits, draft_logits, draft_tokens, draft_lens, uniforms, temperature, **kw):
+    """`algo` ("block", "token" or "greedy") for a batch whose sequence b uses only its first draft_lens[b]
+    draft positions (int32 device tensor [B], values 1 .. gamma); see `spec_verify_ragged` in the header."""
+    return _call("spec_verify_ragged", target_logits, draft_logits, draft_tokens, uniforms, temperature,
+                 draft_lens=draft_lens, algo=algo, **kw)
 
 
 def spec_verify_block(target_logits, draft_logits, draft_tokens, uniforms, temperature, **kw):

@@ -63,6 +63,7 @@ typedef unsigned long long u64;
 struct FusedParams {
     const void *target, *draft;
     const int32_t *tokens;
+    const int32_t *draft_lens;   // NULL, or [B]: sequence b uses its first draft_lens[b] draft positions (1 .. gamma)
     const float *uniforms;
     int B, gamma, V;
     float k;              // float(log2(e) / T): the factor the sweeps multiply logits by
@@ -371,17 +372,18 @@ __device__ __forceinline__ double read_lane_double(double v, int lane)
 // Accept tests and inverse-CDF draw of one sequence (one wave).  What does not need the residual
 // sums (normalisers, ratios, w) is done first, while the sequence's last units are still at work.
 template <typename T, bool ALIGNED, bool GREEDY>
-__device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
+__device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, int gamma)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = kLaneLogits / kVec;
     constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
     const int lane = threadIdx.x & 63;
-    const int gamma = P.gamma, V = P.V, nu = P.nu;
+    // `gamma` is this sequence's draft length; G, the call's (largest) draft length, is the stride of every array
+    const int G = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
     const T *target = static_cast<const T *>(P.target);
     const T *draft = static_cast<const T *>(P.draft);
-    const size_t base = (size_t)b * (gamma + 1);
+    const size_t base = (size_t)b * (G + 1);
     const int e_lane = lane < nu ? lane : nu - 1;
     bool gave_up = false;
 #define FSTAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
@@ -391,7 +393,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     double my_Lp = 0.0, my_Lq = 0.0, my_lr = 0.0;
     float my_Mp = 0.f;
     {
-        const size_t drow = (size_t)b * gamma + (lane < gamma ? lane : gamma - 1);
+        const size_t drow = (size_t)b * G + (lane < gamma ? lane : gamma - 1);
         u64 w0 = ld_u64(P.ratio + drow), w1 = ld_u64(P.rowstat + drow * 3), w2 = ld_u64(P.rowstat + drow * 3 + 1),
             w3 = ld_u64(P.rowstat + drow * 3 + 2);
         w0 = wait_word(P.ratio + drow, w0, lane < gamma, P.spin_limit, gave_up);
@@ -406,7 +408,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     // drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, lw_last = 0.0;
     if (P.algo != kToken) {
-        const u64 *word = P.lw + (size_t)b * gamma + (lane < gamma ? lane : gamma - 1);
+        const u64 *word = P.lw + (size_t)b * G + (lane < gamma ? lane : gamma - 1);
         const double next = unpack_ratio(wait_word(word, ld_u64(word), lane < gamma, P.spin_limit, gave_up));   // log2 w_{lane+1}
         const double prev = __shfl_up(next, 1, kWave);
         my_lw = lane ? prev : 0.0;
@@ -416,7 +418,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     FSTAMP(8);
     // what the accept tests need of w_j is formed now, before the wait for the partial sums: lane l tests
     // position j = l + 1, whose row values sit in lane j
-    const float *eta = P.uniforms + (size_t)b * (gamma + 1);
+    const float *eta = P.uniforms + (size_t)b * (G + 1);
     const int j = lane + 1;
     const double lw_below = __shfl_down(my_lw, 1, kWave);
     const double lw_j = j < gamma ? lw_below : lw_last;
@@ -433,15 +435,15 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
 #pragma unroll
         for (int jj = 0; jj < kBatch; ++jj) {
             const int j = j0 + jj < gamma ? j0 + jj : gamma - 1;
-            sw[jj] = ld_u32(P.spart + ((size_t)b * gamma + j) * nu + e_lane);
-            if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + ((size_t)b * gamma + j) * nu + e_lane);
+            sw[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
+            if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + ((size_t)b * G + j) * nu + e_lane);
         }
 #pragma unroll
         for (int jj = 0; jj < kBatch; ++jj) {
             const int j = j0 + jj;
             kept[jj] = 0.f;
             if (j >= gamma) continue;
-            const size_t drow = (size_t)b * gamma + j;
+            const size_t drow = (size_t)b * G + j;
             float acc = 0.f, rej = 0.f;
             const unsigned w = wait_word32(P.spart + drow * nu + e_lane, sw[jj], lane < nu, P.spin_limit, gave_up);
             if (lane < nu) acc = unpack_partial(w);
@@ -495,7 +497,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     RowCoef rc = {};
     float part0 = 0.f;                                  // this lane's entry `lane` of the row's partial sums
     const u64 *st = P.pstat + (base + tau) * nu;
-    const unsigned *sp = P.spart + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * nu;
+    const unsigned *sp = P.spart + ((size_t)b * G + (tau < gamma ? tau : 0)) * nu;
     if (tau < gamma) {
         Mrow = __shfl(my_Mp, tau, kWave);
         rc = make_row_coef(__shfl(my_Lp, tau, kWave) - __shfl(my_lw, tau, kWave), __shfl(my_Lq, tau, kWave));
@@ -552,7 +554,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     // vocabulary order (vector, lane, element)
     {
         const T *prow = target + (base + tau) * V;
-        const T *qrow = draft + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * V;
+        const T *qrow = draft + ((size_t)b * G + (tau < gamma ? tau : 0)) * V;
         const u64 sv = ld_u64(st + slot);
         const int first = slot * kUnitLogits + lane * kVec;
         float xp[kNV][kVec], xq[kNV][kVec];
@@ -617,14 +619,14 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b)
     // published its partial sum by now; the words of the last target row must all be written first.
     for (int e = lane; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
-    for (int e = lane; e < (gamma + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
-    for (int e = lane; e < gamma * nu; e += kWave) {
-        st_u32(P.spart + (size_t)b * gamma * nu + e, 0);
-        if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * gamma * nu + e, 0);
+    for (int e = lane; e < (G + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
+    for (int e = lane; e < G * nu; e += kWave) {
+        st_u32(P.spart + (size_t)b * G * nu + e, 0);
+        if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * G * nu + e, 0);
     }
-    for (int e = lane; e < gamma * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * gamma * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * gamma * (nu / kWaves) + e, 0); }
-    for (int e = lane; e < gamma; e += kWave) { st_u64(P.ratio + (size_t)b * gamma + e, 0); st_u64(P.lw + (size_t)b * gamma + e, 0); }
-    for (int e = lane; e < 3 * gamma; e += kWave) st_u64(P.rowstat + (size_t)b * gamma * 3 + e, 0);
+    for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
+    for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); }
+    for (int e = lane; e < 3 * G; e += kWave) st_u64(P.rowstat + (size_t)b * G * 3 + e, 0);
 }
 
 // ------------------------------------------------------------------ the kernel
@@ -648,6 +650,11 @@ void fused_verify_kernel(const FusedParams P)
     int wg_x;
     if (!decode_unit(P, wave, U, wg_x)) return;
     SV_STAMP(0);
+    // a sequence with a shorter draft has no row pairs at its unused positions, and its last target row is row gb
+    int gb = gamma;
+    if (P.draft_lens) { gb = P.draft_lens[U.b]; gb = gb < 1 ? 1 : gb > gamma ? gamma : gb; }   // kept in range whatever the caller wrote
+    if (U.last_row) U.i = gb;
+    else if (U.i >= gb) return;
 
     // stream A: the unit's chunk of target row i; stream B: the same chunk of draft row i (none for the last row)
     const size_t trow = (size_t)U.b * (gamma + 1) + U.i, drow = (size_t)U.b * gamma + (U.last_row ? 0 : U.i);
@@ -807,9 +814,9 @@ void fused_verify_kernel(const FusedParams P)
 
     // the first unit of a sequence's last row pair finishes the sequence: the earlier positions come before
     // it in the workgroup order, the last target row (needed only if every token is accepted) right after
-    if (U.i == gamma - 1 && U.c == 0) {
+    if (U.i == gb - 1 && U.c == 0) {
         SV_STAMP(5);
-        finalize_sequence<T, ALIGNED, GREEDY>(P, U.b);
+        finalize_sequence<T, ALIGNED, GREEDY>(P, U.b, gb);
         SV_STAMP(6);
     }
 #undef SV_STAMP

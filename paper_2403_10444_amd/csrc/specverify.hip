@@ -85,7 +85,7 @@ int resident_workgroups(K kernel, int &cache)
 }
 
 template <typename T, bool ALIGNED>
-sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, const int32_t *tokens,
+sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, const int32_t *tokens, const int32_t *draft_lens,
                           const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
                           char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                           hipStream_t stream)
@@ -102,7 +102,7 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
         target, draft, B, gamma, V, k, L.nchunks, stats);
     const size_t sm2 = 2 * (gamma + 1) * sizeof(double) + 2 * (gamma + 1) * sizeof(float);
     prefix_weights_kernel<T><<<B, 64, sm2, stream>>>(target, draft, tokens, gamma, V, k, kd, kd / (double)k - 1.0, L.nchunks,
-                                                    n_target_rows, algo, stats, coef);
+                                                    n_target_rows, algo, stats, coef, draft_lens);
     const unsigned pair_blocks = (unsigned)((size_t)B * gamma * L.nchunks);
     if (algo == kGreedy)
         residual_kernel<T, ALIGNED, true><<<pair_blocks, kThreads, 0, stream>>>(
@@ -113,12 +113,12 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
     const size_t sm4 = 2 * (gamma + 1) * sizeof(double);
     finalize_kernel<T, ALIGNED><<<B, kThreads, sm4, stream>>>(
         target, draft, uniforms, gamma, V, k, L.nchunks, algo, stats, coef, spart, rpart,
-        accept_len, next_token, debug_out);
+        accept_len, next_token, debug_out, draft_lens);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
 template <typename T, bool ALIGNED>
-sv_status_t launch_fused(int algo, const void *target, const void *draft, const int32_t *tokens,
+sv_status_t launch_fused(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
                          const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
@@ -137,7 +137,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     // a row's workgroups wait for each other and must fit on the device together, with room to spare
     if (capacity < 4 * wpr) return capacity < 1 ? SV_ERR_HIP : SV_ERR_UNSUPPORTED;
     FusedParams P;
-    P.target = target; P.draft = draft; P.tokens = tokens; P.uniforms = uniforms;
+    P.target = target; P.draft = draft; P.tokens = tokens; P.draft_lens = draft_lens; P.uniforms = uniforms;
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
     P.nu = L.nu;
     // groups of sequences so large that one position of a group fills the device at least once
@@ -164,7 +164,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
-sv_status_t verify_entry(int algo, const void *target, const void *draft, const int32_t *tokens,
+sv_status_t verify_entry(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
                          const float *uniforms, int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
                          float temperature, void *workspace, size_t workspace_bytes,
                          int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream_v)
@@ -191,13 +191,13 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
 
 #define SV_DISPATCH(FN)                                                                                      \
     (dtype == SV_DTYPE_F32                                                                                   \
-         ? (aligned ? FN<float, true>(algo, target, draft, tokens, uniforms, B, gamma, V, k, kd, L, ws,          \
+         ? (aligned ? FN<float, true>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,          \
                                       accept_len, next_token, debug_out, stream)                             \
-                    : FN<float, false>(algo, target, draft, tokens, uniforms, B, gamma, V, k, kd, L, ws,         \
+                    : FN<float, false>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,         \
                                        accept_len, next_token, debug_out, stream))                           \
-         : (aligned ? FN<bf16_t, true>(algo, target, draft, tokens, uniforms, B, gamma, V, k, kd, L, ws,         \
+         : (aligned ? FN<bf16_t, true>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,         \
                                        accept_len, next_token, debug_out, stream)                            \
-                    : FN<bf16_t, false>(algo, target, draft, tokens, uniforms, B, gamma, V, k, kd, L, ws,        \
+                    : FN<bf16_t, false>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,        \
                                         accept_len, next_token, debug_out, stream)))
     // the fused kernel (every logit read once) is the default; the staged kernels (every logit read twice)
     // take the shapes it does not: rows of more than kMaxUnitsPerRow wave chunks, or rows too wide to fit
@@ -299,7 +299,7 @@ sv_status_t spec_verify_block(const void *target_logits, const void *draft_logit
                               float temperature, void *workspace, size_t workspace_bytes,
                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kBlock, target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, dtype,
+    return verify_entry(kBlock, target_logits, draft_logits, draft_tokens, nullptr, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
@@ -309,7 +309,7 @@ sv_status_t spec_verify_token(const void *target_logits, const void *draft_logit
                               float temperature, void *workspace, size_t workspace_bytes,
                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kToken, target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, dtype,
+    return verify_entry(kToken, target_logits, draft_logits, draft_tokens, nullptr, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
@@ -319,7 +319,20 @@ sv_status_t spec_verify_greedy(const void *target_logits, const void *draft_logi
                                float temperature, void *workspace, size_t workspace_bytes,
                                int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kGreedy, target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, dtype,
+    return verify_entry(kGreedy, target_logits, draft_logits, draft_tokens, nullptr, uniforms, B, gamma, V, dtype,
+                        temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
+}
+
+sv_status_t spec_verify_ragged(sv_algo_t algo, const void *target_logits, const void *draft_logits,
+                               const int32_t *draft_tokens, const int32_t *draft_lens, const float *uniforms,
+                               int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                               float temperature, void *workspace, size_t workspace_bytes,
+                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
+{
+    if (algo != SV_ALGO_BLOCK && algo != SV_ALGO_TOKEN && algo != SV_ALGO_GREEDY) return SV_ERR_INVALID_ARG;
+    if (!draft_lens) return SV_ERR_INVALID_ARG;
+    const int a = algo == SV_ALGO_BLOCK ? kBlock : algo == SV_ALGO_TOKEN ? kToken : kGreedy;
+    return verify_entry(a, target_logits, draft_logits, draft_tokens, draft_lens, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 

@@ -64,13 +64,15 @@ template <typename T>
 __global__ __launch_bounds__(64) void prefix_weights_kernel(
     const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
     int gamma, int V, float k, double kd, double k_eps, int nchunks, int n_target_rows, int algo,
-    const float2 *__restrict__ stats, SeqCoef *__restrict__ coef)
+    const float2 *__restrict__ stats, SeqCoef *__restrict__ coef, const int32_t *__restrict__ draft_lens)
 {
     extern __shared__ double sm[];          // [2*(gamma+1)] log2-normalisers, then row maxima
     double *L_p = sm, *L_q = sm + (gamma + 1);
     float *M_p = reinterpret_cast<float *>(sm + 2 * (gamma + 1));
     float *M_q = M_p + (gamma + 1);
     const int b = blockIdx.x, tid = threadIdx.x;
+    // this sequence's draft length (kept in range whatever the caller wrote); gamma stays the stride
+    const int gb = draft_lens ? (draft_lens[b] < 1 ? 1 : draft_lens[b] > gamma ? gamma : draft_lens[b]) : gamma;
 
     // log2-normaliser of every row of this sequence: L = M + log2 sum_c s_c exp2(mk_c - M)
     for (int j = tid; j < 2 * gamma + 1; j += 64) {
@@ -91,17 +93,17 @@ __global__ __launch_bounds__(64) void prefix_weights_kernel(
     // Alg. 2, the recursion for w_i (the paper's p_i), carried as log2 w_i so that products of
     // ratios neither overflow nor lose 1 - w_i when w_i is close to 1.
     double log2w = 0.0, log2r = 0.0;
-    for (int i = 0; i <= gamma; ++i) {
+    for (int i = 0; i <= gb; ++i) {
         SeqCoef sc;
         const double lw = (algo == kToken) ? 0.0 : log2w;     // token verification: residual is p - q
-        sc.rc = make_row_coef(L_p[i] - lw, i < gamma ? L_q[i] : 0.0);
+        sc.rc = make_row_coef(L_p[i] - lw, i < gb ? L_q[i] : 0.0);
         sc.w = exp2(lw);
         sc.one_minus_w = -expm1(lw * 0.69314718055994530942);
         sc.log2r = log2r;
         sc.row_max = M_p[i];
         sc.pad = 0.f;
         coef[(size_t)b * (gamma + 1) + i] = sc;
-        if (i < gamma) {
+        if (i < gb) {
             // r_{i+1} = p_i(X_{i+1}) / q_i(X_{i+1}) from the two gathered logits.  The sweeps scale
             // logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that moves
             // a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
@@ -162,7 +164,8 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
     int gamma, int V, float k, int nchunks, int algo,
     const float2 *__restrict__ stats, const SeqCoef *__restrict__ coef,
     const float *__restrict__ spart, const float *__restrict__ rpart,
-    int32_t *__restrict__ accept_len, int32_t *__restrict__ next_token, float *__restrict__ debug_out)
+    int32_t *__restrict__ accept_len, int32_t *__restrict__ next_token, float *__restrict__ debug_out,
+    const int32_t *__restrict__ draft_lens)
 {
     extern __shared__ double smd[];                     // [gamma+1] S_i, [gamma+1] rejected mass
     __shared__ float lds[kWaves];
@@ -171,10 +174,12 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
     double *S = smd, *R = smd + (gamma + 1);
     const int b = blockIdx.x, tid = threadIdx.x;
     const SeqCoef *scb = coef + (size_t)b * (gamma + 1);
+    // this sequence's draft length (kept in range whatever the caller wrote); gamma stays the stride
+    const int gb = draft_lens ? (draft_lens[b] < 1 ? 1 : draft_lens[b] > gamma ? gamma : draft_lens[b]) : gamma;
 
     // S_i = cq_i * sum_c spart[b, i, c], chunks added in index order
-    for (int i = tid; i <= gamma; i += kThreads) {
-        if (i < gamma) {
+    for (int i = tid; i <= gb; i += kThreads) {
+        if (i < gb) {
             double acc = 0.0, rej = 0.0;
             const float *sp = spart + ((size_t)b * gamma + i) * nchunks;
             for (int c = 0; c < nchunks; ++c) acc += (double)sp[c];
@@ -195,11 +200,11 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
         // accept tests: eta_i < h_i
         int tau = 0;
         const float *eta = uniforms + (size_t)b * (gamma + 1);
-        for (int i = 0; i <= gamma; ++i) {
+        for (int i = 0; i <= gb; ++i) {
             double h;
             if (i == 0) h = 1.0;
             else if (algo == kToken) h = exp2(fmin(scb[i].log2r, 0.0));                 // min(r_i, 1)
-            else if (i == gamma) h = fmin(scb[i].w, 1.0);                               // h_gamma = w_gamma
+            else if (i == gb) h = fmin(scb[i].w, 1.0);                               // h_gamma = w_gamma
             else if (algo == kGreedy) h = R[i] > 0.0 ? fmin(S[i] / R[i], 1.0) : 1.0;    // p_remain / p_rej
             else h = scb[i].w >= 1.0 ? 1.0 : S[i] / (S[i] + scb[i].one_minus_w);        // block acceptance formula
             if (i >= 1) {
@@ -215,8 +220,8 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
         accept_len[b] = tau;
 
         // pick the chunk of row tau that holds t = u * (total weight)
-        const float u = eta[gamma];
-        int mode = (tau == gamma) ? 1 : 0;              // 1: weights are p_tau; 0: residual weights
+        const float u = eta[gb];
+        int mode = (tau == gb) ? 1 : 0;              // 1: weights are p_tau; 0: residual weights
         double total = 0.0;
         if (mode == 0) {
             const float *sp = spart + ((size_t)b * gamma + tau) * nchunks;
@@ -247,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
     const int tau = s_tau, chunk = s_chunk;
     const bool residual = s_mode == 0;
     const T *prow = target + ((size_t)b * (gamma + 1) + tau) * V;
-    const T *qrow = draft + ((size_t)b * gamma + (tau < gamma ? tau : 0)) * V;
+    const T *qrow = draft + ((size_t)b * gamma + (tau < gb ? tau : 0)) * V;
     const float2 st = stats[((size_t)b * (gamma + 1) + tau) * nchunks + chunk];
     const int y = walk_range<T, ALIGNED>(prow, qrow, V, chunk * kChunk, kChunk / (kThreads * 8), k, residual,
                                          scb[tau].rc, st.x, fast_exp2(st.x - scb[tau].row_max), s_t, lds, s_ints);

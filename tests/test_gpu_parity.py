@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import paper_2403_10444_amd as sv
+import oracle
 import workloads
 from tests import parity
 
@@ -232,6 +233,53 @@ def test_masked_logits_top_k(algo, kt, kd):
     rep = parity.compare(parity.run_gpu(algo, inp, cfg.temperature), parity.run_oracle(algo, inp, cfg.temperature),
                          label=f"top-k {kt}/{kd}/{algo}", greedy=(algo == "greedy"))
     _say(rep)
+
+
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+@pytest.mark.parametrize("B,gamma,V,dtype", [(24, 8, 20000, "bf16"), (9, 5, 8191, "f32"), (130, 16, 3000, "bf16")])
+def test_ragged_draft_lengths(algo, B, gamma, V, dtype):
+    """Sequences with drafts of different lengths in one call: sequence b must come out exactly as a call with
+    gamma = draft_lens[b] on its leading rows does (here: the oracle on those slices).  The rows beyond a
+    sequence's length are poisoned with NaN to show that they are never read."""
+    cfg = _custom(B, gamma, V, dtype, sigma_t=2.5, sigma_d=1.0, T=0.8)
+    inp = workloads.generate(cfg, seed=500 + B + gamma, device=DEV)
+    rng = np.random.default_rng(B * gamma)
+    lens = rng.integers(1, gamma + 1, size=B).astype(np.int32)
+    lens[0], lens[-1] = gamma, 1
+    tl, dl = inp["target_logits"].clone(), inp["draft_logits"].clone()
+    for b in range(B):
+        tl[b, lens[b] + 1:] = float("nan")
+        dl[b, lens[b]:] = float("nan")
+    dbg = torch.full((B, gamma + 1, 3), float("nan"), dtype=torch.float32, device=DEV)
+    tau, y = sv.spec_verify_ragged(algo, tl, dl, inp["draft_tokens"], torch.as_tensor(lens, device=DEV),
+                                   inp["uniforms"], cfg.temperature, debug_out=dbg)
+    torch.cuda.synchronize()
+    tau, y = tau.cpu().numpy(), y.cpu().numpy()
+    host = workloads.to_numpy(inp)
+    odt = oracle.BF16 if dtype == "bf16" else oracle.F32
+    n_safe = 0
+    for g in np.unique(lens):
+        sel = np.nonzero(lens == g)[0]
+        ref = oracle.verify(parity.ALGOS[algo][0], host["target_logits"][sel, :g + 1], host["draft_logits"][sel, :g],
+                            host["draft_tokens"][sel, :g], host["uniforms"][sel, :g + 1], cfg.temperature, dtype=odt)
+        safe = ref["margins"].min(axis=1) >= parity.MARGIN
+        n_safe += int(safe.sum())
+        assert np.array_equal(tau[sel][safe], ref["accept_len"][safe]), (g, algo)
+        same_tau = safe & (tau[sel] == ref["accept_len"])
+        assert np.array_equal(y[sel][same_tau], ref["next_token"][same_tau]), (g, algo)
+        assert np.all(tau[sel] <= g)
+    assert n_safe >= 0.8 * B
+
+
+def test_ragged_with_full_lengths_equals_the_plain_call():
+    cfg = _custom(12, 6, 10000, "bf16")
+    inp = workloads.generate(cfg, seed=41, device=DEV)
+    a = parity.run_gpu("block", inp, 1.0)
+    lens = torch.full((cfg.B,), cfg.gamma, dtype=torch.int32, device=DEV)
+    tau, y = sv.spec_verify_ragged("block", inp["target_logits"], inp["draft_logits"], inp["draft_tokens"], lens,
+                                   inp["uniforms"], 1.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(tau.cpu().numpy(), a["accept_len"]) and np.array_equal(y.cpu().numpy(), a["next_token"])
 
 
 def test_captured_in_a_graph_and_replayed():
