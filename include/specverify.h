@@ -158,22 +158,33 @@ sv_status_t spec_verify_greedy(const void *target_logits, const void *draft_logi
                                void *stream);
 
 /*
- * The same three algorithms for a batch whose sequences carry drafts of different lengths (what a
- * serving stack hands over when drafters stop early).  Sequence b uses its first draft_lens[b]
- * draft positions, 1 <= draft_lens[b] <= gamma: target rows 0 .. draft_lens[b], draft rows and
- * tokens 0 .. draft_lens[b] - 1, uniforms[b][0 .. draft_lens[b] - 1] for the accept tests and
- * uniforms[b][draft_lens[b]] for the draw of Y - exactly the result of a call with gamma =
- * draft_lens[b] on that sequence's leading rows.  `gamma` remains the stride of every array; rows
- * beyond a sequence's length are never read.  draft_lens is device memory, [B] int32; values
- * outside 1 .. gamma are the caller's error and are clamped into that range on the device.
- * accept_len[b] lies in 0 .. draft_lens[b].  Everything else as for spec_verify_block.
+ * The same three algorithms with the input variants a serving stack hands over:
+ *
+ *  - draft_lens (device, [B] int32, or NULL): sequences carry drafts of different lengths.  Sequence
+ *    b uses its first draft_lens[b] draft positions, 1 <= draft_lens[b] <= gamma: target rows
+ *    0 .. draft_lens[b], draft rows and tokens 0 .. draft_lens[b] - 1, uniforms[b][0 ..
+ *    draft_lens[b] - 1] for the accept tests and uniforms[b][draft_lens[b]] for the draw of Y -
+ *    exactly the result of a call with gamma = draft_lens[b] on that sequence's leading rows.
+ *    `gamma` remains the row count per sequence in every array; rows beyond a sequence's length
+ *    are never read.  Values outside 1 .. gamma are the caller's error and are clamped into that
+ *    range on the device.  accept_len[b] lies in 0 .. draft_lens[b].
+ *  - target_row_stride, draft_row_stride (in elements, >= V, or 0 for dense rows): the distance
+ *    from one row of V logits to the next, e.g. a vocabulary padded for the GEMM that produced
+ *    the logits.  Row (b, i) of the target starts (b * (gamma + 1) + i) * target_row_stride
+ *    elements after target_logits, row (b, i) of the draft (b * gamma + i) * draft_row_stride
+ *    after draft_logits; what lies between rows is never read.  16-byte loads need both strides
+ *    in bytes to be multiples of 16 besides the conditions on V and the base pointers.
+ *
+ * SV_ERR_INVALID_ARG also for an unknown algo, a negative stride or a stride below V.  Everything
+ * else as for spec_verify_block.
  */
 typedef enum { SV_ALGO_BLOCK = 0, SV_ALGO_TOKEN = 1, SV_ALGO_GREEDY = 2 } sv_algo_t;
-sv_status_t spec_verify_ragged(sv_algo_t algo, const void *target_logits, const void *draft_logits,
-                               const int32_t *draft_tokens, const int32_t *draft_lens, const float *uniforms,
-                               int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
-                               float temperature, void *workspace, size_t workspace_bytes,
-                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream);
+sv_status_t spec_verify_ex(sv_algo_t algo, const void *target_logits, const void *draft_logits,
+                           const int32_t *draft_tokens, const int32_t *draft_lens,
+                           int64_t target_row_stride, int64_t draft_row_stride, const float *uniforms,
+                           int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                           float temperature, void *workspace, size_t workspace_bytes,
+                           int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream);
 
 const char *spec_verify_status_string(sv_status_t status);
 

@@ -34,7 +34,7 @@ EXPORTED = (
     "spec_verify_block",
     "spec_verify_token",
     "spec_verify_greedy",
-    "spec_verify_ragged",
+    "spec_verify_ex",
     "spec_verify_status_string",
 )
 
@@ -69,8 +69,9 @@ def load() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.restype = ctypes.c_int
             fn.argtypes = _VERIFY_ARGTYPES
-        lib.spec_verify_ragged.restype = ctypes.c_int
-        lib.spec_verify_ragged.argtypes = [ctypes.c_int] + _VERIFY_ARGTYPES[:3] + [ctypes.c_void_p] + _VERIFY_ARGTYPES[3:]
+        lib.spec_verify_ex.restype = ctypes.c_int
+        lib.spec_verify_ex.argtypes = ([ctypes.c_int] + _VERIFY_ARGTYPES[:3]
+                                       + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64] + _VERIFY_ARGTYPES[3:])
         lib.spec_verify_workspace_init.restype = ctypes.c_int
         lib.spec_verify_workspace_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
                                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
@@ -180,6 +181,16 @@ def _dtype_code(t: torch.Tensor) -> int:
 SV_ALGO = {"block": 0, "token": 1, "greedy": 2}
 
 
+def _row_stride(t: torch.Tensor, rows_per_seq: int) -> int:
+    """Row stride in elements of a [B, rows_per_seq, V] tensor whose rows are dense and evenly spaced
+    (a contiguous tensor, or the [..., :V] view of one with a padded last dimension)."""
+    B, R, V = t.shape
+    sb, sr, sv_ = t.stride()
+    if sv_ != 1 or sr < V or (B > 1 and sb != sr * rows_per_seq):
+        raise ValueError("logits must have unit stride along the vocabulary and evenly spaced rows")
+    return sr
+
+
 def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature,
           workspace=None, accept_len=None, next_token=None, debug_out=None, stream=None, draft_lens=None, algo=None):
     lib = load()
@@ -196,9 +207,13 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
     for t, want in ((draft_tokens, torch.int32), (uniforms, torch.float32)):
         if t.dtype != want:
             raise TypeError(f"expected {want}, got {t.dtype}")
+    extended = name == "spec_verify_ex"
     for t in (target_logits, draft_logits, draft_tokens, uniforms):
-        if not t.is_contiguous() or t.device != dev:
-            raise ValueError("inputs must be contiguous and on one device")
+        if t.device != dev:
+            raise ValueError("inputs must be on one device")
+    for t in (draft_tokens, uniforms) + (() if extended else (target_logits, draft_logits)):
+        if not t.is_contiguous():
+            raise ValueError("inputs must be contiguous")
     if workspace is None:
         workspace = alloc_workspace(B, gamma, V, dev)
     if accept_len is None:
@@ -208,15 +223,17 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
     head = ()
-    tokens_and_lens = (draft_tokens.data_ptr(),)
-    if draft_lens is not None:
-        if tuple(draft_lens.shape) != (B,) or draft_lens.dtype != torch.int32 or draft_lens.device != dev \
-                or not draft_lens.is_contiguous():
+    after_tokens = ()
+    if extended:
+        if draft_lens is not None and (tuple(draft_lens.shape) != (B,) or draft_lens.dtype != torch.int32
+                                       or draft_lens.device != dev or not draft_lens.is_contiguous()):
             raise ValueError("draft_lens must be a contiguous int32 tensor [B] on the inputs' device")
         head = (SV_ALGO[algo],)
-        tokens_and_lens = (draft_tokens.data_ptr(), draft_lens.data_ptr())
+        after_tokens = (draft_lens.data_ptr() if draft_lens is not None else None,
+                        _row_stride(target_logits, gamma + 1), _row_stride(draft_logits, gamma))
     code = getattr(lib, name)(
-        *head, target_logits.data_ptr(), draft_logits.data_ptr(), *tokens_and_lens, uniforms.data_ptr(),
+        *head, target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), *after_tokens,
+        uniforms.data_ptr(),
         B, gamma, V, _dtype_code(target_logits), float(temperature),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         accept_len.data_ptr(), next_token.data_ptr(),
@@ -226,10 +243,12 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
     return accept_len, next_token
 
 
-def spec_verify_ragged(algo, target_logits, draft_logits, draft_tokens, draft_lens, uniforms, temperature, **kw):
-    """`algo` ("block", "token" or "greedy") for a batch whose sequence b uses only its first draft_lens[b]
-    draft positions (int32 device tensor [B], values 1 .. gamma); see `spec_verify_ragged` in the header."""
-    return _call("spec_verify_ragged", target_logits, draft_logits, draft_tokens, uniforms, temperature,
+def spec_verify_ex(algo, target_logits, draft_logits, draft_tokens, uniforms, temperature, draft_lens=None, **kw):
+    """`algo` ("block", "token" or "greedy") with the input variants of `spec_verify_ex` in the header:
+    ``draft_lens`` (int32 device tensor [B], values 1 .. gamma, or None) makes sequence b use only its first
+    draft_lens[b] draft positions; the logits may be ``[..., :V]`` views of buffers whose last dimension is
+    padded (the row strides are taken from the tensors)."""
+    return _call("spec_verify_ex", target_logits, draft_logits, draft_tokens, uniforms, temperature,
                  draft_lens=draft_lens, algo=algo, **kw)
 
 

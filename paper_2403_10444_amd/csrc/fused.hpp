@@ -66,6 +66,7 @@ struct FusedParams {
     const int32_t *draft_lens;   // NULL, or [B]: sequence b uses its first draft_lens[b] draft positions (1 .. gamma)
     const float *uniforms;
     int B, gamma, V;
+    size_t tstride, dstride;     // elements from one target / draft row to the next (>= V)
     float k;              // float(log2(e) / T): the factor the sweeps multiply logits by
     double kd;            // log2(e) / T in double
     double k_eps;         // kd / k - 1: what rounding k to float left out (|k_eps| <= 2^-24)
@@ -553,8 +554,8 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     // ---- ... then the token inside that chunk: weights recomputed from the logits, walked in
     // vocabulary order (vector, lane, element)
     {
-        const T *prow = target + (base + tau) * V;
-        const T *qrow = draft + ((size_t)b * G + (tau < gamma ? tau : 0)) * V;
+        const T *prow = target + (base + tau) * P.tstride;
+        const T *qrow = draft + ((size_t)b * G + (tau < gamma ? tau : 0)) * P.dstride;
         const u64 sv = ld_u64(st + slot);
         const int first = slot * kUnitLogits + lane * kVec;
         float xp[kNV][kVec], xq[kNV][kVec];
@@ -658,8 +659,8 @@ void fused_verify_kernel(const FusedParams P)
 
     // stream A: the unit's chunk of target row i; stream B: the same chunk of draft row i (none for the last row)
     const size_t trow = (size_t)U.b * (gamma + 1) + U.i, drow = (size_t)U.b * gamma + (U.last_row ? 0 : U.i);
-    const T *rowA = static_cast<const T *>(P.target) + trow * V;
-    const T *rowB = static_cast<const T *>(P.draft) + drow * V;
+    const T *rowA = static_cast<const T *>(P.target) + trow * P.tstride;
+    const T *rowB = static_cast<const T *>(P.draft) + drow * P.dstride;
     const int unit_first = U.c * kUnitLogits;
     RawSlice<T, ALIGNED> rawA, rawB;
     issue_loads<T, ALIGNED>(rowA, unit_first, V, rawA);

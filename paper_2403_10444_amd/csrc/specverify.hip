@@ -86,7 +86,7 @@ int resident_workgroups(K kernel, int &cache)
 
 template <typename T, bool ALIGNED>
 sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, const int32_t *tokens, const int32_t *draft_lens,
-                          const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
+                          size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
                           char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                           hipStream_t stream)
 {
@@ -99,27 +99,27 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
     const int n_target_rows = B * (gamma + 1);
 
     row_stats_kernel<T, ALIGNED><<<(unsigned)(L.rows_total * L.nchunks), kThreads, 0, stream>>>(
-        target, draft, B, gamma, V, k, L.nchunks, stats);
+        target, draft, tstride, dstride, B, gamma, V, k, L.nchunks, stats);
     const size_t sm2 = 2 * (gamma + 1) * sizeof(double) + 2 * (gamma + 1) * sizeof(float);
-    prefix_weights_kernel<T><<<B, 64, sm2, stream>>>(target, draft, tokens, gamma, V, k, kd, kd / (double)k - 1.0, L.nchunks,
+    prefix_weights_kernel<T><<<B, 64, sm2, stream>>>(target, draft, tstride, dstride, tokens, gamma, V, k, kd, kd / (double)k - 1.0, L.nchunks,
                                                     n_target_rows, algo, stats, coef, draft_lens);
     const unsigned pair_blocks = (unsigned)((size_t)B * gamma * L.nchunks);
     if (algo == kGreedy)
         residual_kernel<T, ALIGNED, true><<<pair_blocks, kThreads, 0, stream>>>(
-            target, draft, gamma, V, k, L.nchunks, coef, spart, rpart);
+            target, draft, tstride, dstride, gamma, V, k, L.nchunks, coef, spart, rpart);
     else
         residual_kernel<T, ALIGNED, false><<<pair_blocks, kThreads, 0, stream>>>(
-            target, draft, gamma, V, k, L.nchunks, coef, spart, rpart);
+            target, draft, tstride, dstride, gamma, V, k, L.nchunks, coef, spart, rpart);
     const size_t sm4 = 2 * (gamma + 1) * sizeof(double);
     finalize_kernel<T, ALIGNED><<<B, kThreads, sm4, stream>>>(
-        target, draft, uniforms, gamma, V, k, L.nchunks, algo, stats, coef, spart, rpart,
+        target, draft, tstride, dstride, uniforms, gamma, V, k, L.nchunks, algo, stats, coef, spart, rpart,
         accept_len, next_token, debug_out, draft_lens);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
 template <typename T, bool ALIGNED>
 sv_status_t launch_fused(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
-                         const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
+                         size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
 {
@@ -138,6 +138,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     if (capacity < 4 * wpr) return capacity < 1 ? SV_ERR_HIP : SV_ERR_UNSUPPORTED;
     FusedParams P;
     P.target = target; P.draft = draft; P.tokens = tokens; P.draft_lens = draft_lens; P.uniforms = uniforms;
+    P.tstride = tstride; P.dstride = dstride;
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
     P.nu = L.nu;
     // groups of sequences so large that one position of a group fills the device at least once
@@ -165,6 +166,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
 }
 
 sv_status_t verify_entry(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
+                         int64_t target_row_stride, int64_t draft_row_stride,
                          const float *uniforms, int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
                          float temperature, void *workspace, size_t workspace_bytes,
                          int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream_v)
@@ -182,23 +184,23 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
     const double kd = 1.4426950408889634074 / (double)temperature;
     const float k = (float)kd;
     const size_t esize = dtype == SV_DTYPE_F32 ? 4 : 2;
+    // rows are V logits, target_row_stride / draft_row_stride elements apart (0: dense, the stride is V)
+    if (target_row_stride < 0 || draft_row_stride < 0) return SV_ERR_INVALID_ARG;
+    const size_t tstride = target_row_stride ? (size_t)target_row_stride : (size_t)V;
+    const size_t dstride = draft_row_stride ? (size_t)draft_row_stride : (size_t)V;
+    if (tstride < (size_t)V || dstride < (size_t)V) return SV_ERR_INVALID_ARG;
     const bool aligned = ((reinterpret_cast<uintptr_t>(target) | reinterpret_cast<uintptr_t>(draft)) & 15u) == 0 &&
-                         ((size_t)V * esize) % 16 == 0;
+                         ((size_t)V * esize) % 16 == 0 && (tstride * esize) % 16 == 0 && (dstride * esize) % 16 == 0;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     char *ws = static_cast<char *>(workspace);
     const int path = g_path.load();
     if (path == 2 && !L.fused_ok) return SV_ERR_UNSUPPORTED;
 
-#define SV_DISPATCH(FN)                                                                                      \
-    (dtype == SV_DTYPE_F32                                                                                   \
-         ? (aligned ? FN<float, true>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,          \
-                                      accept_len, next_token, debug_out, stream)                             \
-                    : FN<float, false>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,         \
-                                       accept_len, next_token, debug_out, stream))                           \
-         : (aligned ? FN<bf16_t, true>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,         \
-                                       accept_len, next_token, debug_out, stream)                            \
-                    : FN<bf16_t, false>(algo, target, draft, tokens, draft_lens, uniforms, B, gamma, V, k, kd, L, ws,        \
-                                        accept_len, next_token, debug_out, stream)))
+#define SV_ARGS algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, L, ws, \
+                accept_len, next_token, debug_out, stream
+#define SV_DISPATCH(FN)                                                                   \
+    (dtype == SV_DTYPE_F32 ? (aligned ? FN<float, true>(SV_ARGS) : FN<float, false>(SV_ARGS)) \
+                           : (aligned ? FN<bf16_t, true>(SV_ARGS) : FN<bf16_t, false>(SV_ARGS)))
     // the fused kernel (every logit read once) is the default; the staged kernels (every logit read twice)
     // take the shapes it does not: rows of more than kMaxUnitsPerRow wave chunks, or rows too wide to fit
     // four times into the device's resident set
@@ -210,6 +212,7 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
     }
     return SV_DISPATCH(launch_staged);
 #undef SV_DISPATCH
+#undef SV_ARGS
 }
 
 }  // namespace
@@ -299,7 +302,7 @@ sv_status_t spec_verify_block(const void *target_logits, const void *draft_logit
                               float temperature, void *workspace, size_t workspace_bytes,
                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kBlock, target_logits, draft_logits, draft_tokens, nullptr, uniforms, B, gamma, V, dtype,
+    return verify_entry(kBlock, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
@@ -309,7 +312,7 @@ sv_status_t spec_verify_token(const void *target_logits, const void *draft_logit
                               float temperature, void *workspace, size_t workspace_bytes,
                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kToken, target_logits, draft_logits, draft_tokens, nullptr, uniforms, B, gamma, V, dtype,
+    return verify_entry(kToken, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
@@ -319,21 +322,22 @@ sv_status_t spec_verify_greedy(const void *target_logits, const void *draft_logi
                                float temperature, void *workspace, size_t workspace_bytes,
                                int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kGreedy, target_logits, draft_logits, draft_tokens, nullptr, uniforms, B, gamma, V, dtype,
+    return verify_entry(kGreedy, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
-sv_status_t spec_verify_ragged(sv_algo_t algo, const void *target_logits, const void *draft_logits,
-                               const int32_t *draft_tokens, const int32_t *draft_lens, const float *uniforms,
-                               int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
-                               float temperature, void *workspace, size_t workspace_bytes,
-                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
+sv_status_t spec_verify_ex(sv_algo_t algo, const void *target_logits, const void *draft_logits,
+                           const int32_t *draft_tokens, const int32_t *draft_lens,
+                           int64_t target_row_stride, int64_t draft_row_stride, const float *uniforms,
+                           int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                           float temperature, void *workspace, size_t workspace_bytes,
+                           int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
     if (algo != SV_ALGO_BLOCK && algo != SV_ALGO_TOKEN && algo != SV_ALGO_GREEDY) return SV_ERR_INVALID_ARG;
-    if (!draft_lens) return SV_ERR_INVALID_ARG;
     const int a = algo == SV_ALGO_BLOCK ? kBlock : algo == SV_ALGO_TOKEN ? kToken : kGreedy;
-    return verify_entry(a, target_logits, draft_logits, draft_tokens, draft_lens, uniforms, B, gamma, V, dtype,
-                        temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
+    return verify_entry(a, target_logits, draft_logits, draft_tokens, draft_lens, target_row_stride, draft_row_stride,
+                        uniforms, B, gamma, V, dtype, temperature, workspace, workspace_bytes, accept_len, next_token,
+                        debug_out, stream);
 }
 
 const char *spec_verify_status_string(sv_status_t status)

@@ -28,7 +28,7 @@ struct SeqCoef {
 
 template <typename T, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void row_stats_kernel(
-    const T *__restrict__ target, const T *__restrict__ draft,
+    const T *__restrict__ target, const T *__restrict__ draft, size_t tstride, size_t dstride,
     int B, int gamma, int V, float k, int nchunks, float2 *__restrict__ stats)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
     __shared__ float lds[kWaves];
     const int r = blockIdx.x / nchunks, c = blockIdx.x - r * nchunks, tid = threadIdx.x;
     const int n_target_rows = B * (gamma + 1);
-    const T *row = r < n_target_rows ? target + (size_t)r * V : draft + (size_t)(r - n_target_rows) * V;
+    const T *row = r < n_target_rows ? target + (size_t)r * tstride : draft + (size_t)(r - n_target_rows) * dstride;
 
     float x[kU][kVec];
 #pragma unroll
@@ -62,7 +62,8 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(
 
 template <typename T>
 __global__ __launch_bounds__(64) void prefix_weights_kernel(
-    const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
+    const T *__restrict__ target, const T *__restrict__ draft, size_t tstride, size_t dstride,
+    const int32_t *__restrict__ tokens,
     int gamma, int V, float k, double kd, double k_eps, int nchunks, int n_target_rows, int algo,
     const float2 *__restrict__ stats, SeqCoef *__restrict__ coef, const int32_t *__restrict__ draft_lens)
 {
@@ -109,8 +110,8 @@ __global__ __launch_bounds__(64) void prefix_weights_kernel(
             // a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the
             // row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
             const int tok = tokens[(size_t)b * gamma + i];
-            const double ya = logit_as_double(target + ((size_t)b * (gamma + 1) + i) * V + tok) * kd;
-            const double yb = logit_as_double(draft + ((size_t)b * gamma + i) * V + tok) * kd;
+            const double ya = logit_as_double(target + ((size_t)b * (gamma + 1) + i) * tstride + tok) * kd;
+            const double yb = logit_as_double(draft + ((size_t)b * gamma + i) * dstride + tok) * kd;
             log2r = (ya - (L_p[i] + k_eps * (double)M_p[i])) - (yb - (L_q[i] + k_eps * (double)M_q[i]));
             log2r = fmax(log2r, kLog2RatioFloor);   // a drafted token the target masks out (logit -inf): r = 0, kept finite
             log2w += log2r;
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(64) void prefix_weights_kernel(
 
 template <typename T, bool ALIGNED, bool GREEDY>
 __global__ __launch_bounds__(kThreads) void residual_kernel(
-    const T *__restrict__ target, const T *__restrict__ draft,
+    const T *__restrict__ target, const T *__restrict__ draft, size_t tstride, size_t dstride,
     int gamma, int V, float k, int nchunks, const SeqCoef *__restrict__ coef,
     float *__restrict__ spart, float *__restrict__ rpart)
 {
@@ -131,8 +132,8 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
     const int pr = blockIdx.x / nchunks, c = blockIdx.x - pr * nchunks, tid = threadIdx.x;
     const int b = pr / gamma, i = pr - b * gamma;
     const RowCoef rc = coef[(size_t)b * (gamma + 1) + i].rc;
-    const T *prow = target + ((size_t)b * (gamma + 1) + i) * V;
-    const T *qrow = draft + ((size_t)b * gamma + i) * V;
+    const T *prow = target + ((size_t)b * (gamma + 1) + i) * tstride;
+    const T *qrow = draft + ((size_t)b * gamma + i) * dstride;
 
     float xp[kU][kVec], xq[kU][kVec];
 #pragma unroll
@@ -160,7 +161,8 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
 
 template <typename T, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void finalize_kernel(
-    const T *__restrict__ target, const T *__restrict__ draft, const float *__restrict__ uniforms,
+    const T *__restrict__ target, const T *__restrict__ draft, size_t tstride, size_t dstride,
+    const float *__restrict__ uniforms,
     int gamma, int V, float k, int nchunks, int algo,
     const float2 *__restrict__ stats, const SeqCoef *__restrict__ coef,
     const float *__restrict__ spart, const float *__restrict__ rpart,
@@ -251,8 +253,8 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
     __syncthreads();
     const int tau = s_tau, chunk = s_chunk;
     const bool residual = s_mode == 0;
-    const T *prow = target + ((size_t)b * (gamma + 1) + tau) * V;
-    const T *qrow = draft + ((size_t)b * gamma + (tau < gb ? tau : 0)) * V;
+    const T *prow = target + ((size_t)b * (gamma + 1) + tau) * tstride;
+    const T *qrow = draft + ((size_t)b * gamma + (tau < gb ? tau : 0)) * dstride;
     const float2 st = stats[((size_t)b * (gamma + 1) + tau) * nchunks + chunk];
     const int y = walk_range<T, ALIGNED>(prow, qrow, V, chunk * kChunk, kChunk / (kThreads * 8), k, residual,
                                          scb[tau].rc, st.x, fast_exp2(st.x - scb[tau].row_max), s_t, lds, s_ints);

@@ -125,13 +125,14 @@ def test_sample_tokens_validates_its_arguments():
     assert call(rows=1 << 31) == binding.SV_ERR_UNSUPPORTED
 
 
-def test_ragged_entry_validates_its_arguments():
+def test_extended_entry_validates_its_arguments():
     lib = sv.load()
 
-    def call(algo=0, lens=0x1000, B=2):
-        return lib.spec_verify_ragged(algo, 0x1000, 0x1000, 0x1000, lens, 0x1000, B, 3, 100, 0, 1.0, 0x1000, 1 << 30,
-                                      0x1000, 0x1000, None, None)
+    def call(algo=0, lens=0x1000, B=2, ts=0, ds=0):
+        return lib.spec_verify_ex(algo, 0x1000, 0x1000, 0x1000, lens, ts, ds, 0x1000, B, 3, 100, 0, 1.0, 0x1000,
+                                  1 << 30, 0x1000, 0x1000, None, None)
 
     assert call(algo=3) == binding.SV_ERR_INVALID_ARG
-    assert call(lens=None) == binding.SV_ERR_INVALID_ARG
     assert call(B=0) == binding.SV_ERR_INVALID_ARG
+    assert call(ts=99) == binding.SV_ERR_INVALID_ARG       # a stride below V
+    assert call(ds=-1) == binding.SV_ERR_INVALID_ARG

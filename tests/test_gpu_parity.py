@@ -251,8 +251,8 @@ def test_ragged_draft_lengths(algo, B, gamma, V, dtype):
         tl[b, lens[b] + 1:] = float("nan")
         dl[b, lens[b]:] = float("nan")
     dbg = torch.full((B, gamma + 1, 3), float("nan"), dtype=torch.float32, device=DEV)
-    tau, y = sv.spec_verify_ragged(algo, tl, dl, inp["draft_tokens"], torch.as_tensor(lens, device=DEV),
-                                   inp["uniforms"], cfg.temperature, debug_out=dbg)
+    tau, y = sv.spec_verify_ex(algo, tl, dl, inp["draft_tokens"], inp["uniforms"], cfg.temperature,
+                               draft_lens=torch.as_tensor(lens, device=DEV), debug_out=dbg)
     torch.cuda.synchronize()
     tau, y = tau.cpu().numpy(), y.cpu().numpy()
     host = workloads.to_numpy(inp)
@@ -276,10 +276,55 @@ def test_ragged_with_full_lengths_equals_the_plain_call():
     inp = workloads.generate(cfg, seed=41, device=DEV)
     a = parity.run_gpu("block", inp, 1.0)
     lens = torch.full((cfg.B,), cfg.gamma, dtype=torch.int32, device=DEV)
-    tau, y = sv.spec_verify_ragged("block", inp["target_logits"], inp["draft_logits"], inp["draft_tokens"], lens,
-                                   inp["uniforms"], 1.0)
+    tau, y = sv.spec_verify_ex("block", inp["target_logits"], inp["draft_logits"], inp["draft_tokens"],
+                               inp["uniforms"], 1.0, draft_lens=lens)
     torch.cuda.synchronize()
     assert np.array_equal(tau.cpu().numpy(), a["accept_len"]) and np.array_equal(y.cpu().numpy(), a["next_token"])
+
+
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+@pytest.mark.parametrize("B,gamma,V,dtype,pad_t,pad_d", [
+    (16, 8, 20000, "bf16", 96, 32),     # strides keep 16-byte alignment: vector loads
+    (7, 4, 8191, "f32", 1, 9),          # odd V and odd strides: scalar loads
+    (5, 3, 33000, "bf16", 24, 0),       # target padded, draft dense; bf16 stride a multiple of 8 elements
+    (70, 2, 3000, "bf16", 3, 5),        # several sequence groups, misaligned strides
+])
+def test_padded_rows(algo, B, gamma, V, dtype, pad_t, pad_d):
+    """Rows of V logits inside buffers whose last dimension is padded (stride > V).  The padding is poisoned
+    with NaN to show that it is never read; the result must be the one for dense rows (the oracle's)."""
+    cfg = _custom(B, gamma, V, dtype, sigma_t=2.5, sigma_d=1.0, T=0.8)
+    inp = workloads.generate(cfg, seed=700 + B + gamma, device=DEV)
+    tbuf = torch.full((B, gamma + 1, V + pad_t), float("nan"), dtype=inp["target_logits"].dtype, device=DEV)
+    dbuf = torch.full((B, gamma, V + pad_d), float("nan"), dtype=inp["draft_logits"].dtype, device=DEV)
+    tbuf[..., :V] = inp["target_logits"]
+    dbuf[..., :V] = inp["draft_logits"]
+    tau, y = sv.spec_verify_ex(algo, tbuf[..., :V], dbuf[..., :V], inp["draft_tokens"], inp["uniforms"],
+                               cfg.temperature)
+    torch.cuda.synchronize()
+    gpu = {"accept_len": tau.cpu().numpy(), "next_token": y.cpu().numpy()}
+    ref = parity.run_oracle(algo, inp, cfg.temperature)
+    safe = ref["margins"].min(axis=1) >= parity.MARGIN
+    assert safe.sum() >= 0.8 * B
+    assert np.array_equal(gpu["accept_len"][safe], ref["accept_len"][safe])
+    assert np.array_equal(gpu["next_token"][safe], ref["next_token"][safe])
+
+
+def test_padded_rows_with_draft_lengths():
+    """Both input variants in one call."""
+    B, gamma, V = 12, 6, 12000
+    cfg = _custom(B, gamma, V, "bf16", sigma_t=2.5, sigma_d=1.0, T=1.0)
+    inp = workloads.generate(cfg, seed=77, device=DEV)
+    lens = torch.tensor([1 + (b * 5) % gamma for b in range(B)], dtype=torch.int32, device=DEV)
+    tbuf = torch.full((B, gamma + 1, V + 40), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dbuf = torch.full((B, gamma, V + 8), float("nan"), dtype=torch.bfloat16, device=DEV)
+    tbuf[..., :V] = inp["target_logits"]
+    dbuf[..., :V] = inp["draft_logits"]
+    a = sv.spec_verify_ex("block", inp["target_logits"], inp["draft_logits"], inp["draft_tokens"], inp["uniforms"],
+                          1.0, draft_lens=lens)
+    b = sv.spec_verify_ex("block", tbuf[..., :V], dbuf[..., :V], inp["draft_tokens"], inp["uniforms"], 1.0,
+                          draft_lens=lens)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
 def test_captured_in_a_graph_and_replayed():
