@@ -36,7 +36,8 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F64 = 2 };   /* F64: tests only (exact tiny tables) */
+enum { ORACLE_LOGITS = 0, ORACLE_PROBS = 1 };               /* what the rows hold */
 enum { ORACLE_BLOCK = 0, ORACLE_TOKEN = 1, ORACLE_GREEDY = 2 };
 
 /* number of doubles per (sequence, position) in the debug block */
@@ -49,6 +50,8 @@ static double logit_at(const void *base, int dtype, size_t idx)
 {
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[idx];
+    if (dtype == ORACLE_F64)
+        return ((const double *)base)[idx];
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -71,6 +74,19 @@ static double softmax_row(const void *base, int dtype, size_t off, int V, double
     double logz = amax + log(z);
     for (int x = 0; x < V; ++x) prob[x] = exp(scaled[x] - logz);
     return logz;
+}
+
+/* A row that already holds a distribution (the p_i, q_i of Alg. 1 / Alg. 2 handed over as they are, the
+ * form of the arrays in App. A): prob(x) is the stored value, used as given (not renormalised), and
+ * `scaled` receives its log (-inf for a zero), so that with a log-normaliser of 0 the rest of the
+ * oracle reads the row exactly like a softmax row.  Returns that 0.                              */
+static double given_row(const void *base, int dtype, size_t off, int V, double *scaled, double *prob)
+{
+    for (int x = 0; x < V; ++x) {
+        prob[x] = logit_at(base, dtype, off + (size_t)x);
+        scaled[x] = log(prob[x]);
+    }
+    return 0.0;
 }
 
 /* Inverse-CDF draw: rho(x) >= 0 are unnormalised weights.  C_x = sum_{x'<=x} rho,
@@ -129,7 +145,7 @@ static void scratch_free(scratch_t *s)
 }
 
 /* One sequence.  Returns 1 if the degenerate all-zero-residual fallback was taken. */
-static int verify_one(int algo, const void *tl, const void *dl, int dtype,
+static int verify_one(int algo, int form, const void *tl, const void *dl, int dtype,
                       const int32_t *X, const float *uni, int gamma, int V, double T,
                       size_t t_off, size_t d_off, scratch_t *s,
                       int32_t *tau_out, int32_t *y_out, double *dbg, double *margins)
@@ -138,9 +154,13 @@ static int verify_one(int algo, const void *tl, const void *dl, int dtype,
 
     /* The 2*gamma+1 distributions along the sample path (inputs of Alg. 1 / Alg. 2). */
     for (int i = 0; i <= gamma; ++i)
-        s->A[i] = softmax_row(tl, dtype, t_off + (size_t)i * Vz, V, T, s->a + i * Vz, s->p + i * Vz);
+        s->A[i] = form == ORACLE_PROBS
+                      ? given_row(tl, dtype, t_off + (size_t)i * Vz, V, s->a + i * Vz, s->p + i * Vz)
+                      : softmax_row(tl, dtype, t_off + (size_t)i * Vz, V, T, s->a + i * Vz, s->p + i * Vz);
     for (int i = 0; i < gamma; ++i)
-        s->Bn[i] = softmax_row(dl, dtype, d_off + (size_t)i * Vz, V, T, s->b + i * Vz, s->q + i * Vz);
+        s->Bn[i] = form == ORACLE_PROBS
+                       ? given_row(dl, dtype, d_off + (size_t)i * Vz, V, s->b + i * Vz, s->q + i * Vz)
+                       : softmax_row(dl, dtype, d_off + (size_t)i * Vz, V, T, s->b + i * Vz, s->q + i * Vz);
     /* q_gamma == 0: the padding row that makes position gamma look like the others (App. A). */
     for (int x = 0; x < V; ++x) s->q[(size_t)gamma * Vz + x] = 0.0;
     s->Bn[gamma] = NAN;
@@ -287,16 +307,16 @@ static int verify_one(int algo, const void *tl, const void *dl, int dtype,
  *   nthreads        host threads over sequences (<=0: runtime default)
  * Returns 0, or -1 on a bad argument, -2 when memory runs out.
  */
-int oracle_spec_verify(int algo, const void *target_logits, const void *draft_logits,
-                       const int32_t *draft_tokens, const float *uniforms,
-                       int B, int gamma, int V, int dtype, double temperature,
-                       int32_t *accept_len, int32_t *next_token,
-                       double *dbg, double *margins, int32_t *n_fallback, int nthreads)
+static int verify_batch(int algo, int form, const void *target_logits, const void *draft_logits,
+                        const int32_t *draft_tokens, const float *uniforms,
+                        int B, int gamma, int V, int dtype, double temperature,
+                        int32_t *accept_len, int32_t *next_token,
+                        double *dbg, double *margins, int32_t *n_fallback, int nthreads)
 {
     if (!target_logits || !draft_logits || !draft_tokens || !uniforms || !accept_len || !next_token)
         return -1;
     if (B < 1 || gamma < 1 || V < 1 || !(temperature > 0.0) || !isfinite(temperature)) return -1;
-    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return -1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F64) return -1;
     if (algo != ORACLE_BLOCK && algo != ORACLE_TOKEN && algo != ORACLE_GREEDY) return -1;
     for (size_t k = 0; k < (size_t)B * gamma; ++k)
         if (draft_tokens[k] < 0 || draft_tokens[k] >= V) return -1;
@@ -318,7 +338,7 @@ int oracle_spec_verify(int algo, const void *target_logits, const void *draft_lo
 #endif
         for (int b = 0; b < B; ++b) {
             if (fail) continue;
-            fb += verify_one(algo, target_logits, draft_logits, dtype,
+            fb += verify_one(algo, form, target_logits, draft_logits, dtype,
                              draft_tokens + (size_t)b * gamma, uniforms + (size_t)b * (gamma + 1),
                              gamma, V, temperature,
                              (size_t)b * (gamma + 1) * V, (size_t)b * gamma * V, &s,
@@ -331,6 +351,32 @@ int oracle_spec_verify(int algo, const void *target_logits, const void *draft_lo
     if (fail) return -2;
     if (n_fallback) *n_fallback = fb;
     return 0;
+}
+
+int oracle_spec_verify(int algo, const void *target_logits, const void *draft_logits,
+                       const int32_t *draft_tokens, const float *uniforms,
+                       int B, int gamma, int V, int dtype, double temperature,
+                       int32_t *accept_len, int32_t *next_token,
+                       double *dbg, double *margins, int32_t *n_fallback, int nthreads)
+{
+    return verify_batch(algo, ORACLE_LOGITS, target_logits, draft_logits, draft_tokens, uniforms, B, gamma, V, dtype,
+                        temperature, accept_len, next_token, dbg, margins, n_fallback, nthreads);
+}
+
+/*
+ * The same with the distributions themselves as inputs (the ps / qs arrays of App. A): target_probs
+ * [B, gamma+1, V] holds p_i(x), draft_probs [B, gamma, V] holds q_i(x), values >= 0, q_{i-1}(X_i) > 0.
+ * The rows are used as given: no temperature, no renormalisation (the draw of Y divides by the sum
+ * of the weights it draws from, whatever that sum is).  dbg columns 3 and 4 are 0.
+ */
+int oracle_spec_verify_probs(int algo, const void *target_probs, const void *draft_probs,
+                             const int32_t *draft_tokens, const float *uniforms,
+                             int B, int gamma, int V, int dtype,
+                             int32_t *accept_len, int32_t *next_token,
+                             double *dbg, double *margins, int32_t *n_fallback, int nthreads)
+{
+    return verify_batch(algo, ORACLE_PROBS, target_probs, draft_probs, draft_tokens, uniforms, B, gamma, V, dtype,
+                        1.0, accept_len, next_token, dbg, margins, n_fallback, nthreads);
 }
 
 /*

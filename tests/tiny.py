@@ -73,10 +73,19 @@ def joint(table, seq):
     return out
 
 
-def _rows(Mb, Ms, xs, gamma):
-    tl = np.stack([Mb.logits[tuple(xs[:i])] for i in range(gamma + 1)])
-    dl = np.stack([Ms.logits[tuple(xs[:i])] for i in range(gamma)])
+def _rows(Mb, Ms, xs, gamma, form="logits"):
+    src_b, src_s = (Mb.logits, Ms.logits) if form == "logits" else (Mb.prob, Ms.prob)
+    tl = np.stack([src_b[tuple(xs[:i])] for i in range(gamma + 1)])
+    dl = np.stack([src_s[tuple(xs[:i])] for i in range(gamma)])
     return tl, dl
+
+
+def _run(form):
+    """The oracle entry for a form of the inputs: "logits" (float32 logits, T = 1) or "probs" (the same
+    models handed over as float64 probability rows)."""
+    if form == "logits":
+        return lambda algo, tl, dl, tok, uni: oracle.verify(algo, tl, dl, tok, uni, 1.0)
+    return lambda algo, tl, dl, tok, uni: oracle.verify_probs(algo, tl, dl, tok, uni, dtype=oracle.F64)
 
 
 def _f32_mid(lo, hi):
@@ -87,18 +96,18 @@ def _f32_mid(lo, hi):
     return None
 
 
-def output_law(algo, Mb, Ms, V, gamma):
+def output_law(algo, Mb, Ms, V, gamma, form="logits"):
     """dict (xs, tau, Y) -> probability, plus per-draft debug blocks and the skipped volume."""
+    run = _run(form)
     law = {}
     dbg_by_draft = {}
     skipped = 0.0
     for xs in itertools.product(range(V), repeat=gamma):
         if joint(Ms, xs) == 0.0:
             continue                                        # a draft the drafter never produces
-        tl, dl = _rows(Mb, Ms, xs, gamma)
+        tl, dl = _rows(Mb, Ms, xs, gamma, form)
         tok = np.asarray(xs, dtype=np.int32)[None]
-        probe = oracle.verify(algo, tl[None], dl[None], tok,
-                              np.zeros((1, gamma + 1), np.float32), 1.0)
+        probe = run(algo, tl[None], dl[None], tok, np.zeros((1, gamma + 1), np.float32))
         dbg = probe["dbg"][0]
         dbg_by_draft[xs] = dbg
         h = dbg[:, 2]
@@ -137,8 +146,7 @@ def output_law(algo, Mb, Ms, V, gamma):
         if n == 0:
             continue
         uni = np.asarray(pts, dtype=np.float32)
-        out = oracle.verify(algo, np.repeat(tl[None], n, 0), np.repeat(dl[None], n, 0),
-                            np.repeat(tok, n, 0), uni, 1.0)
+        out = run(algo, np.repeat(tl[None], n, 0), np.repeat(dl[None], n, 0), np.repeat(tok, n, 0), uni)
         assert out["n_fallback"] == 0
         ms = joint(Ms, xs)
         for k in range(n):
