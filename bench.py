@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=3, help="workload configuration (3 = headline)")
     ap.add_argument("--algo", default="block", choices=["block", "token", "greedy"])
+    ap.add_argument("--input", default="logits", choices=["logits", "probs"],
+                    help="probs: the same workload handed over as probabilities (spec_verify_probs); a side "
+                         "measurement, the headline metric is quoted on logits")
     ap.add_argument("--sets", type=int, default=4, help="distinct input sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", default="default", choices=["default", "staged", "fused"],
@@ -96,8 +99,18 @@ def main():
     y = torch.empty(cfg.B, dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream(dev)
 
+    if args.input == "probs":
+        for s in sets:
+            dt = s["target_logits"].dtype
+            s["target_logits"] = torch.softmax(s["target_logits"].float() / cfg.temperature, -1).to(dt)
+            s["draft_logits"] = torch.softmax(s["draft_logits"].float() / cfg.temperature, -1).to(dt)
+
     def step(i):
         s = sets[i % len(sets)]
+        if args.input == "probs":
+            sv.spec_verify_probs(args.algo, s["target_logits"], s["draft_logits"], s["draft_tokens"], s["uniforms"],
+                                 workspace=ws, accept_len=tau, next_token=y, stream=stream.cuda_stream)
+            return
         fn(s["target_logits"], s["draft_logits"], s["draft_tokens"], s["uniforms"], cfg.temperature,
            workspace=ws, accept_len=tau, next_token=y, stream=stream.cuda_stream)
 
@@ -131,17 +144,20 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "algo": args.algo, "B": cfg.B, "gamma": cfg.gamma, "V": cfg.V,
-                   "logit_dtype": cfg.dtype, "temperature": cfg.temperature, "input_sets": len(sets), "path": args.path},
+                   "logit_dtype": cfg.dtype, "temperature": cfg.temperature, "input_sets": len(sets), "path": args.path,
+                   "input": args.input},
         "seq_verifications_per_s": calls_per_s * cfg.B,
         "mean_accept_len": float(tau.float().mean().item()),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(cfg.name, args.algo) if args.path == "default" else None,
+                     "traffic": measured_traffic(cfg.name, args.algo)
+                     if args.path == "default" and args.input == "logits" else None,
                      "kernel": "whole call: fused_verify_kernel, the call's only kernel on the default path "
-                               "(four staged kernels with --path staged)",
+                               "(four staged kernels with --path staged)" if args.input == "logits" else
+                               "whole call: probs_weights_kernel, probs_residual_kernel, probs_finalize_kernel",
                      "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.input == "logits":
         out["cpu_baseline"] = cpu_baseline(cfg, sets[0])
     print(json.dumps(out), flush=True)
 

@@ -186,6 +186,24 @@ sv_status_t spec_verify_ex(sv_algo_t algo, const void *target_logits, const void
                            float temperature, void *workspace, size_t workspace_bytes,
                            int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream);
 
+/*
+ * The three algorithms with the distributions themselves as inputs, the form of the arrays in the
+ * paper's App. A: target_probs [B, gamma+1, V] holds p_i(x) = M_b(x | c, X^i), draft_probs
+ * [B, gamma, V] holds q_i(x) = M_s(x | c, X^i) (device, dtype, token index contiguous).  The rows are
+ * used as given: there is no temperature and no normalisation; the draw of Y divides by the sum of
+ * the weights it draws from, whatever that sum is.  Contract (unchecked): values finite and >= 0,
+ * every q_{i-1}(X_i) > 0 (the drafter produced X_i), every row with some positive value.  A drafted
+ * token with p_{i-1}(X_i) = 0 has ratio 0 and is never accepted.  draft_lens, the row strides and all
+ * other arguments as for spec_verify_ex; the workspace is the same one (its initialised state is
+ * neither needed nor disturbed).  Every element is read from device memory once, in three launches.
+ */
+sv_status_t spec_verify_probs(sv_algo_t algo, const void *target_probs, const void *draft_probs,
+                              const int32_t *draft_tokens, const int32_t *draft_lens,
+                              int64_t target_row_stride, int64_t draft_row_stride, const float *uniforms,
+                              int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                              void *workspace, size_t workspace_bytes,
+                              int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream);
+
 const char *spec_verify_status_string(sv_status_t status);
 
 #ifdef __cplusplus

@@ -35,6 +35,7 @@ EXPORTED = (
     "spec_verify_token",
     "spec_verify_greedy",
     "spec_verify_ex",
+    "spec_verify_probs",
     "spec_verify_status_string",
 )
 
@@ -72,6 +73,8 @@ def load() -> ctypes.CDLL:
         lib.spec_verify_ex.restype = ctypes.c_int
         lib.spec_verify_ex.argtypes = ([ctypes.c_int] + _VERIFY_ARGTYPES[:3]
                                        + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64] + _VERIFY_ARGTYPES[3:])
+        lib.spec_verify_probs.restype = ctypes.c_int
+        lib.spec_verify_probs.argtypes = [a for j, a in enumerate(lib.spec_verify_ex.argtypes) if j != 12]   # no temperature
         lib.spec_verify_workspace_init.restype = ctypes.c_int
         lib.spec_verify_workspace_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
                                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
@@ -207,7 +210,7 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
     for t, want in ((draft_tokens, torch.int32), (uniforms, torch.float32)):
         if t.dtype != want:
             raise TypeError(f"expected {want}, got {t.dtype}")
-    extended = name == "spec_verify_ex"
+    extended = name in ("spec_verify_ex", "spec_verify_probs")
     for t in (target_logits, draft_logits, draft_tokens, uniforms):
         if t.device != dev:
             raise ValueError("inputs must be on one device")
@@ -234,7 +237,7 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
     code = getattr(lib, name)(
         *head, target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), *after_tokens,
         uniforms.data_ptr(),
-        B, gamma, V, _dtype_code(target_logits), float(temperature),
+        B, gamma, V, _dtype_code(target_logits), *(() if name == "spec_verify_probs" else (float(temperature),)),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         accept_len.data_ptr(), next_token.data_ptr(),
         debug_out.data_ptr() if debug_out is not None else None, stream)
@@ -249,6 +252,14 @@ def spec_verify_ex(algo, target_logits, draft_logits, draft_tokens, uniforms, te
     draft_lens[b] draft positions; the logits may be ``[..., :V]`` views of buffers whose last dimension is
     padded (the row strides are taken from the tensors)."""
     return _call("spec_verify_ex", target_logits, draft_logits, draft_tokens, uniforms, temperature,
+                 draft_lens=draft_lens, algo=algo, **kw)
+
+
+def spec_verify_probs(algo, target_probs, draft_probs, draft_tokens, uniforms, draft_lens=None, **kw):
+    """`algo` ("block", "token" or "greedy") on distributions handed over as probabilities (the arrays of the
+    paper's App. A), used as given: see `spec_verify_probs` in the header.  ``draft_lens`` and padded rows as for
+    `spec_verify_ex`."""
+    return _call("spec_verify_probs", target_probs, draft_probs, draft_tokens, uniforms, None,
                  draft_lens=draft_lens, algo=algo, **kw)
 
 

@@ -2,7 +2,8 @@
 //
 // Host side only: argument checks, workspace layout and kernel launches.  The kernels are in
 // fused.hpp (one launch, every logit read from HBM once; the default) and staged.hpp (four
-// launches, no limit on the vocabulary size).
+// launches, no limit on the vocabulary size); probs.hpp holds the kernels for inputs that are
+// probabilities already.
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -12,6 +13,7 @@
 #include "../../include/specverify.h"
 #include "common.hpp"
 #include "fused.hpp"
+#include "probs.hpp"
 #include "sample.hpp"
 #include "staged.hpp"
 
@@ -117,6 +119,32 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
+// Probabilities as inputs: three launches, every element read once.  Scratch: the staged path's areas
+// (chunk partial sums where its row statistics go, the weights where its row constants go).
+template <typename T, bool ALIGNED>
+sv_status_t launch_probs(int algo, const void *target_v, const void *draft_v, const int32_t *tokens, const int32_t *draft_lens,
+                         size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, const Layout &L,
+                         char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out, hipStream_t stream)
+{
+    static_assert(sizeof(ProbWeight) <= sizeof(SeqCoef), "the weights reuse the staged path's row-constant area");
+    const T *target = static_cast<const T *>(target_v);
+    const T *draft = static_cast<const T *>(draft_v);
+    float2 *part = reinterpret_cast<float2 *>(ws + L.off_stats);
+    ProbWeight *weights = reinterpret_cast<ProbWeight *>(ws + L.off_coef);
+    const unsigned blocks = (unsigned)((size_t)B * (gamma + 1) * L.nchunks);
+    probs_weights_kernel<T><<<B, 64, 0, stream>>>(target, draft, tstride, dstride, tokens, draft_lens, gamma, algo, weights);
+    if (algo == kGreedy)
+        probs_residual_kernel<T, ALIGNED, true><<<blocks, kThreads, 0, stream>>>(
+            target, draft, tstride, dstride, draft_lens, gamma, V, L.nchunks, part, weights);
+    else
+        probs_residual_kernel<T, ALIGNED, false><<<blocks, kThreads, 0, stream>>>(
+            target, draft, tstride, dstride, draft_lens, gamma, V, L.nchunks, part, weights);
+    probs_finalize_kernel<T, ALIGNED><<<B, kThreads, 2 * (gamma + 1) * sizeof(double), stream>>>(
+        target, draft, tstride, dstride, uniforms, draft_lens, gamma, V, L.nchunks, algo, part, weights,
+        accept_len, next_token, debug_out);
+    return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
 template <typename T, bool ALIGNED>
 sv_status_t launch_fused(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
                          size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
@@ -165,7 +193,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
-sv_status_t verify_entry(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
+sv_status_t verify_entry(int algo, bool probs, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
                          int64_t target_row_stride, int64_t draft_row_stride,
                          const float *uniforms, int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
                          float temperature, void *workspace, size_t workspace_bytes,
@@ -174,7 +202,7 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
     if (!target || !draft || !tokens || !uniforms || !workspace || !accept_len || !next_token)
         return SV_ERR_INVALID_ARG;
     if (B < 1 || gamma < 1 || V < 1) return SV_ERR_INVALID_ARG;
-    if (!(temperature > 0.f) || !isfinite(temperature)) return SV_ERR_INVALID_ARG;
+    if (!probs && (!(temperature > 0.f) || !isfinite(temperature))) return SV_ERR_INVALID_ARG;
     if (dtype != SV_DTYPE_F32 && dtype != SV_DTYPE_BF16) return SV_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SV_ERR_INVALID_ARG;
     Layout L;
@@ -193,6 +221,13 @@ sv_status_t verify_entry(int algo, const void *target, const void *draft, const 
                          ((size_t)V * esize) % 16 == 0 && (tstride * esize) % 16 == 0 && (dstride * esize) % 16 == 0;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     char *ws = static_cast<char *>(workspace);
+    if (probs) {
+#define SV_PROBS(TT, AL) launch_probs<TT, AL>(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, \
+                                              L, ws, accept_len, next_token, debug_out, stream)
+        return dtype == SV_DTYPE_F32 ? (aligned ? SV_PROBS(float, true) : SV_PROBS(float, false))
+                                     : (aligned ? SV_PROBS(bf16_t, true) : SV_PROBS(bf16_t, false));
+#undef SV_PROBS
+    }
     const int path = g_path.load();
     if (path == 2 && !L.fused_ok) return SV_ERR_UNSUPPORTED;
 
@@ -302,7 +337,7 @@ sv_status_t spec_verify_block(const void *target_logits, const void *draft_logit
                               float temperature, void *workspace, size_t workspace_bytes,
                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kBlock, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
+    return verify_entry(kBlock, false, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
@@ -312,7 +347,7 @@ sv_status_t spec_verify_token(const void *target_logits, const void *draft_logit
                               float temperature, void *workspace, size_t workspace_bytes,
                               int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kToken, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
+    return verify_entry(kToken, false, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
@@ -322,7 +357,7 @@ sv_status_t spec_verify_greedy(const void *target_logits, const void *draft_logi
                                float temperature, void *workspace, size_t workspace_bytes,
                                int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
 {
-    return verify_entry(kGreedy, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
+    return verify_entry(kGreedy, false, target_logits, draft_logits, draft_tokens, nullptr, 0, 0, uniforms, B, gamma, V, dtype,
                         temperature, workspace, workspace_bytes, accept_len, next_token, debug_out, stream);
 }
 
@@ -335,8 +370,22 @@ sv_status_t spec_verify_ex(sv_algo_t algo, const void *target_logits, const void
 {
     if (algo != SV_ALGO_BLOCK && algo != SV_ALGO_TOKEN && algo != SV_ALGO_GREEDY) return SV_ERR_INVALID_ARG;
     const int a = algo == SV_ALGO_BLOCK ? kBlock : algo == SV_ALGO_TOKEN ? kToken : kGreedy;
-    return verify_entry(a, target_logits, draft_logits, draft_tokens, draft_lens, target_row_stride, draft_row_stride,
+    return verify_entry(a, false, target_logits, draft_logits, draft_tokens, draft_lens, target_row_stride, draft_row_stride,
                         uniforms, B, gamma, V, dtype, temperature, workspace, workspace_bytes, accept_len, next_token,
+                        debug_out, stream);
+}
+
+sv_status_t spec_verify_probs(sv_algo_t algo, const void *target_probs, const void *draft_probs,
+                              const int32_t *draft_tokens, const int32_t *draft_lens,
+                              int64_t target_row_stride, int64_t draft_row_stride, const float *uniforms,
+                              int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
+                              void *workspace, size_t workspace_bytes,
+                              int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
+{
+    if (algo != SV_ALGO_BLOCK && algo != SV_ALGO_TOKEN && algo != SV_ALGO_GREEDY) return SV_ERR_INVALID_ARG;
+    const int a = algo == SV_ALGO_BLOCK ? kBlock : algo == SV_ALGO_TOKEN ? kToken : kGreedy;
+    return verify_entry(a, true, target_probs, draft_probs, draft_tokens, draft_lens, target_row_stride, draft_row_stride,
+                        uniforms, B, gamma, V, dtype, 1.f, workspace, workspace_bytes, accept_len, next_token,
                         debug_out, stream);
 }
 

@@ -136,3 +136,18 @@ def test_extended_entry_validates_its_arguments():
     assert call(B=0) == binding.SV_ERR_INVALID_ARG
     assert call(ts=99) == binding.SV_ERR_INVALID_ARG       # a stride below V
     assert call(ds=-1) == binding.SV_ERR_INVALID_ARG
+
+
+def test_probs_entry_validates_its_arguments():
+    lib = sv.load()
+
+    def call(algo=0, target=0x1000, B=2, ts=0, dtype=0, ws_bytes=1 << 30):
+        return lib.spec_verify_probs(algo, target, 0x1000, 0x1000, None, ts, 0, 0x1000, B, 3, 100, dtype, 0x1000,
+                                     ws_bytes, 0x1000, 0x1000, None, None)
+
+    assert call(algo=7) == binding.SV_ERR_INVALID_ARG
+    assert call(target=None) == binding.SV_ERR_INVALID_ARG
+    assert call(B=0) == binding.SV_ERR_INVALID_ARG
+    assert call(ts=50) == binding.SV_ERR_INVALID_ARG
+    assert call(dtype=9) == binding.SV_ERR_INVALID_ARG
+    assert call(ws_bytes=16) == binding.SV_ERR_WORKSPACE_TOO_SMALL
