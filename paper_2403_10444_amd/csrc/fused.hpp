@@ -393,10 +393,23 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     // row's first unit published them
     double my_Lp = 0.0, my_Lq = 0.0, my_lr = 0.0;
     float my_Mp = 0.f;
+    // everything the tests need is asked for at once (one round trip instead of three): the rows' words, log2 w,
+    // the uniforms and the first batch of partial sums; what is not there yet is polled where it is used
+    const u64 *lw_word = P.lw + (size_t)b * G + (lane < gamma ? lane : gamma - 1);
+    const float *eta = P.uniforms + (size_t)b * (G + 1);
+    u64 lw_first = 0;
+    unsigned sw_first[kBatch], rw_first[kBatch];
     {
         const size_t drow = (size_t)b * G + (lane < gamma ? lane : gamma - 1);
         u64 w0 = ld_u64(P.ratio + drow), w1 = ld_u64(P.rowstat + drow * 3), w2 = ld_u64(P.rowstat + drow * 3 + 1),
             w3 = ld_u64(P.rowstat + drow * 3 + 2);
+        if (P.algo != kToken) lw_first = ld_u64(lw_word);
+#pragma unroll
+        for (int jj = 0; jj < kBatch; ++jj) {
+            const int j = jj < gamma ? jj : gamma - 1;
+            sw_first[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
+            if constexpr (GREEDY) rw_first[jj] = ld_u32(P.rpart + ((size_t)b * G + j) * nu + e_lane);
+        }
         w0 = wait_word(P.ratio + drow, w0, lane < gamma, P.spin_limit, gave_up);
         w1 = wait_word(P.rowstat + drow * 3, w1, lane < gamma, P.spin_limit, gave_up);
         w2 = wait_word(P.rowstat + drow * 3 + 1, w2, lane < gamma, P.spin_limit, gave_up);
@@ -409,8 +422,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     // drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, lw_last = 0.0;
     if (P.algo != kToken) {
-        const u64 *word = P.lw + (size_t)b * G + (lane < gamma ? lane : gamma - 1);
-        const double next = unpack_ratio(wait_word(word, ld_u64(word), lane < gamma, P.spin_limit, gave_up));   // log2 w_{lane+1}
+        const double next = unpack_ratio(wait_word(lw_word, lw_first, lane < gamma, P.spin_limit, gave_up));   // log2 w_{lane+1}
         const double prev = __shfl_up(next, 1, kWave);
         my_lw = lane ? prev : 0.0;
         lw_last = read_lane_double(next, gamma - 1);
@@ -419,7 +431,6 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     FSTAMP(8);
     // what the accept tests need of w_j is formed now, before the wait for the partial sums: lane l tests
     // position j = l + 1, whose row values sit in lane j
-    const float *eta = P.uniforms + (size_t)b * (G + 1);
     const int j = lane + 1;
     const double lw_below = __shfl_down(my_lw, 1, kWave);
     const double lw_j = j < gamma ? lw_below : lw_last;
@@ -436,8 +447,13 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
 #pragma unroll
         for (int jj = 0; jj < kBatch; ++jj) {
             const int j = j0 + jj < gamma ? j0 + jj : gamma - 1;
-            sw[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
-            if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + ((size_t)b * G + j) * nu + e_lane);
+            if (j0 == 0) {                               // asked for at the start
+                sw[jj] = sw_first[jj];
+                if constexpr (GREEDY) rw[jj] = rw_first[jj];
+            } else {
+                sw[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
+                if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + ((size_t)b * G + j) * nu + e_lane);
+            }
         }
 #pragma unroll
         for (int jj = 0; jj < kBatch; ++jj) {
@@ -550,6 +566,17 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     }
     if (slot < 0) { slot = 0; t_in = INFINITY; }
 
+    // ---- the sequence's words are left zero for the next call.  Every reader of the row-pair words has published
+    // its partial sum by now and this wave has read all of those, so all but the target rows' words (needed once
+    // more below) can go now, under the latency of the loads that follow.
+    for (int e = lane; e < G * nu; e += kWave) {
+        st_u32(P.spart + (size_t)b * G * nu + e, 0);
+        if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * G * nu + e, 0);
+    }
+    for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
+    for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); }
+    for (int e = lane; e < 3 * G; e += kWave) st_u64(P.rowstat + (size_t)b * G * 3 + e, 0);
+
     FSTAMP(11);
     // ---- ... then the token inside that chunk: weights recomputed from the logits, walked in
     // vocabulary order (vector, lane, element)
@@ -616,18 +643,10 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     }
 
     FSTAMP(12);
-    // ---- leave the sequence's words zero for the next call.  Every reader of the row-pair words has
-    // published its partial sum by now; the words of the last target row must all be written first.
+    // ---- the target rows' words: those of the last target row must all be written first
     for (int e = lane; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     for (int e = lane; e < (G + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
-    for (int e = lane; e < G * nu; e += kWave) {
-        st_u32(P.spart + (size_t)b * G * nu + e, 0);
-        if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * G * nu + e, 0);
-    }
-    for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
-    for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); }
-    for (int e = lane; e < 3 * G; e += kWave) st_u64(P.rowstat + (size_t)b * G * 3 + e, 0);
 }
 
 // ------------------------------------------------------------------ the kernel
