@@ -140,3 +140,33 @@ def test_float32_and_bf16_probability_rows_are_upcast_exactly():
     for other in (b, c):
         assert np.array_equal(a["accept_len"], other["accept_len"]) and np.array_equal(a["next_token"], other["next_token"])
         assert np.array_equal(a["dbg"][:, :, :3], other["dbg"][:, :, :3])
+
+
+# ---------------------------------------------------------------- greedy block verification (Alg. 4)
+@pytest.mark.parametrize("V,gamma", [(2, 2), (3, 2), (3, 3)])
+def test_greedy_joint_acceptance_is_min_of_joints_probability_form(V, gamma):
+    """Lemma on greedy block verification: Pr(X^l = x^l, tau >= l) = min{M_b(x^l), M_s(x^l)}."""
+    rng = np.random.default_rng(31 * V + gamma)
+    Mb = tiny.random_tables(rng, V, gamma)
+    Ms = tiny.random_tables(rng, V, gamma)
+    law, _, skipped = tiny.output_law(oracle.GREEDY, Mb, Ms, V, gamma, form="probs")
+    assert skipped < 1e-9
+    for l in range(1, gamma + 1):
+        for prefix in itertools.product(range(V), repeat=l):
+            got = sum(m for (xs, tau, _), m in law.items() if xs[:l] == prefix and tau >= l)
+            assert got == pytest.approx(min(tiny.joint(Mb, prefix), tiny.joint(Ms, prefix)), abs=1e-12)
+
+
+@pytest.mark.parametrize("V,gamma", CASES)
+def test_expected_accept_length_ordering_probability_form(V, gamma):
+    """Theorem 2 (block >= token in expected accepted length) and the greedy upper bound sum_l sum_x min{M_s, M_b}."""
+    rng = np.random.default_rng(400 * V + gamma)
+    Mb = tiny.random_tables(rng, V, gamma)
+    Ms = tiny.random_tables(rng, V, gamma)
+    e = {a: _expected_tau(tiny.output_law(a, Mb, Ms, V, gamma, form="probs")[0])
+         for a in (oracle.BLOCK, oracle.TOKEN, oracle.GREEDY)}
+    bound = sum(min(tiny.joint(Mb, x), tiny.joint(Ms, x))
+                for l in range(1, gamma + 1) for x in itertools.product(range(V), repeat=l))
+    assert e[oracle.TOKEN] <= e[oracle.BLOCK] + 1e-12
+    assert e[oracle.BLOCK] <= e[oracle.GREEDY] + 1e-12
+    assert e[oracle.GREEDY] == pytest.approx(bound, abs=1e-11)
