@@ -19,6 +19,8 @@
 
 namespace sv {
 
+constexpr int kProbsKeepMax = 8192;      // chunk sums of one sequence that the finishing kernel keeps in LDS (32 KB)
+
 struct ProbWeight {
     double w;            // w_i (1 for token verification, whose residual is p - q)
     double one_minus_w;
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
     int gamma, int V, int nchunks, int algo, const float2 *__restrict__ part, const ProbWeight *__restrict__ weights,
     int32_t *__restrict__ accept_len, int32_t *__restrict__ next_token, float *__restrict__ debug_out)
 {
-    extern __shared__ double smd[];                     // [gamma+1] S_i, [gamma+1] rejected mass
+    extern __shared__ double smd[];                     // [gamma+1] S_i, [gamma+1] rejected mass, then the kept partial sums
     __shared__ double wave_tot[kWaves];
     __shared__ int s_tau, s_chunk, s_mode, s_winner, s_cand;
     __shared__ double s_t, s_total;
@@ -197,11 +199,26 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
     const ProbWeight *wb = weights + (size_t)b * (gamma + 1);
     const float2 *pb = part + (size_t)b * (gamma + 1) * nchunks;
     const float *eta = uniforms + (size_t)b * (gamma + 1);
+    // the chunk sums stay in LDS for the draw when they fit (the host sizes the dynamic LDS to match)
+    const bool keep = (gamma + 1) * nchunks <= kProbsKeepMax;
+    float *kept = reinterpret_cast<float *>(smd + 2 * (gamma + 1));
+
+    // what the accept tests need besides the sums is asked for now, so that it arrives together with them
+    ProbWeight pw = {};
+    float eta_i = 0.f, u = 0.f;
+    if (wave == 0) {
+        if (lane + 1 <= gb) { pw = wb[lane + 1]; eta_i = eta[lane]; }
+        u = eta[gb];
+    }
 
     // S_i = sum over the chunks: wave (i mod 4) takes position i, lanes stride over the chunks
     for (int i = wave; i <= gb; i += kWaves) {
         double acc = 0.0, rej = 0.0;
-        for (int c = lane; c < nchunks; c += 64) { const float2 v = pb[(size_t)i * nchunks + c]; acc += (double)v.x; rej += (double)v.y; }
+        for (int c = lane; c < nchunks; c += 64) {
+            const float2 v = pb[(size_t)i * nchunks + c];
+            if (keep) kept[i * nchunks + c] = v.x;
+            acc += (double)v.x; rej += (double)v.y;
+        }
         acc = wave_sum_double(acc);
         rej = wave_sum_double(rej);
         if (lane == 0) { S[i] = acc; R[i] = rej; }
@@ -213,13 +230,12 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
         const int i = lane + 1;
         bool pass = false;
         if (i <= gb) {
-            const ProbWeight pw = wb[i];
             double h;
             if (algo == kToken) h = pw.h_token;                                         // min(r_i, 1)
             else if (i == gb) h = fmin(pw.w, 1.0);                                      // h_gamma = w_gamma
             else if (algo == kGreedy) h = R[i] > 0.0 ? fmin(S[i] / R[i], 1.0) : 1.0;    // p_remain / p_rej
             else h = pw.w >= 1.0 ? 1.0 : S[i] / (S[i] + pw.one_minus_w);                // block acceptance formula
-            pass = (double)eta[i - 1] < h;
+            pass = (double)eta_i < h;
             if (debug_out) {
                 float *d = debug_out + ((size_t)b * (gamma + 1) + i) * 3;
                 // q == 0 at the last position: the residual mass there is w times the row's own sum
@@ -273,17 +289,17 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
             scan_chunk(c, false, mine, below, total);
             row_total += total;
         }
-        if (tid == 0) { s_total = (double)eta[gb] * row_total; s_winner = -1; s_cand = -1; }
+        if (tid == 0) { s_total = (double)u * row_total; s_winner = -1; s_cand = -1; }
     } else if (wave == 0) {
         // pick the chunk of row tau that holds t = u * (total weight): 64 chunk sums at a time, scanned in order
         const double total = mode == 1 ? S[gb] : S[tau];
-        const double t = (double)eta[gb] * total;
+        const double t = (double)u * total;
         const float2 *pp = pb + (size_t)tau * nchunks;
         int chunk = -1, last_nonzero = 0;
         double carry = 0.0, t_in = INFINITY;
         for (int c0 = 0; c0 < nchunks && chunk < 0; c0 += 64) {
             const int c = c0 + lane;
-            const double v = c < nchunks ? (double)pp[c].x : 0.0;
+            const double v = c < nchunks ? (double)(keep ? kept[tau * nchunks + c] : pp[c].x) : 0.0;
             const double inc = wave_inclusive_scan_double(v) + carry;
             const unsigned long long nz = __ballot(v > 0.0), hit = __ballot(c < nchunks && inc > t);
             if (nz) last_nonzero = c0 + 63 - __clzll((long long)nz);

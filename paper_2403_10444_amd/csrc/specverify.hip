@@ -139,7 +139,8 @@ sv_status_t launch_probs(int algo, const void *target_v, const void *draft_v, co
     else
         probs_residual_kernel<T, ALIGNED, false><<<blocks, kThreads, 0, stream>>>(
             target, draft, tstride, dstride, draft_lens, gamma, V, L.nchunks, part, weights);
-    probs_finalize_kernel<T, ALIGNED><<<B, kThreads, 2 * (gamma + 1) * sizeof(double), stream>>>(
+    const size_t keep = (size_t)(gamma + 1) * L.nchunks <= (size_t)kProbsKeepMax ? (size_t)(gamma + 1) * L.nchunks * sizeof(float) : 0;
+    probs_finalize_kernel<T, ALIGNED><<<B, kThreads, 2 * (gamma + 1) * sizeof(double) + keep, stream>>>(
         target, draft, tstride, dstride, uniforms, draft_lens, gamma, V, L.nchunks, algo, part, weights,
         accept_len, next_token, debug_out);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
