@@ -221,6 +221,27 @@ def test_runs_on_a_side_stream():
     assert np.array_equal(tau.cpu().numpy(), ref["accept_len"]) and np.array_equal(y.cpu().numpy(), ref["next_token"])
 
 
+def test_two_calls_overlap_on_two_streams_with_their_own_workspaces():
+    """Calls are re-entrant given disjoint workspaces: two calls launched on two streams without a
+    synchronisation between them (their kernels share the device) give what each gives alone."""
+    cfg = _custom(32, 4, 60000, "bf16", sigma_t=2.5, sigma_d=1.0, T=0.9)
+    inps = [workloads.generate(cfg, seed=60 + i, device=DEV) for i in range(2)]
+    refs = [parity.run_gpu("block", inp, cfg.temperature) for inp in inps]
+    wss = [sv.alloc_workspace(cfg.B, cfg.gamma, cfg.V, DEV) for _ in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        outs = []
+        for inp, ws, st in zip(inps, wss, streams):
+            with torch.cuda.stream(st):
+                outs.append(sv.spec_verify_block(inp["target_logits"], inp["draft_logits"], inp["draft_tokens"],
+                                                 inp["uniforms"], cfg.temperature, workspace=ws))
+        torch.cuda.synchronize()
+        for (tau, y), ref, ws in zip(outs, refs, wss):
+            assert np.array_equal(tau.cpu().numpy(), ref["accept_len"]) and np.array_equal(y.cpu().numpy(), ref["next_token"])
+            assert sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V) == 0
+
+
 @pytest.mark.parametrize("algo", ["block", "token", "greedy"])
 @pytest.mark.parametrize("kt,kd", [(50, 50), (20, 200), (500, 5), (1, 40)])
 def test_masked_logits_top_k(algo, kt, kd):
