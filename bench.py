@@ -68,7 +68,7 @@ def main():
                          "measurement, the headline metric is quoted on logits")
     ap.add_argument("--sets", type=int, default=4, help="distinct input sets rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--path", default="default", choices=["default", "staged", "fused"],
+    ap.add_argument("--path", default="default", choices=["default", "staged", "fused", "fused-small", "fused-large"],
                     help="kernel path (testing hook of the library)")
     ap.add_argument("--spin-limit", type=int, default=-1,
                     help="bound of the fused kernel's waits in polls (testing hook; 0 makes results invalid)")
@@ -86,7 +86,7 @@ def main():
     import workloads
 
     sv.load()
-    sv.spec_verify_debug_config({"default": 0, "staged": 1, "fused": 2}[args.path], args.spin_limit)
+    sv.spec_verify_debug_config({"default": 0, "staged": 1, "fused": 2, "fused-small": 3, "fused-large": 4}[args.path], args.spin_limit)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -82,8 +82,11 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
 /* Testing hook, process-wide: `path` 0 = the library's choice (the fused kernel where it
  * takes the shape, else the staged kernels), 1 = the four-launch staged kernels, 2 = the
  * single-launch fused kernel (takes V <= 128 * 8192 and a device that keeps four rows'
- * workgroups resident; other shapes are then refused); `spin_limit` bounds every wait
- * inside the fused kernel in polls (negative: default).                                  */
+ * workgroups resident; other shapes are then refused), 3 / 4 = the fused kernel with its
+ * small / large units (32 / 64 logits of a row per lane; large ones exist for bf16 rows on
+ * the 16-byte path only, other calls use the small ones; the library's own choice depends on
+ * the shape); `spin_limit` bounds every wait inside the fused kernel in polls (negative:
+ * default).                                                                               */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);
 
 /* Tuning hook, process-wide: when `device_buffer` is not NULL the fused kernel stores up to

@@ -6,11 +6,11 @@
 // sweep never touches memory: the first sweep's exponentials stay in registers until the
 // row's normalisers are known.
 //
-// A *unit* is 2048 contiguous logits of a (target row i, draft row i) pair - the last target
-// row, which has no draft row, counts as a pair without its second half - and belongs to one
-// wavefront; a workgroup is four waves (four neighbouring units).  A wave
-//   1. loads its 2 x 2048 logits (32 + 32 per lane, 16-byte loads, 1 KB per load instruction),
-//   2. turns them into exp2(y - shift) with a wave-uniform shift per row and KEEPS those 2 x 32
+// A *unit* is 64 * LANE contiguous logits (LANE = 32 or 64 per lane: 2048 or 4096) of a (target row i,
+// draft row i) pair - the last target row, which has no draft row, counts as a pair without its second
+// half - and belongs to one wavefront; a workgroup is four waves (four neighbouring units).  A wave
+//   1. loads its 2 x 64 * LANE logits (16-byte loads, 1 KB per load instruction),
+//   2. turns them into exp2(y - shift) with a wave-uniform shift per row and KEEPS those 2 x LANE
 //      floats per lane in registers; its partial normalisers (shift, sum) meet those of the
 //      workgroup's other waves in LDS,
 //   3. sleeps at a barrier while the workgroup's first wave publishes the workgroup's two words,
@@ -46,8 +46,10 @@
 namespace sv {
 
 constexpr int kWave = 64;
-constexpr int kLaneLogits = 32;                      // logits of one row that a lane holds of a unit
-constexpr int kUnitLogits = kWave * kLaneLogits;    // contiguous logits of one row in a unit
+// LANE, a template parameter of the kernel: logits of one row that a lane holds of a unit, 32 or 64.  A unit is
+// kWave * LANE contiguous logits of one row; fatter units mean fewer workgroups per row to wait for and the
+// fixed registers of a wave spread over more logits (bf16 rows only: 161 VGPRs, 3 waves per SIMD).
+constexpr int kLaneSmall = 32, kLaneLarge = 64;
 constexpr int kMaxUnitsPerRow = 512;     // wave chunks per row the fused kernel takes (V <= 1 Mi logits): 8 words per lane
 
 // Word 0 of an initialised workspace: a constant mixed with the shape it was initialised for.
@@ -240,29 +242,30 @@ __device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit
 }
 
 // The logits a lane holds of one row, as loaded: raw 16-byte vectors on the aligned path.
-template <typename T, bool ALIGNED> struct RawSlice;
-template <typename T> struct RawSlice<T, true> {
-    static constexpr int kNV = kLaneLogits / ElemTraits<T>::kVec;
+template <typename T, bool ALIGNED, int LANE> struct RawSlice;
+template <typename T, int LANE> struct RawSlice<T, true, LANE> {
+    static constexpr int kNV = LANE / ElemTraits<T>::kVec;
     uint4 v[kNV];
 };
-template <typename T> struct RawSlice<T, false> { };      // the element-wise path loads when it unpacks
+template <typename T, int LANE> struct RawSlice<T, false, LANE> { };      // the element-wise path loads when it unpacks
 
 // Vector v of a lane starts at element first + v * 64 * kVec of the row, so one load instruction of
 // the wave covers 1 KB of contiguous memory.
-template <typename T, bool ALIGNED>
-__device__ __forceinline__ void issue_loads(const T *row, int unit_first, int V, RawSlice<T, ALIGNED> &raw)
+template <typename T, bool ALIGNED, int LANE>
+__device__ __forceinline__ void issue_loads(const T *row, int unit_first, int V, RawSlice<T, ALIGNED, LANE> &raw)
 {
+    constexpr int kUnitLogits = kWave * LANE;
     if constexpr (ALIGNED) {
         constexpr int kVec = ElemTraits<T>::kVec;
         const char *base = reinterpret_cast<const char *>(row);
         const unsigned lane_off = (unsigned)(unit_first + (int)(threadIdx.x & 63) * kVec) * (unsigned)sizeof(T);
         if (unit_first + kUnitLogits <= V) {                   // wave-uniform: the whole unit lies inside the row
 #pragma unroll
-            for (int v = 0; v < RawSlice<T, true>::kNV; ++v)
+            for (int v = 0; v < RawSlice<T, true, LANE>::kNV; ++v)
                 raw.v[v] = *reinterpret_cast<const uint4 *>(base + (lane_off + (unsigned)(v * kWave * 16)));
         } else {
 #pragma unroll
-            for (int v = 0; v < RawSlice<T, true>::kNV; ++v) {
+            for (int v = 0; v < RawSlice<T, true, LANE>::kNV; ++v) {
                 const unsigned off = lane_off + (unsigned)(v * kWave * 16);
                 // vectors beyond the row are recognised again when the slice is unpacked; load something valid
                 raw.v[v] = *reinterpret_cast<const uint4 *>(base + (off < (unsigned)V * (unsigned)sizeof(T) ? off : 0u));
@@ -283,12 +286,13 @@ __device__ __forceinline__ void unpack_vec(const uint4 &v, float *out)
     }
 }
 
-template <typename T, bool ALIGNED>
-__device__ __forceinline__ void unpack_slice(const T *row, int unit_first, int V, const RawSlice<T, ALIGNED> &raw,
-                                             float (&x)[kLaneLogits])
+template <typename T, bool ALIGNED, int LANE>
+__device__ __forceinline__ void unpack_slice(const T *row, int unit_first, int V, const RawSlice<T, ALIGNED, LANE> &raw,
+                                             float (&x)[LANE])
 {
     constexpr int kVec = ElemTraits<T>::kVec;
-    constexpr int kNV = kLaneLogits / kVec;
+    constexpr int kNV = LANE / kVec;
+    constexpr int kUnitLogits = kWave * LANE;
     const int first = unit_first + (int)(threadIdx.x & 63) * kVec;
     if constexpr (ALIGNED) {
 #pragma unroll
@@ -312,16 +316,17 @@ __device__ __forceinline__ void unpack_slice(const T *row, int unit_first, int V
 // First sweep over the logits the wave holds of one row: x[j] becomes exp2(x[j] * k - shift) with
 // the wave-uniform shift = k * (largest logit of the unit), or 0 when the whole unit lies beyond
 // the row.  Returns the unit's word: (k * largest logit, sum of the exponentials); (-inf, 0) beyond.
-__device__ __forceinline__ u64 first_sweep_row(float (&x)[kLaneLogits], float k, float &shift)
+template <int LANE>
+__device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float &shift)
 {
     float m = x[0];
 #pragma unroll
-    for (int j = 1; j < kLaneLogits; ++j) m = fmaxf(m, x[j]);
+    for (int j = 1; j < LANE; ++j) m = fmaxf(m, x[j]);
     const float Mw = wave_max(m * k);
     shift = Mw > -INFINITY ? Mw : 0.f;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};     // four partial sums: shorter chains, smaller rounding error
 #pragma unroll
-    for (int j = 0; j < kLaneLogits; ++j) {
+    for (int j = 0; j < LANE; ++j) {
         x[j] = fast_exp2(__builtin_fmaf(x[j], k, -shift));
         acc[j & 3] += x[j];
     }
@@ -372,11 +377,12 @@ __device__ __forceinline__ double read_lane_double(double v, int lane)
 
 // Accept tests and inverse-CDF draw of one sequence (one wave).  What does not need the residual
 // sums (normalisers, ratios, w) is done first, while the sequence's last units are still at work.
-template <typename T, bool ALIGNED, bool GREEDY>
+template <typename T, bool ALIGNED, bool GREEDY, int LANE>
 __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, int gamma)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
-    constexpr int kNV = kLaneLogits / kVec;
+    constexpr int kNV = LANE / kVec;
+    constexpr int kUnitLogits = kWave * LANE;
     constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
     const int lane = threadIdx.x & 63;
     // `gamma` is this sequence's draft length; G, the call's (largest) draft length, is the stride of every array
@@ -650,11 +656,12 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
 }
 
 // ------------------------------------------------------------------ the kernel
-template <typename T, bool ALIGNED, bool GREEDY, int NW>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ElemTraits<T>::kVec == 8 ? 5 : 4)))
+template <typename T, bool ALIGNED, bool GREEDY, int NW, int LANE>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(LANE == kLaneLarge ? 3 : ElemTraits<T>::kVec == 8 ? 5 : 4)))
 void fused_verify_kernel(const FusedParams P)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
+    constexpr int kUnitLogits = kWave * LANE;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int gamma = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
@@ -681,9 +688,9 @@ void fused_verify_kernel(const FusedParams P)
     const T *rowA = static_cast<const T *>(P.target) + trow * P.tstride;
     const T *rowB = static_cast<const T *>(P.draft) + drow * P.dstride;
     const int unit_first = U.c * kUnitLogits;
-    RawSlice<T, ALIGNED> rawA, rawB;
-    issue_loads<T, ALIGNED>(rowA, unit_first, V, rawA);
-    if (!U.last_row) issue_loads<T, ALIGNED>(rowB, unit_first, V, rawB);
+    RawSlice<T, ALIGNED, LANE> rawA, rawB;
+    issue_loads<T, ALIGNED, LANE>(rowA, unit_first, V, rawA);
+    if (!U.last_row) issue_loads<T, ALIGNED, LANE>(rowB, unit_first, V, rawB);
     // draft token X_{i+1} and its two logits: the first wave of the row's last workgroup (the one with the
     // fewest logits) publishes the row's ratio from them
     const int nwg = nu / kWaves;
@@ -694,9 +701,9 @@ void fused_verify_kernel(const FusedParams P)
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     __shared__ u64 wave_words[2][kWaves];
     __shared__ double row_values[3];
-    float xa[kLaneLogits], xb[kLaneLogits];
+    float xa[LANE], xb[LANE];
     float shiftA, shiftB;
-    unpack_slice<T, ALIGNED>(rowA, unit_first, V, rawA, xa);
+    unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
     {
         const u64 stA = first_sweep_row(xa, k, shiftA);
         if (lane == 0) { st_u64(P.pstat + trow * nu + U.c, stA); wave_words[0][wave] = stA; }
@@ -705,7 +712,7 @@ void fused_verify_kernel(const FusedParams P)
     // the two logits of the draft token, asked for only now so that the streams above did not queue behind them
     double ya = 0.0, yb = 0.0;
     if (leader) { ya = logit_as_double(rowA + tok); yb = logit_as_double(rowB + tok); }
-    unpack_slice<T, ALIGNED>(rowB, unit_first, V, rawB, xb);
+    unpack_slice<T, ALIGNED, LANE>(rowB, unit_first, V, rawB, xb);
     {
         const u64 stB = first_sweep_row(xb, k, shiftB);
         if (lane == 0) wave_words[1][wave] = stB;
@@ -803,7 +810,7 @@ void fused_verify_kernel(const FusedParams P)
     if constexpr (GREEDY) {
         const float cp = fast_exp2((float)log2cp), cq = fast_exp2((float)log2cq);
 #pragma unroll
-        for (int j = 0; j < kLaneLogits; ++j) {
+        for (int j = 0; j < LANE; ++j) {
             const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
             acc += fmaxf(d, 0.f);
             rej += fmaxf(-d, 0.f);
@@ -816,12 +823,12 @@ void fused_verify_kernel(const FusedParams P)
         if (log2rho <= 0.0) {
             const float rho = fast_exp2((float)log2rho);
 #pragma unroll
-            for (int j = 0; j < kLaneLogits; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xa[j], rho, -xb[j]), 0.f, 1.f);
+            for (int j = 0; j < LANE; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xa[j], rho, -xb[j]), 0.f, 1.f);
             acc *= fast_exp2((float)log2cq);
         } else {
             const float nrho = -fast_exp2((float)-log2rho);
 #pragma unroll
-            for (int j = 0; j < kLaneLogits; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xb[j], nrho, xa[j]), 0.f, 1.f);
+            for (int j = 0; j < LANE; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xb[j], nrho, xa[j]), 0.f, 1.f);
             acc *= fast_exp2((float)log2cp);
         }
     }
@@ -836,7 +843,7 @@ void fused_verify_kernel(const FusedParams P)
     // it in the workgroup order, the last target row (needed only if every token is accepted) right after
     if (U.i == gb - 1 && U.c == 0) {
         SV_STAMP(5);
-        finalize_sequence<T, ALIGNED, GREEDY>(P, U.b, gb);
+        finalize_sequence<T, ALIGNED, GREEDY, LANE>(P, U.b, gb);
         SV_STAMP(6);
     }
 #undef SV_STAMP

@@ -23,8 +23,9 @@ using namespace sv;
 
 constexpr int kDefaultSpinLimit = 1 << 20;
 
-std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused (testing hook)
+std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused; 3 / 4: fused with small / large units (testing hook)
 std::atomic<int> g_spin_limit{kDefaultSpinLimit};
+std::atomic<int> g_lane{0};                        // 0 auto, 32 or 64: logits per lane of the fused kernel's units (testing hook)
 std::atomic<long long *> g_prof{nullptr};          // device buffer for per-unit timestamps (tuning hook)
 
 struct Layout {
@@ -50,7 +51,7 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     const size_t rows_t = (size_t)B * (gamma + 1), rows_d = (size_t)B * gamma;
 
     // a workgroup is four waves, each with one wave chunk of a row
-    L.nu = (V + kChunk - 1) / kChunk * kWaves;
+    L.nu = (V + kWaves * kWave * kLaneSmall - 1) / (kWaves * kWave * kLaneSmall) * kWaves;
     L.fused_grid = rows_t * (size_t)(L.nu / kWaves);
     L.fused_ok = L.nu <= kMaxUnitsPerRow && L.fused_grid <= 0x7fffffffull;
     size_t off = kHdrWords * sizeof(int);
@@ -152,24 +153,36 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
 {
-    // the instantiation for this row width (1, 2, 4 or 8 words of a row per lane) and its resident workgroups
-    static int cap[2][2] = {{0, 0}, {0, 0}};
+    // Unit size: 64 logits per lane (3 waves per SIMD) for bf16 rows on the vector path when the rows are wide or
+    // the call is many resident sets long - fewer workgroups per row to wait for; 32 (5 waves per SIMD) otherwise.
+    // The workspace is laid out for the smaller units, whose words are a superset.
+    constexpr bool kLargeOk = ALIGNED && ElemTraits<T>::kVec == 8;
+    const bool large = kLargeOk && g_lane.load() != kLaneSmall &&
+                       (g_lane.load() == kLaneLarge || V > 131072 || (size_t)B * (gamma + 1) * (L.nu / kWaves) >= 16384);
+    const int lane_logits = large ? kLaneLarge : kLaneSmall;
+    const int nu = (V + kWaves * kWave * lane_logits - 1) / (kWaves * kWave * lane_logits) * kWaves;
+    // the instantiation for this row width (one or two words of a row per lane of the collecting wave) and its
+    // resident workgroups
+    static int cap[2][2][2] = {{{0, 0}, {0, 0}}, {{0, 0}, {0, 0}}};
     const bool greedy = algo == kGreedy;
-    const int nwg = L.nu / kWaves;                // a row's workgroup words: one or two per lane of the collecting wave
+    const int nwg = nu / kWaves;
     const int nw_log = nwg <= kWave ? 0 : 1;
     void (*kernel)(const FusedParams) = nullptr;
-#define SV_PICK(G) (nw_log == 0 ? fused_verify_kernel<T, ALIGNED, G, 1> : fused_verify_kernel<T, ALIGNED, G, 2>)
-    kernel = greedy ? SV_PICK(true) : SV_PICK(false);
+#define SV_PICK(G, LN) (nw_log == 0 ? fused_verify_kernel<T, ALIGNED, G, 1, LN> : fused_verify_kernel<T, ALIGNED, G, 2, LN>)
+    if constexpr (kLargeOk) {
+        if (large) kernel = greedy ? SV_PICK(true, kLaneLarge) : SV_PICK(false, kLaneLarge);
+    }
+    if (!kernel) kernel = greedy ? SV_PICK(true, kLaneSmall) : SV_PICK(false, kLaneSmall);
 #undef SV_PICK
-    const int capacity = resident_workgroups(kernel, cap[greedy ? 1 : 0][nw_log]);
-    const int wpr = L.nu / kWaves;
+    const int capacity = resident_workgroups(kernel, cap[greedy ? 1 : 0][nw_log][large ? 1 : 0]);
+    const int wpr = nwg;
     // a row's workgroups wait for each other and must fit on the device together, with room to spare
     if (capacity < 4 * wpr) return capacity < 1 ? SV_ERR_HIP : SV_ERR_UNSUPPORTED;
     FusedParams P;
     P.target = target; P.draft = draft; P.tokens = tokens; P.draft_lens = draft_lens; P.uniforms = uniforms;
     P.tstride = tstride; P.dstride = dstride;
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
-    P.nu = L.nu;
+    P.nu = nu;
     // groups of sequences so large that one position of a group fills the device at least once
     const int min_seqs = (capacity + wpr - 1) / wpr;
     const int groups = B / min_seqs > 1 ? B / min_seqs : 1;
@@ -288,7 +301,8 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
 
 void spec_verify_debug_config(int32_t path, int32_t spin_limit)
 {
-    g_path.store(path >= 0 && path <= 2 ? path : 0);
+    g_path.store(path >= 0 && path <= 2 ? path : path == 3 || path == 4 ? 2 : 0);
+    g_lane.store(path == 3 ? kLaneSmall : path == 4 ? kLaneLarge : 0);
     g_spin_limit.store(spin_limit >= 0 ? spin_limit : kDefaultSpinLimit);
 }
 
