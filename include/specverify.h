@@ -28,7 +28,8 @@
  * is enqueued on `stream` (a hipStream_t passed as void*; NULL is the default stream) and
  * the outputs are valid once the caller has synchronised that stream.  The library never
  * allocates, frees or synchronises, and keeps no reference to any argument after return.
- * Errors are reported by return code only.  Logits are finite or -inf (a token masked out by
+ * Errors are reported by return code only.  Logits are finite (|logit| * log2(e) / T within float
+ * range) or -inf (a token masked out by
  * top-k / top-p warping: probability exactly 0), never +inf or NaN; every row keeps at least one
  * finite logit and a drafted token has a finite DRAFT logit (its target logit may be -inf: its
  * ratio is then 0 and it is never accepted).  That, tokens in [0, V) and uniforms in [0, 1) are
