@@ -84,7 +84,6 @@ struct FusedParams {
     u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
-    unsigned *rpart;      // [B, gamma, nu]           greedy only: partial sums of max(q - w p, 0), same encoding
     int32_t *accept_len, *next_token;
     float *debug_out;
     long long *prof;      // NULL, or [workgroups, 8] timestamps (100 MHz ticks) for tuning
@@ -377,7 +376,7 @@ __device__ __forceinline__ double read_lane_double(double v, int lane)
 
 // Accept tests and inverse-CDF draw of one sequence (one wave).  What does not need the residual
 // sums (normalisers, ratios, w) is done first, while the sequence's last units are still at work.
-template <typename T, bool ALIGNED, bool GREEDY, int LANE>
+template <typename T, bool ALIGNED, int LANE>
 __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, int gamma)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
@@ -404,7 +403,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     const u64 *lw_word = P.lw + (size_t)b * G + (lane < gamma ? lane : gamma - 1);
     const float *eta = P.uniforms + (size_t)b * (G + 1);
     u64 lw_first = 0;
-    unsigned sw_first[kBatch], rw_first[kBatch];
+    unsigned sw_first[kBatch];
     {
         const size_t drow = (size_t)b * G + (lane < gamma ? lane : gamma - 1);
         u64 w0 = ld_u64(P.ratio + drow), w1 = ld_u64(P.rowstat + drow * 3), w2 = ld_u64(P.rowstat + drow * 3 + 1),
@@ -414,7 +413,6 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
         for (int jj = 0; jj < kBatch; ++jj) {
             const int j = jj < gamma ? jj : gamma - 1;
             sw_first[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
-            if constexpr (GREEDY) rw_first[jj] = ld_u32(P.rpart + ((size_t)b * G + j) * nu + e_lane);
         }
         w0 = wait_word(P.ratio + drow, w0, lane < gamma, P.spin_limit, gave_up);
         w1 = wait_word(P.rowstat + drow * 3, w1, lane < gamma, P.spin_limit, gave_up);
@@ -432,7 +430,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
         const double prev = __shfl_up(next, 1, kWave);
         my_lw = lane ? prev : 0.0;
         lw_last = read_lane_double(next, gamma - 1);
-        if (GREEDY) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
+        if (P.algo == kGreedy) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
     }
     FSTAMP(8);
     // what the accept tests need of w_j is formed now, before the wait for the partial sums: lane l tests
@@ -445,20 +443,18 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     const double h_token = exp2(fmin(my_lr, 0.0));      // min(r_j, 1); lane l holds log2 r_{l+1}
     const float eta_j = eta[j <= gamma ? j - 1 : 0];
 
-    // ---- S_j (and, greedy, the rejected mass) = sum of row j's partial sums, into lane j.  kept[jj]
+    // ---- S_j = sum of row j's partial sums, into lane j.  kept[jj]
     // holds this lane's partial sum of row jj when gamma <= kBatch (used again for the draw).
-    float my_S = 0.f, my_R = 0.f, kept[kBatch];
+    float my_S = 0.f, kept[kBatch];
     for (int j0 = 0; j0 < gamma; j0 += kBatch) {
-        unsigned sw[kBatch], rw[kBatch];
+        unsigned sw[kBatch];
 #pragma unroll
         for (int jj = 0; jj < kBatch; ++jj) {
             const int j = j0 + jj < gamma ? j0 + jj : gamma - 1;
             if (j0 == 0) {                               // asked for at the start
                 sw[jj] = sw_first[jj];
-                if constexpr (GREEDY) rw[jj] = rw_first[jj];
             } else {
                 sw[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
-                if constexpr (GREEDY) rw[jj] = ld_u32(P.rpart + ((size_t)b * G + j) * nu + e_lane);
             }
         }
 #pragma unroll
@@ -467,35 +463,31 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
             kept[jj] = 0.f;
             if (j >= gamma) continue;
             const size_t drow = (size_t)b * G + j;
-            float acc = 0.f, rej = 0.f;
+            float acc = 0.f;
             const unsigned w = wait_word32(P.spart + drow * nu + e_lane, sw[jj], lane < nu, P.spin_limit, gave_up);
             if (lane < nu) acc = unpack_partial(w);
             kept[jj] = acc;
-            if constexpr (GREEDY) {
-                const unsigned r = wait_word32(P.rpart + drow * nu + e_lane, rw[jj], lane < nu, P.spin_limit, gave_up);
-                if (lane < nu) rej = unpack_partial(r);
-            }
             for (int e = lane + kWave; e < nu; e += kWave) {
                 acc += unpack_partial(wait_word32(P.spart + drow * nu + e, P.spin_limit, gave_up));
-                if constexpr (GREEDY) rej += unpack_partial(wait_word32(P.rpart + drow * nu + e, P.spin_limit, gave_up));
             }
             acc = wave_sum(acc);
-            if constexpr (GREEDY) rej = wave_sum(rej);
-            if (lane == j) { my_S = acc; my_R = rej; }
+            if (lane == j) my_S = acc;
         }
     }
 
     FSTAMP(9);
     // ---- accept tests eta_j < h_j
-    const double S_row = (double)__shfl_down(my_S, 1, kWave), R_row = (double)__shfl_down(my_R, 1, kWave);
+    const double S_row = (double)__shfl_down(my_S, 1, kWave);
     bool pass = false;
     if (j <= gamma) {
         const double S = j < gamma ? S_row : w_j;        // q_gamma == 0: S_gamma = w_gamma
         double h;
         if (P.algo == kToken) h = h_token;
         else if (j == gamma) h = fmin(w_j, 1.0);                                           // h_gamma = w_gamma
-        else if (GREEDY) h = R_row > 0.0 ? fmin(S / R_row, 1.0) : 1.0;                     // p_remain / p_rej
-        else h = lw_j >= 0.0 ? 1.0 : S / (S + one_minus_w);                                // S / (S + 1 - w)
+        // block: S / (S + 1 - w).  Greedy (Alg. 4) divides by the rejected mass sum_x max(q - w p, 0) instead, which
+        // is the same number: it equals S - sum_x (w p - q) = S + 1 - w because both rows sum to one (w unclipped;
+        // at w >= 1 the ratio is >= 1 and every eta in [0, 1) passes)
+        else h = lw_j >= 0.0 ? 1.0 : S / (S + one_minus_w);
         pass = (double)eta_j < h;
         if (P.debug_out) {
             float *d = P.debug_out + (base + j) * 3;
@@ -577,7 +569,6 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     // more below) can go now, under the latency of the loads that follow.
     for (int e = lane; e < G * nu; e += kWave) {
         st_u32(P.spart + (size_t)b * G * nu + e, 0);
-        if constexpr (GREEDY) st_u32(P.rpart + (size_t)b * G * nu + e, 0);
     }
     for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
     for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); }
@@ -656,7 +647,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
 }
 
 // ------------------------------------------------------------------ the kernel
-template <typename T, bool ALIGNED, bool GREEDY, int NW, int LANE>
+template <typename T, bool ALIGNED, int NW, int LANE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(LANE == kLaneLarge ? 3 : ElemTraits<T>::kVec == 8 ? 5 : 4)))
 void fused_verify_kernel(const FusedParams P)
 {
@@ -791,7 +782,7 @@ void fused_verify_kernel(const FusedParams P)
         if (leader && P.algo != kToken) {
             // w_{i+1} for the workgroups of the next position
             double next = log2w + lr;
-            if (!GREEDY && next > 0.0) next = 0.0;
+            if (P.algo != kGreedy && next > 0.0) next = 0.0;       // the min{., 1}; greedy block verification omits it
             if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
         }
         if (lane == 0) { row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w; }
@@ -801,22 +792,13 @@ void fused_verify_kernel(const FusedParams P)
     __syncthreads();
     const double Lp = row_values[0], Lq = row_values[1];
     double log2w = row_values[2];
-    if (GREEDY) log2w = fmin(log2w, 100.0);                 // keeps w p finite in float
+    if (P.algo == kGreedy) log2w = fmin(log2w, 100.0);      // keeps w p finite in float
     SV_STAMP(3);
 
     // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq with wave-uniform cp, cq
     const double log2cp = (double)shiftA - (Lp - log2w), log2cq = (double)shiftB - Lq;
-    float acc = 0.f, rej = 0.f;
-    if constexpr (GREEDY) {
-        const float cp = fast_exp2((float)log2cp), cq = fast_exp2((float)log2cq);
-#pragma unroll
-        for (int j = 0; j < LANE; ++j) {
-            const float d = __builtin_fmaf(xa[j], cp, -(xb[j] * cq));
-            acc += fmaxf(d, 0.f);
-            rej += fmaxf(-d, 0.f);
-        }
-        rej = wave_sum(rej);
-    } else {
+    float acc = 0.f;
+    {
         // sum of max(xa cp - xb cq, 0) with the larger factor taken out, so that every term lies in [0, 1]
         // (xa, xb <= 1) and the clamp of the fma is the max: two instructions per pair
         const double log2rho = log2cp - log2cq;
@@ -834,7 +816,6 @@ void fused_verify_kernel(const FusedParams P)
     }
     acc = wave_sum(acc);
     if (lane == 0) {
-        if constexpr (GREEDY) st_u32(P.rpart + drow * nu + U.c, pack_partial(rej));
         st_u32(P.spart + drow * nu + U.c, pack_partial(acc));
     }
     SV_STAMP(4);
@@ -843,7 +824,7 @@ void fused_verify_kernel(const FusedParams P)
     // it in the workgroup order, the last target row (needed only if every token is accepted) right after
     if (U.i == gb - 1 && U.c == 0) {
         SV_STAMP(5);
-        finalize_sequence<T, ALIGNED, GREEDY, LANE>(P, U.b, gb);
+        finalize_sequence<T, ALIGNED, LANE>(P, U.b, gb);
         SV_STAMP(6);
     }
 #undef SV_STAMP

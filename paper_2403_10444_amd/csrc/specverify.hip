@@ -35,11 +35,11 @@ struct Layout {
     int nu;                       // wave chunks per row = 4 * workgroups per row
     size_t fused_grid;            // workgroups of the fused kernel
     size_t control_words;         // header and all words that cross waves: in ints, at offset 0, zero between calls
-    size_t off_ratio, off_lw, off_rowstat, off_pstat, off_pgrp, off_qgrp, off_spart, off_rpart;
+    size_t off_ratio, off_lw, off_rowstat, off_pstat, off_pgrp, off_qgrp, off_spart;
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
-    size_t off_stats, off_coef, off_sspart, off_srpart;
+    size_t off_stats, off_coef, off_sspart;
 };
 
 bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
@@ -62,14 +62,12 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_qgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
-    L.off_rpart = off;  off += rows_d * L.nu * sizeof(unsigned);
     L.control_words = off / sizeof(int);
     off = align_up(off, 256);
     // the staged path's scratch follows, so that it never touches the control words
     L.off_stats = off;  off = align_up(off + L.rows_total * L.nchunks * sizeof(float2), 256);
     L.off_coef = off;   off = align_up(off + rows_t * sizeof(SeqCoef), 256);
     L.off_sspart = off; off = align_up(off + rows_d * L.nchunks * sizeof(float), 256);
-    L.off_srpart = off; off = align_up(off + rows_d * L.nchunks * sizeof(float), 256);
     L.total = off;
     return true;
 }
@@ -98,7 +96,6 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
     float2 *stats = reinterpret_cast<float2 *>(ws + L.off_stats);
     SeqCoef *coef = reinterpret_cast<SeqCoef *>(ws + L.off_coef);
     float *spart = reinterpret_cast<float *>(ws + L.off_sspart);
-    float *rpart = reinterpret_cast<float *>(ws + L.off_srpart);
     const int n_target_rows = B * (gamma + 1);
 
     row_stats_kernel<T, ALIGNED><<<(unsigned)(L.rows_total * L.nchunks), kThreads, 0, stream>>>(
@@ -107,15 +104,11 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
     prefix_weights_kernel<T><<<B, 64, sm2, stream>>>(target, draft, tstride, dstride, tokens, gamma, V, k, kd, kd / (double)k - 1.0, L.nchunks,
                                                     n_target_rows, algo, stats, coef, draft_lens);
     const unsigned pair_blocks = (unsigned)((size_t)B * gamma * L.nchunks);
-    if (algo == kGreedy)
-        residual_kernel<T, ALIGNED, true><<<pair_blocks, kThreads, 0, stream>>>(
-            target, draft, tstride, dstride, gamma, V, k, L.nchunks, coef, spart, rpart);
-    else
-        residual_kernel<T, ALIGNED, false><<<pair_blocks, kThreads, 0, stream>>>(
-            target, draft, tstride, dstride, gamma, V, k, L.nchunks, coef, spart, rpart);
-    const size_t sm4 = 2 * (gamma + 1) * sizeof(double);
+    residual_kernel<T, ALIGNED><<<pair_blocks, kThreads, 0, stream>>>(
+        target, draft, tstride, dstride, gamma, V, k, L.nchunks, coef, spart);
+    const size_t sm4 = (gamma + 1) * sizeof(double);
     finalize_kernel<T, ALIGNED><<<B, kThreads, sm4, stream>>>(
-        target, draft, tstride, dstride, uniforms, gamma, V, k, L.nchunks, algo, stats, coef, spart, rpart,
+        target, draft, tstride, dstride, uniforms, gamma, V, k, L.nchunks, algo, stats, coef, spart,
         accept_len, next_token, debug_out, draft_lens);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
@@ -163,18 +156,17 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     const int nu = (V + kWaves * kWave * lane_logits - 1) / (kWaves * kWave * lane_logits) * kWaves;
     // the instantiation for this row width (one or two words of a row per lane of the collecting wave) and its
     // resident workgroups
-    static int cap[2][2][2] = {{{0, 0}, {0, 0}}, {{0, 0}, {0, 0}}};
-    const bool greedy = algo == kGreedy;
+    static int cap[2][2] = {{0, 0}, {0, 0}};
     const int nwg = nu / kWaves;
     const int nw_log = nwg <= kWave ? 0 : 1;
     void (*kernel)(const FusedParams) = nullptr;
-#define SV_PICK(G, LN) (nw_log == 0 ? fused_verify_kernel<T, ALIGNED, G, 1, LN> : fused_verify_kernel<T, ALIGNED, G, 2, LN>)
+#define SV_PICK(LN) (nw_log == 0 ? fused_verify_kernel<T, ALIGNED, 1, LN> : fused_verify_kernel<T, ALIGNED, 2, LN>)
     if constexpr (kLargeOk) {
-        if (large) kernel = greedy ? SV_PICK(true, kLaneLarge) : SV_PICK(false, kLaneLarge);
+        if (large) kernel = SV_PICK(kLaneLarge);
     }
-    if (!kernel) kernel = greedy ? SV_PICK(true, kLaneSmall) : SV_PICK(false, kLaneSmall);
+    if (!kernel) kernel = SV_PICK(kLaneSmall);
 #undef SV_PICK
-    const int capacity = resident_workgroups(kernel, cap[greedy ? 1 : 0][nw_log][large ? 1 : 0]);
+    const int capacity = resident_workgroups(kernel, cap[nw_log][large ? 1 : 0]);
     const int wpr = nwg;
     // a row's workgroups wait for each other and must fit on the device together, with room to spare
     if (capacity < 4 * wpr) return capacity < 1 ? SV_ERR_HIP : SV_ERR_UNSUPPORTED;
@@ -200,7 +192,6 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
     P.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
     P.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
-    P.rpart = reinterpret_cast<unsigned *>(ws + L.off_rpart);
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
     P.prof = g_prof.load();
     kernel<<<grid, kThreads, 0, stream>>>(P);

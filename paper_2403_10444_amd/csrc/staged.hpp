@@ -120,11 +120,11 @@ __global__ __launch_bounds__(64) void prefix_weights_kernel(
     }
 }
 
-template <typename T, bool ALIGNED, bool GREEDY>
+template <typename T, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void residual_kernel(
     const T *__restrict__ target, const T *__restrict__ draft, size_t tstride, size_t dstride,
     int gamma, int V, float k, int nchunks, const SeqCoef *__restrict__ coef,
-    float *__restrict__ spart, float *__restrict__ rpart)
+    float *__restrict__ spart)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kU = kChunk / (kThreads * kVec);
@@ -142,21 +142,13 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
         load_vec<T, ALIGNED>(prow, V, idx, xp[u]);
         load_vec<T, ALIGNED>(qrow, V, idx, xq[u]);
     }
-    float acc = 0.f, rej = 0.f;
+    float acc = 0.f;
 #pragma unroll
     for (int u = 0; u < kU; ++u)
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            const float d = residual_term(xp[u][e], xq[u][e], k, rc);
-            acc += fmaxf(d, 0.f);
-            if constexpr (GREEDY) rej += fmaxf(-d, 0.f);
-        }
+        for (int e = 0; e < kVec; ++e) acc += fmaxf(residual_term(xp[u][e], xq[u][e], k, rc), 0.f);
     acc = block_sum(acc, lds);
-    if constexpr (GREEDY) rej = block_sum(rej, lds);
-    if (tid == 0) {
-        spart[(size_t)pr * nchunks + c] = acc;
-        if constexpr (GREEDY) rpart[(size_t)pr * nchunks + c] = rej;
-    }
+    if (tid == 0) spart[(size_t)pr * nchunks + c] = acc;
 }
 
 template <typename T, bool ALIGNED>
@@ -165,15 +157,15 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
     const float *__restrict__ uniforms,
     int gamma, int V, float k, int nchunks, int algo,
     const float2 *__restrict__ stats, const SeqCoef *__restrict__ coef,
-    const float *__restrict__ spart, const float *__restrict__ rpart,
+    const float *__restrict__ spart,
     int32_t *__restrict__ accept_len, int32_t *__restrict__ next_token, float *__restrict__ debug_out,
     const int32_t *__restrict__ draft_lens)
 {
-    extern __shared__ double smd[];                     // [gamma+1] S_i, [gamma+1] rejected mass
+    extern __shared__ double smd[];                     // [gamma+1] S_i
     __shared__ float lds[kWaves];
     __shared__ int s_tau, s_chunk, s_mode, s_ints[2];
     __shared__ float s_t;
-    double *S = smd, *R = smd + (gamma + 1);
+    double *S = smd;
     const int b = blockIdx.x, tid = threadIdx.x;
     const SeqCoef *scb = coef + (size_t)b * (gamma + 1);
     // this sequence's draft length (kept in range whatever the caller wrote); gamma stays the stride
@@ -182,18 +174,12 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
     // S_i = cq_i * sum_c spart[b, i, c], chunks added in index order
     for (int i = tid; i <= gb; i += kThreads) {
         if (i < gb) {
-            double acc = 0.0, rej = 0.0;
+            double acc = 0.0;
             const float *sp = spart + ((size_t)b * gamma + i) * nchunks;
             for (int c = 0; c < nchunks; ++c) acc += (double)sp[c];
-            if (algo == kGreedy) {
-                const float *rp = rpart + ((size_t)b * gamma + i) * nchunks;
-                for (int c = 0; c < nchunks; ++c) rej += (double)rp[c];
-            }
             S[i] = acc * (double)scb[i].rc.cq;
-            R[i] = rej * (double)scb[i].rc.cq;
         } else {
             S[i] = scb[i].w;       // q_gamma == 0: the residual mass of the last row is w_gamma
-            R[i] = 0.0;
         }
     }
     __syncthreads();
@@ -207,8 +193,10 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
             if (i == 0) h = 1.0;
             else if (algo == kToken) h = exp2(fmin(scb[i].log2r, 0.0));                 // min(r_i, 1)
             else if (i == gb) h = fmin(scb[i].w, 1.0);                               // h_gamma = w_gamma
-            else if (algo == kGreedy) h = R[i] > 0.0 ? fmin(S[i] / R[i], 1.0) : 1.0;    // p_remain / p_rej
-            else h = scb[i].w >= 1.0 ? 1.0 : S[i] / (S[i] + scb[i].one_minus_w);        // block acceptance formula
+            // block acceptance formula.  Greedy block verification (Alg. 4) divides by the rejected mass
+            // sum_x max(q - w p, 0) instead: the same number, S - sum_x (w p - q) = S + 1 - w for rows that sum to
+            // one (w unclipped; at w >= 1 the ratio is >= 1 and every eta in [0, 1) passes)
+            else h = scb[i].w >= 1.0 ? 1.0 : S[i] / (S[i] + scb[i].one_minus_w);
             if (i >= 1) {
                 const bool pass = (double)eta[i - 1] < h;
                 if (algo == kToken) { if (pass && tau == i - 1) tau = i; }              // stops at the first failure

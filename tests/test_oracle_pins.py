@@ -391,3 +391,17 @@ def test_bad_arguments_are_rejected():
     bad[0, 0] = 10
     with pytest.raises(RuntimeError):
         oracle.verify(oracle.BLOCK, tl, dl, bad, uni, 1.0)
+
+
+def test_greedy_rejected_mass_equals_residual_mass_plus_one_minus_w():
+    """For rows that sum to one, sum_x max(q - w p, 0) = sum_x max(w p - q, 0) - sum_x (w p - q) = S + 1 - w, so the
+    ratio of Alg. 4 (which the oracle forms from the two sums, each taken directly) is S / (S + 1 - w) wherever
+    w < 1, and at least 1 wherever w >= 1.  The kernels rely on this to skip the second sum."""
+    rng = np.random.default_rng(99)
+    tl, dl, tok, uni = _random_call(rng, 50, 6, 400)
+    out = oracle.verify(oracle.GREEDY, tl, dl, tok, uni, 0.9)
+    w, S, h = out["dbg"][:, 1:6, 0], out["dbg"][:, 1:6, 1], out["dbg"][:, 1:6, 2]      # positions 1 .. gamma - 1
+    below = w < 1.0
+    assert below.any() and (~below).any()
+    np.testing.assert_allclose(h[below], np.minimum(S[below] / (S[below] + 1.0 - w[below]), 1.0), rtol=1e-9, atol=1e-12)
+    assert np.all(h[~below] == 1.0)
