@@ -214,6 +214,18 @@ __device__ __forceinline__ float row_max_shift(const u64 *words, int n, int limi
     return wave_max(m);
 }
 
+// Whether position i's residual mass S_i can matter.  The acceptance probability of block (and greedy block)
+// verification never exceeds w_i: h_i = S_i / (S_i + 1 - w_i) with S_i <= w_i.  So a test with eta_i >= w_i fails
+// whatever S_i is, the position cannot become tau either (tau is a position whose test passed, or 0), and neither
+// its second sweep nor its partial sums are needed.  Decided on log2 w_i as published and the uniform as stored,
+// with a margin far above the rounding of h_i; the units of a row and the wave that finishes the sequence evaluate
+// this same function on the same values, so they always agree on which partial sums exist.
+__device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i)
+{
+    if (i == 0 || P.debug_out || P.algo == kToken) return true;     // tau = 0 draws from row 0; the debug block reports every S_i
+    return (double)__builtin_amdgcn_logf(eta_i) < log2w_i + 1.0e-3;
+}
+
 struct Unit {
     int b, i, c;          // sequence, position (gamma: the last target row, which has no draft row), wave chunk
     bool last_row;
@@ -424,11 +436,12 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     FSTAMP(7);
     // log2 w_j for lane j as the rows' first units published it (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4
     // drops the min); lw_last is log2 w_gamma
-    double my_lw = 0.0, lw_last = 0.0;
+    double my_lw = 0.0, my_lw_raw = 0.0, lw_last = 0.0;
     if (P.algo != kToken) {
         const double next = unpack_ratio(wait_word(lw_word, lw_first, lane < gamma, P.spin_limit, gave_up));   // log2 w_{lane+1}
         const double prev = __shfl_up(next, 1, kWave);
         my_lw = lane ? prev : 0.0;
+        my_lw_raw = my_lw;
         lw_last = read_lane_double(next, gamma - 1);
         if (P.algo == kGreedy) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
     }
@@ -442,6 +455,10 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     const double one_minus_w = -expm1(lw_j * 0.69314718055994530942);
     const double h_token = exp2(fmin(my_lr, 0.0));      // min(r_j, 1); lane l holds log2 r_{l+1}
     const float eta_j = eta[j <= gamma ? j - 1 : 0];
+    // the positions whose residual mass exists (see residual_needed): bit l stands for position l + 1; position 0
+    // always has it.  The rule is evaluated on log2 w as published (before the cap that greedy applies above)
+    const double lw_rule = P.algo == kToken ? 0.0 : __shfl_down(my_lw_raw, 1, kWave);
+    const u64 have = __ballot(j < gamma && residual_needed(P, j, j < gamma ? lw_rule : 0.0, eta_j));
 
     // ---- S_j = sum of row j's partial sums, into lane j.  kept[jj]
     // holds this lane's partial sum of row jj when gamma <= kBatch (used again for the draw).
@@ -462,6 +479,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
             const int j = j0 + jj;
             kept[jj] = 0.f;
             if (j >= gamma) continue;
+            if (j > 0 && !((have >> (j - 1)) & 1)) continue;      // no partial sums were formed for this row: S stays 0
             const size_t drow = (size_t)b * G + j;
             float acc = 0.f;
             const unsigned w = wait_word32(P.spart + drow * nu + e_lane, sw[jj], lane < nu, P.spin_limit, gave_up);
@@ -488,7 +506,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
         // is the same number: it equals S - sum_x (w p - q) = S + 1 - w because both rows sum to one (w unclipped;
         // at w >= 1 the ratio is >= 1 and every eta in [0, 1) passes)
         else h = lw_j >= 0.0 ? 1.0 : S / (S + one_minus_w);
-        pass = (double)eta_j < h;
+        pass = (double)eta_j < h && (j == gamma || ((have >> (j - 1)) & 1));
         if (P.debug_out) {
             float *d = P.debug_out + (base + j) * 3;
             d[0] = (float)w_j; d[1] = (float)S; d[2] = (float)h;
@@ -688,10 +706,18 @@ void fused_verify_kernel(const FusedParams P)
     const bool leader = wave == 0 && wg_x == nwg - 1;
     int tok = 0;
     if (!U.last_row && leader) tok = P.tokens[drow];
+    // log2 w_i (published by the previous position's leader, usually long ago) and the uniform of position i's
+    // test: what decides whether this row's residual mass can matter at all
+    const bool need_w = P.algo != kToken && U.i > 0 && !U.last_row;
+    const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 && !U.last_row ? U.i - 1 : 0);
+    u64 wt = 1;
+    float eta_i = 0.f;
+    if (wave == 0 && need_w) { wt = ld_u64(lw_word); eta_i = P.uniforms[(size_t)U.b * (gamma + 1) + U.i - 1]; }
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     __shared__ u64 wave_words[2][kWaves];
     __shared__ double row_values[3];
+    __shared__ int row_needed;
     float xa[LANE], xb[LANE];
     float shiftA, shiftB;
     unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
@@ -715,9 +741,9 @@ void fused_verify_kernel(const FusedParams P)
     // those; the other three waves sleep at the barrier meanwhile.  The row's leader also publishes the
     // row's ratio, normalisers and w_{i+1}.  log2 w_i comes from the leader of the previous position
     // (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
+    bool gave_up = false;
     if (wave == 0) {
         SV_STAMP(1);
-        bool gave_up = false;
         StatAcc ga, gb;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) { ga.add(wave_words[0][w]); gb.add(wave_words[1][w]); }
@@ -725,9 +751,22 @@ void fused_verify_kernel(const FusedParams P)
             st_u64(P.pgrp + drow * nwg + wg_x, pack_stat(ga.m, ga.z));
             st_u64(P.qgrp + drow * nwg + wg_x, pack_stat(gb.m, gb.z));
         }
-        const bool need_w = P.algo != kToken && U.i > 0;
-        const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 ? U.i - 1 : 0);
-        u64 wt = 1;
+        // can this row's residual mass matter?  Needs log2 w_i; a row that is not needed costs its workgroups no wait
+        bool needed = true;
+        if (need_w && !P.debug_out) {
+            wt = wait_word(lw_word, wt, true, P.spin_limit, gave_up);
+            needed = residual_needed(P, U.i, unpack_ratio(wt), eta_i);
+        }
+        if (lane == 0) row_needed = needed ? 1 : 0;
+    }
+    __syncthreads();
+    const bool needed = row_needed != 0;
+    const bool finisher = U.i == gb - 1 && U.c == 0;
+    // a row whose residual mass cannot matter: only its leader (the next position needs this row's ratio) and the
+    // wave that finishes the sequence stay; everybody else is done and frees its registers
+    if (!needed && !leader && !finisher) return;
+
+    if (wave == 0 && (needed || leader)) {
         float Mp, Mq;
         double Lp, Lq;
         if (nwg <= kWave / 2) {
@@ -786,9 +825,10 @@ void fused_verify_kernel(const FusedParams P)
             if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
         }
         if (lane == 0) { row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w; }
-        if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
         SV_STAMP(2);
     }
+    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
+    if (needed) {
     __syncthreads();
     const double Lp = row_values[0], Lq = row_values[1];
     double log2w = row_values[2];
@@ -820,9 +860,10 @@ void fused_verify_kernel(const FusedParams P)
     }
     SV_STAMP(4);
 
+    }
     // the first unit of a sequence's last row pair finishes the sequence: the earlier positions come before
     // it in the workgroup order, the last target row (needed only if every token is accepted) right after
-    if (U.i == gb - 1 && U.c == 0) {
+    if (finisher) {
         SV_STAMP(5);
         finalize_sequence<T, ALIGNED, LANE>(P, U.b, gb);
         SV_STAMP(6);

@@ -31,7 +31,12 @@ def run_gpu(algo, inputs, temperature, workspace=None):
     dbg = torch.full((B, g1, 3), float("nan"), dtype=torch.float32, device=inputs["target_logits"].device)
     tau, y = ALGOS[algo][1](inputs["target_logits"], inputs["draft_logits"], inputs["draft_tokens"],
                             inputs["uniforms"], temperature, debug_out=dbg, workspace=workspace)
+    # without the debug block the kernels leave out the residual masses that cannot matter (positions whose test
+    # fails whatever S_i is): the decisions must be the same, bit for bit
+    tau2, y2 = ALGOS[algo][1](inputs["target_logits"], inputs["draft_logits"], inputs["draft_tokens"],
+                              inputs["uniforms"], temperature, workspace=workspace)
     torch.cuda.synchronize()
+    assert torch.equal(tau, tau2) and torch.equal(y, y2), "results differ with and without the debug block"
     return {"accept_len": tau.cpu().numpy(), "next_token": y.cpu().numpy(), "dbg": dbg.cpu().numpy()}
 
 
