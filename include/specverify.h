@@ -86,7 +86,9 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
  * workgroups resident; other shapes are then refused), 3 / 4 = the fused kernel with its
  * small / large units (32 / 64 logits of a row per lane; large ones exist for bf16 rows on
  * the 16-byte path only, other calls use the small ones; the library's own choice depends on
- * the shape); `spin_limit` bounds every wait inside the fused kernel in polls (negative:
+ * the shape; both also switch on, whatever the size of the call, the leaving-out of residual
+ * masses that cannot matter, which the library otherwise uses for calls larger than one
+ * resident set of workgroups); `spin_limit` bounds every wait inside the fused kernel in polls (negative:
  * default).                                                                               */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);
 

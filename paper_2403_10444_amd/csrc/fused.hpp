@@ -75,6 +75,8 @@ struct FusedParams {
     int algo;
     int nu;               // units (wave chunks) per row = 4 * workgroups per row
     int group_seqs;       // sequences per group of the row order
+    int prune;            // leave out residual masses that cannot matter (residual_needed); off for calls so small that
+                          // all positions run at once, where asking for log2 w first only lengthens the chain
     int spin_limit;
     int magic;            // workspace_magic(B, gamma, V)
     int *header;
@@ -222,7 +224,7 @@ __device__ __forceinline__ float row_max_shift(const u64 *words, int n, int limi
 // this same function on the same values, so they always agree on which partial sums exist.
 __device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i)
 {
-    if (i == 0 || P.debug_out || P.algo == kToken) return true;     // tau = 0 draws from row 0; the debug block reports every S_i
+    if (i == 0 || !P.prune || P.debug_out || P.algo == kToken) return true;   // tau = 0 draws from row 0; the debug block reports every S_i
     return (double)__builtin_amdgcn_logf(eta_i) < log2w_i + 1.0e-3;
 }
 
@@ -753,7 +755,7 @@ void fused_verify_kernel(const FusedParams P)
         }
         // can this row's residual mass matter?  Needs log2 w_i; a row that is not needed costs its workgroups no wait
         bool needed = true;
-        if (need_w && !P.debug_out) {
+        if (need_w && P.prune && !P.debug_out) {
             wt = wait_word(lw_word, wt, true, P.spin_limit, gave_up);
             needed = residual_needed(P, U.i, unpack_ratio(wt), eta_i);
         }

@@ -146,12 +146,12 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
 {
-    // Unit size: 64 logits per lane (3 waves per SIMD) for bf16 rows on the vector path when the rows are wide or
-    // the call is many resident sets long - fewer workgroups per row to wait for; 32 (5 waves per SIMD) otherwise.
+    // Unit size: 64 logits per lane (3 waves per SIMD) for bf16 rows on the vector path when the rows are very wide -
+    // half as many workgroups per row to wait for; 32 (5 waves per SIMD) otherwise.
     // The workspace is laid out for the smaller units, whose words are a superset.
     constexpr bool kLargeOk = ALIGNED && ElemTraits<T>::kVec == 8;
     const bool large = kLargeOk && g_lane.load() != kLaneSmall &&
-                       (g_lane.load() == kLaneLarge || V > 131072 || (size_t)B * (gamma + 1) * (L.nu / kWaves) >= 16384);
+                       (g_lane.load() == kLaneLarge || V > 200000);
     const int lane_logits = large ? kLaneLarge : kLaneSmall;
     const int nu = (V + kWaves * kWave * lane_logits - 1) / (kWaves * kWave * lane_logits) * kWaves;
     // the instantiation for this row width (one or two words of a row per lane of the collecting wave) and its
@@ -182,6 +182,8 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     const int n_groups = (B + P.group_seqs - 1) / P.group_seqs;
     if ((size_t)n_groups * (gamma + 1) > 65535u || P.group_seqs > 65535) return SV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)wpr, (unsigned)P.group_seqs, (unsigned)(n_groups * (gamma + 1)));
+    // (the testing hook's forced unit sizes also force the pruning, so that small test shapes exercise it)
+    P.prune = g_lane.load() != 0 || (size_t)wpr * P.group_seqs * n_groups * (gamma + 1) > (size_t)capacity ? 1 : 0;
     P.spin_limit = g_spin_limit.load();
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);

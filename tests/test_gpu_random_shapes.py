@@ -70,7 +70,16 @@ def _check(case, it, probs):
             else:
                 tau, y = sv.spec_verify_ex(algo, tb[..., :V], db[..., :V], inp["draft_tokens"], inp["uniforms"], T,
                                            draft_lens=dl, debug_out=dbg, workspace=ws)
+        # the same without the debug block: residual masses that cannot matter are then left out, and the
+        # decisions must not change
+        if probs:
+            tau2, y2 = sv.spec_verify_probs(algo, tb[..., :V], db[..., :V], inp["draft_tokens"], inp["uniforms"],
+                                            draft_lens=dl, workspace=ws)
+        else:
+            tau2, y2 = sv.spec_verify_ex(algo, tb[..., :V], db[..., :V], inp["draft_tokens"], inp["uniforms"], T,
+                                         draft_lens=dl, workspace=ws)
         torch.cuda.synchronize()
+        assert torch.equal(tau, tau2) and torch.equal(y, y2), case
     finally:
         sv.spec_verify_debug_config(0, -1)
     assert sv.spec_verify_workspace_check(ws, B, gamma, V) == 0
