@@ -224,7 +224,11 @@ __device__ __forceinline__ float row_max_shift(const u64 *words, int n, int limi
 // this same function on the same values, so they always agree on which partial sums exist.
 __device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i)
 {
-    if (i == 0 || !P.prune || P.debug_out || P.algo == kToken) return true;   // tau = 0 draws from row 0; the debug block reports every S_i
+    if (i == 0 || !P.prune || P.debug_out) return true;   // tau = 0 draws from row 0; the debug block reports every S_i
+    // token verification (Alg. 1) stops at the first failure: the word that carries log2 w_i for the other two
+    // algorithms carries 0 while every test up to position i has passed and kLog2RatioFloor afterwards; only a
+    // position that all earlier tests let through can become tau
+    if (P.algo == kToken) return log2w_i > 0.5 * kLog2RatioFloor;
     return (double)__builtin_amdgcn_logf(eta_i) < log2w_i + 1.0e-3;
 }
 
@@ -422,7 +426,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
         const size_t drow = (size_t)b * G + (lane < gamma ? lane : gamma - 1);
         u64 w0 = ld_u64(P.ratio + drow), w1 = ld_u64(P.rowstat + drow * 3), w2 = ld_u64(P.rowstat + drow * 3 + 1),
             w3 = ld_u64(P.rowstat + drow * 3 + 2);
-        if (P.algo != kToken) lw_first = ld_u64(lw_word);
+        lw_first = ld_u64(lw_word);
 #pragma unroll
         for (int jj = 0; jj < kBatch; ++jj) {
             const int j = jj < gamma ? jj : gamma - 1;
@@ -439,13 +443,15 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     // log2 w_j for lane j as the rows' first units published it (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4
     // drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, my_lw_raw = 0.0, lw_last = 0.0;
-    if (P.algo != kToken) {
+    {
         const double next = unpack_ratio(wait_word(lw_word, lw_first, lane < gamma, P.spin_limit, gave_up));   // log2 w_{lane+1}
         const double prev = __shfl_up(next, 1, kWave);
-        my_lw = lane ? prev : 0.0;
-        my_lw_raw = my_lw;
-        lw_last = read_lane_double(next, gamma - 1);
-        if (P.algo == kGreedy) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
+        my_lw_raw = lane ? prev : 0.0;
+        if (P.algo != kToken) {                              // token verification: the words only say where the tests stopped
+            my_lw = my_lw_raw;
+            lw_last = read_lane_double(next, gamma - 1);
+            if (P.algo == kGreedy) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
+        }
     }
     FSTAMP(8);
     // what the accept tests need of w_j is formed now, before the wait for the partial sums: lane l tests
@@ -459,7 +465,7 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     const float eta_j = eta[j <= gamma ? j - 1 : 0];
     // the positions whose residual mass exists (see residual_needed): bit l stands for position l + 1; position 0
     // always has it.  The rule is evaluated on log2 w as published (before the cap that greedy applies above)
-    const double lw_rule = P.algo == kToken ? 0.0 : __shfl_down(my_lw_raw, 1, kWave);
+    const double lw_rule = __shfl_down(my_lw_raw, 1, kWave);
     const u64 have = __ballot(j < gamma && residual_needed(P, j, j < gamma ? lw_rule : 0.0, eta_j));
 
     // ---- S_j = sum of row j's partial sums, into lane j.  kept[jj]
@@ -710,11 +716,13 @@ void fused_verify_kernel(const FusedParams P)
     if (!U.last_row && leader) tok = P.tokens[drow];
     // log2 w_i (published by the previous position's leader, usually long ago) and the uniform of position i's
     // test: what decides whether this row's residual mass can matter at all
-    const bool need_w = P.algo != kToken && U.i > 0 && !U.last_row;
+    const bool need_w = U.i > 0 && !U.last_row;
     const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 && !U.last_row ? U.i - 1 : 0);
     u64 wt = 1;
     float eta_i = 0.f;
     if (wave == 0 && need_w) { wt = ld_u64(lw_word); eta_i = P.uniforms[(size_t)U.b * (gamma + 1) + U.i - 1]; }
+    float eta_next = 0.f;                                    // the uniform of test i + 1, which the leader judges for Alg. 1
+    if (leader && !U.last_row && P.algo == kToken) eta_next = P.uniforms[(size_t)U.b * (gamma + 1) + U.i];
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     __shared__ u64 wave_words[2][kWaves];
@@ -820,12 +828,19 @@ void fused_verify_kernel(const FusedParams P)
         }
         double log2w = 0.0;
         if (need_w) log2w = unpack_ratio(wait_word(lw_word, wt, true, P.spin_limit, gave_up));
-        if (leader && P.algo != kToken) {
+        if (leader) {
             // w_{i+1} for the workgroups of the next position
             double next = log2w + lr;
-            if (P.algo != kGreedy && next > 0.0) next = 0.0;       // the min{., 1}; greedy block verification omits it
+            if (P.algo == kBlock && next > 0.0) next = 0.0;        // the min{., 1}; greedy block verification omits it
+            if (P.algo == kToken) {
+                // token verification: 0 while every test so far has passed (test i+1: eta_{i+1} < min(r_{i+1}, 1), the
+                // expression the finishing wave evaluates too), kLog2RatioFloor from the first failure on
+                const bool pass = log2w > 0.5 * kLog2RatioFloor && (double)eta_next < exp2(fmin(unpack_ratio(pack_ratio(lr)), 0.0));
+                next = pass ? 0.0 : kLog2RatioFloor;
+            }
             if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
         }
+        if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
         if (lane == 0) { row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w; }
         SV_STAMP(2);
     }
