@@ -395,8 +395,10 @@ __device__ __forceinline__ double read_lane_double(double v, int lane)
 // Accept tests and inverse-CDF draw of one sequence (one wave).  What does not need the residual
 // sums (normalisers, ratios, w) is done first, while the sequence's last units are still at work.
 template <typename T, bool ALIGNED, int LANE>
-__device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, int gamma)
+__device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, int gamma, const double *own)
 {
+    // `own` (LDS, written by this same wave): log2 r, L_p, L_q, M_p and the word for the next position of the
+    // sequence's last row pair, whose leader this wave is - they need no trip through device memory
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = LANE / kVec;
     constexpr int kUnitLogits = kWave * LANE;
@@ -432,19 +434,21 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
             const int j = jj < gamma ? jj : gamma - 1;
             sw_first[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
         }
-        w0 = wait_word(P.ratio + drow, w0, lane < gamma, P.spin_limit, gave_up);
-        w1 = wait_word(P.rowstat + drow * 3, w1, lane < gamma, P.spin_limit, gave_up);
-        w2 = wait_word(P.rowstat + drow * 3 + 1, w2, lane < gamma, P.spin_limit, gave_up);
-        w3 = wait_word(P.rowstat + drow * 3 + 2, w3, lane < gamma, P.spin_limit, gave_up);
+        w0 = wait_word(P.ratio + drow, w0, lane < gamma - 1, P.spin_limit, gave_up);
+        w1 = wait_word(P.rowstat + drow * 3, w1, lane < gamma - 1, P.spin_limit, gave_up);
+        w2 = wait_word(P.rowstat + drow * 3 + 1, w2, lane < gamma - 1, P.spin_limit, gave_up);
+        w3 = wait_word(P.rowstat + drow * 3 + 2, w3, lane < gamma - 1, P.spin_limit, gave_up);
         my_lr = unpack_ratio(w0); my_Lp = unpack_ratio(w1); my_Lq = unpack_ratio(w2);
         my_Mp = __uint_as_float((unsigned)(w3 >> 32));
+        if (lane == gamma - 1) { my_lr = own[0]; my_Lp = own[1]; my_Lq = own[2]; my_Mp = (float)own[3]; }
     }
     FSTAMP(7);
     // log2 w_j for lane j as the rows' first units published it (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4
     // drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, my_lw_raw = 0.0, lw_last = 0.0;
     {
-        const double next = unpack_ratio(wait_word(lw_word, lw_first, lane < gamma, P.spin_limit, gave_up));   // log2 w_{lane+1}
+        double next = unpack_ratio(wait_word(lw_word, lw_first, lane < gamma - 1, P.spin_limit, gave_up));   // log2 w_{lane+1}
+        if (lane == gamma - 1) next = own[4];
         const double prev = __shfl_up(next, 1, kWave);
         my_lw_raw = lane ? prev : 0.0;
         if (P.algo != kToken) {                              // token verification: the words only say where the tests stopped
@@ -728,6 +732,7 @@ void fused_verify_kernel(const FusedParams P)
     __shared__ u64 wave_words[2][kWaves];
     __shared__ double row_values[3];
     __shared__ int row_needed;
+    __shared__ double own_values[5];                         // the leader's results for its own use when it finishes the sequence
     float xa[LANE], xb[LANE];
     float shiftA, shiftB;
     unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
@@ -771,10 +776,11 @@ void fused_verify_kernel(const FusedParams P)
     }
     __syncthreads();
     const bool needed = row_needed != 0;
-    const bool finisher = U.i == gb - 1 && U.c == 0;
-    // a row whose residual mass cannot matter: only its leader (the next position needs this row's ratio) and the
-    // wave that finishes the sequence stay; everybody else is done and frees its registers
-    if (!needed && !leader && !finisher) return;
+    // the leader of a sequence's last row pair finishes the sequence: what it works out for its row it has at hand
+    const bool finisher = leader && U.i == gb - 1;
+    // a row whose residual mass cannot matter: only its leader (the next position needs this row's ratio; the
+    // last one finishes the sequence) stays; everybody else is done and frees its registers
+    if (!needed && !leader) return;
 
     if (wave == 0 && (needed || leader)) {
         float Mp, Mq;
@@ -820,10 +826,15 @@ void fused_verify_kernel(const FusedParams P)
             const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
             lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
             if (lane == 0) {
-                st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
-                st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
-                st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
-                st_u64(P.ratio + drow, pack_ratio(lr));
+                if (finisher) {                     // nobody else reads the last row pair's words
+                    own_values[0] = unpack_ratio(pack_ratio(lr)); own_values[1] = unpack_ratio(pack_ratio(Lp));
+                    own_values[2] = unpack_ratio(pack_ratio(Lq)); own_values[3] = (double)Mp;
+                } else {
+                    st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
+                    st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
+                    st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
+                    st_u64(P.ratio + drow, pack_ratio(lr));
+                }
             }
         }
         double log2w = 0.0;
@@ -838,7 +849,10 @@ void fused_verify_kernel(const FusedParams P)
                 const bool pass = log2w > 0.5 * kLog2RatioFloor && (double)eta_next < exp2(fmin(unpack_ratio(pack_ratio(lr)), 0.0));
                 next = pass ? 0.0 : kLog2RatioFloor;
             }
-            if (lane == 0) st_u64(P.lw + drow, pack_ratio(next));
+            if (lane == 0) {
+                if (finisher) own_values[4] = unpack_ratio(pack_ratio(next));
+                else st_u64(P.lw + drow, pack_ratio(next));
+            }
         }
         if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
         if (lane == 0) { row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w; }
@@ -878,11 +892,12 @@ void fused_verify_kernel(const FusedParams P)
     SV_STAMP(4);
 
     }
-    // the first unit of a sequence's last row pair finishes the sequence: the earlier positions come before
+    // the leader of a sequence's last row pair finishes the sequence: the earlier positions come before
     // it in the workgroup order, the last target row (needed only if every token is accepted) right after
     if (finisher) {
         SV_STAMP(5);
-        finalize_sequence<T, ALIGNED, LANE>(P, U.b, gb);
+        __builtin_amdgcn_wave_barrier();                     // own_values: written by lane 0 above, read by another lane below
+        finalize_sequence<T, ALIGNED, LANE>(P, U.b, gb, own_values);
         SV_STAMP(6);
     }
 #undef SV_STAMP
