@@ -594,17 +594,8 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     }
     if (slot < 0) { slot = 0; t_in = INFINITY; }
 
-    // ---- the sequence's words are left zero for the next call.  Every reader of the row-pair words has published
-    // its partial sum by now and this wave has read all of those, so all but the target rows' words (needed once
-    // more below) can go now, under the latency of the loads that follow.
-    for (int e = lane; e < G * nu; e += kWave) {
-        st_u32(P.spart + (size_t)b * G * nu + e, 0);
-    }
-    for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
-    for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); }
-    for (int e = lane; e < 3 * G; e += kWave) st_u64(P.rowstat + (size_t)b * G * 3 + e, 0);
-
     FSTAMP(11);
+    u64 last_first_word = 0;
     // ---- ... then the token inside that chunk: weights recomputed from the logits, walked in
     // vocabulary order (vector, lane, element)
     {
@@ -618,6 +609,17 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
             load_vec<T, ALIGNED>(prow, V, first + v * kWave * kVec, xp[v]);
             if (mode == 0) load_vec<T, ALIGNED>(qrow, V, first + v * kWave * kVec, xq[v]);
         }
+        // the last target row's words, wanted at the very end, are asked for now as well
+        last_first_word = ld_u64(P.pstat + (base + gamma) * nu + e_lane);
+        // ---- the sequence's words are left zero for the next call.  Every reader of the row-pair words has published
+        // its partial sum by now and this wave has read all of those, so all but the target rows' words (needed once
+        // more below) can go now; the stores come after the loads, whose data would otherwise queue behind them.
+        for (int e = lane; e < G * nu; e += kWave) {
+            st_u32(P.spart + (size_t)b * G * nu + e, 0);
+        }
+        for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
+        for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); }
+        for (int e = lane; e < 3 * G; e += kWave) st_u64(P.rowstat + (size_t)b * G * 3 + e, 0);
         const float shift = stat_shift(sv), scale = fast_exp2(shift - Mrow);
         float t = mode == 0 ? (float)(t_in / (double)rc.cq) : (float)t_in;
         int y = -1, last_positive = -1;
@@ -671,7 +673,8 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
 
     FSTAMP(12);
     // ---- the target rows' words: those of the last target row must all be written first
-    for (int e = lane; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
+    wait_word(P.pstat + (base + gamma) * nu + e_lane, last_first_word, lane < nu, P.spin_limit, gave_up);
+    for (int e = lane + kWave; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
     for (int e = lane; e < (G + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
 }
