@@ -81,7 +81,7 @@ struct FusedParams {
     int magic;            // workspace_magic(B, gamma, V)
     int *header;
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
-    u64 *rowstat;         // [B, gamma, 3]            L_p, L_q (double bits, lowest bit set), M_p (float bits << 32 | 1)
+    unsigned *ycand;      // [B, gamma]               token drawn from the row pair's residual by its leader, + 2
     u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy), same encoding; not for token verification
     u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
@@ -392,58 +392,179 @@ __device__ __forceinline__ double read_lane_double(double v, int lane)
     return __longlong_as_double((long long)read_lane_u64((u64)__double_as_longlong(v), lane));
 }
 
-// Accept tests and inverse-CDF draw of one sequence (one wave).  What does not need the residual
-// sums (normalisers, ratios, w) is done first, while the sequence's last units are still at work.
+#define FSTAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
+
+// Inverse-CDF draw of one token from row `row` of sequence b (one wave), in index order, first token whose
+// running sum exceeds u * total.  mode 0: from the residual max(w p - q, 0) of row pair `row`, located by the
+// partial sums per wave chunk that the pair's units publish (polled here until all are there) and then by
+// the weights of that one chunk, formed again from the logits with alpha_p = L_p - log2 w and alpha_q = L_q;
+// a residual without any mass falls back to mode 1.  mode 1: from p_row itself, by the target row's
+// (shift, sum) words.
 template <typename T, bool ALIGNED, int LANE>
-__device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, int gamma, const double *own)
+__device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int row, int mode, double alpha_p, double alpha_q,
+                                             float u, bool &gave_up)
 {
-    // `own` (LDS, written by this same wave): log2 r, L_p, L_q, M_p and the word for the next position of the
-    // sequence's last row pair, whose leader this wave is - they need no trip through device memory
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = LANE / kVec;
     constexpr int kUnitLogits = kWave * LANE;
-    constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
     const int lane = threadIdx.x & 63;
-    // `gamma` is this sequence's draft length; G, the call's (largest) draft length, is the stride of every array
     const int G = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
     const T *target = static_cast<const T *>(P.target);
     const T *draft = static_cast<const T *>(P.draft);
     const size_t base = (size_t)b * (G + 1);
-    const int e_lane = lane < nu ? lane : nu - 1;
-    bool gave_up = false;
-#define FSTAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
+    const size_t drow = (size_t)b * G + (mode == 0 ? row : 0);
+    const u64 *st = P.pstat + (base + row) * nu;
+    const unsigned *sp = P.spart + drow * nu;
 
-    // ---- row results live in lane j's registers (gamma <= 64): log2 r_{j+1}, L_p, L_q and M_p as the
-    // row's first unit published them
-    double my_Lp = 0.0, my_Lq = 0.0, my_lr = 0.0;
-    float my_Mp = 0.f;
-    // everything the tests need is asked for at once (one round trip instead of three): the rows' words, log2 w,
-    // the uniforms and the first batch of partial sums; what is not there yet is polled where it is used
-    const u64 *lw_word = P.lw + (size_t)b * G + (lane < gamma ? lane : gamma - 1);
-    const float *eta = P.uniforms + (size_t)b * (G + 1);
-    u64 lw_first = 0;
-    unsigned sw_first[kBatch];
-    {
-        const size_t drow = (size_t)b * G + (lane < gamma ? lane : gamma - 1);
-        u64 w0 = ld_u64(P.ratio + drow), w1 = ld_u64(P.rowstat + drow * 3), w2 = ld_u64(P.rowstat + drow * 3 + 1),
-            w3 = ld_u64(P.rowstat + drow * 3 + 2);
-        lw_first = ld_u64(lw_word);
-#pragma unroll
-        for (int jj = 0; jj < kBatch; ++jj) {
-            const int j = jj < gamma ? jj : gamma - 1;
-            sw_first[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
+    // ---- first the wave chunk that holds t = u * total ...
+    float Mrow = 0.f;
+    RowCoef rc = {};
+    if (mode == 0) rc = make_row_coef(alpha_p, alpha_q);
+    else Mrow = row_max_shift(st, nu, P.spin_limit, gave_up);
+    int slot = -1, last_nonzero = 0;
+    double t_in = 0.0;
+    for (int attempt = 0; attempt < 2 && slot < 0; ++attempt) {
+        double total = 0.0, t = 0.0;
+        for (int pass_no = 0; pass_no < 2; ++pass_no) {           // pass 0: total; pass 1: locate t = u * total
+            double carry = 0.0;
+            for (int e0 = 0; e0 < nu; e0 += kWave) {
+                const int e = e0 + lane, ee = e < nu ? e : nu - 1;
+                double part = 0.0;
+                if (mode == 0) {
+                    unsigned w = ld_u32(sp + ee);
+                    if (pass_no == 0) w = wait_word32(sp + ee, w, e < nu, P.spin_limit, gave_up);
+                    if (e < nu) part = (double)unpack_partial(w);
+                } else {
+                    const u64 v = ld_u64(st + ee);
+                    const float sh = stat_shift(v);
+                    if (e < nu && sh > -INFINITY) part = (double)(stat_sum(v) * fast_exp2(sh - Mrow));
+                }
+                const double inc = wave_scan(part) + carry;
+                if (pass_no == 1 && slot < 0) {
+                    const u64 hit = __ballot(e < nu && inc > t);
+                    const u64 nz = __ballot(e < nu && part > 0.0);
+                    if (nz) last_nonzero = e0 + 63 - __clzll((long long)nz);
+                    if (hit) {
+                        const int first = __ffsll((long long)hit) - 1;
+                        slot = e0 + first;
+                        t_in = t - read_lane_double(inc - part, first);
+                    }
+                }
+                carry = read_lane_double(inc, kWave - 1);
+            }
+            if (pass_no == 0) { total = carry; t = (double)u * total; }
         }
-        w0 = wait_word(P.ratio + drow, w0, lane < gamma - 1, P.spin_limit, gave_up);
-        w1 = wait_word(P.rowstat + drow * 3, w1, lane < gamma - 1, P.spin_limit, gave_up);
-        w2 = wait_word(P.rowstat + drow * 3 + 1, w2, lane < gamma - 1, P.spin_limit, gave_up);
-        w3 = wait_word(P.rowstat + drow * 3 + 2, w3, lane < gamma - 1, P.spin_limit, gave_up);
-        my_lr = unpack_ratio(w0); my_Lp = unpack_ratio(w1); my_Lq = unpack_ratio(w2);
-        my_Mp = __uint_as_float((unsigned)(w3 >> 32));
-        if (lane == gamma - 1) { my_lr = own[0]; my_Lp = own[1]; my_Lq = own[2]; my_Mp = (float)own[3]; }
+        if (slot < 0) {
+            if (mode == 0 && !(total > 0.0)) {                         // no residual mass: draw from p_row
+                mode = 1;
+                Mrow = row_max_shift(st, nu, P.spin_limit, gave_up);
+                continue;
+            }
+            slot = last_nonzero; t_in = INFINITY;                      // rounding pushed t past the end
+        }
     }
+    if (slot < 0) { slot = 0; t_in = INFINITY; }
+
+    // ---- ... then the token inside that chunk: weights recomputed from the logits, walked in
+    // vocabulary order (vector, lane, element)
+    const T *prow = target + (base + row) * P.tstride;
+    const T *qrow = draft + drow * P.dstride;
+    const int first = slot * kUnitLogits + lane * kVec;
+    float xp[kNV][kVec], xq[kNV][kVec];
+#pragma unroll
+    for (int v = 0; v < kNV; ++v) {
+        load_vec<T, ALIGNED>(prow, V, first + v * kWave * kVec, xp[v]);
+        if (mode == 0) load_vec<T, ALIGNED>(qrow, V, first + v * kWave * kVec, xq[v]);
+    }
+    const u64 sv = wait_word(st + slot, P.spin_limit, gave_up);
+    const float shift = stat_shift(sv), scale = fast_exp2(shift - Mrow);
+    float t = mode == 0 ? (float)(t_in / (double)rc.cq) : (float)t_in;
+    int y = -1, last_positive = -1;
+#pragma unroll
+    for (int v = 0; v < kNV; ++v) {
+        const int idx = first + v * kWave * kVec;
+        float wgt[kVec];
+        if (mode == 0) {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) wgt[e] = fmaxf(residual_term(xp[v][e], xq[v][e], k, rc), 0.f);
+        } else {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) wgt[e] = fast_exp2(__builtin_fmaf(xp[v][e], k, -shift)) * scale;
+        }
+        float mine = 0.f;
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            mine += wgt[e];
+            if (wgt[e] > 0.f) last_positive = idx + e;
+        }
+        const float inc = wave_scan(mine);
+        const float total = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(inc), kWave - 1));
+        const u64 hit = __ballot(inc > t);
+        if (y < 0 && hit) {
+            const int first_lane = __ffsll((long long)hit) - 1;
+            int cand = -1;
+            if (lane == first_lane) {
+                float run = inc - mine;
+                int lastpos = 0;
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) {
+                    run += wgt[e];
+                    if (wgt[e] > 0.f) lastpos = e;
+                    if (cand < 0 && run > t) cand = e;
+                }
+                if (cand < 0) cand = lastpos;     // scan and walk rounded differently: last positive weight
+                cand += idx;
+            }
+            y = __builtin_amdgcn_readlane(cand, first_lane);
+        }
+        t -= total;
+    }
+    if (y < 0) {
+        // t lies beyond the chunk's recomputed total: the last token of positive weight
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) last_positive = max(last_positive, __shfl_xor(last_positive, off, kWave));
+        y = last_positive < 0 ? 0 : last_positive;
+    }
+    return y;
+}
+
+// Accept tests of one sequence (one wave: the leader of the sequence's last row pair).  Returns tau and writes
+// it; y_out is the token that the leader of row pair tau has drawn from its residual, or -1 when tau is the
+// last row pair or beyond (then the caller draws); lw_own is log2 w of the last row pair.
+// `own` (LDS, written by this same wave): log2 r, L_p, L_q and the word for the next position of the
+// sequence's last row pair - they need no trip through device memory.
+__device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int gamma, const double *own, int &y_out,
+                                              double &lw_own, u64 &last_first, bool &gave_up)
+{
+    constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
+    const int lane = threadIdx.x & 63;
+    // `gamma` is this sequence's draft length; G, the call's (largest) draft length, is the stride of every array
+    const int G = P.gamma, nu = P.nu;
+    const size_t base = (size_t)b * (G + 1);
+    const int e_lane = lane < nu ? lane : nu - 1;
+
+    // everything the tests need is asked for at once (one round trip): the rows' ratios, log2 w, the uniforms,
+    // the first batch of partial sums and the tokens the rows' leaders have drawn; what is not there yet is
+    // polled where it is used.  Lane j holds what belongs to row pair j (gamma <= 64).
+    const size_t drow_l = (size_t)b * G + (lane < gamma ? lane : gamma - 1);
+    const u64 *lw_word = P.lw + drow_l;
+    const float *eta = P.uniforms + (size_t)b * (G + 1);
+    u64 w0 = ld_u64(P.ratio + drow_l);
+    const u64 lw_first = ld_u64(lw_word);
+    unsigned sw_first[kBatch];
+#pragma unroll
+    for (int jj = 0; jj < kBatch; ++jj) {
+        const int j = jj < gamma ? jj : gamma - 1;
+        sw_first[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
+    }
+    const unsigned cand_first = ld_u32(P.ycand + drow_l);
+    last_first = ld_u64(P.pstat + (base + gamma) * nu + e_lane);    // for the clean-up at the very end
+    w0 = wait_word(P.ratio + drow_l, w0, lane < gamma - 1, P.spin_limit, gave_up);
+    double my_lr = unpack_ratio(w0);                    // log2 r_{lane+1}
+    if (lane == gamma - 1) my_lr = own[0];
     FSTAMP(7);
-    // log2 w_j for lane j as the rows' first units published it (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4
+    // log2 w_j for lane j as the rows' leaders published it (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4
     // drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, my_lw_raw = 0.0, lw_last = 0.0;
     {
@@ -472,9 +593,8 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     const double lw_rule = __shfl_down(my_lw_raw, 1, kWave);
     const u64 have = __ballot(j < gamma && residual_needed(P, j, j < gamma ? lw_rule : 0.0, eta_j));
 
-    // ---- S_j = sum of row j's partial sums, into lane j.  kept[jj]
-    // holds this lane's partial sum of row jj when gamma <= kBatch (used again for the draw).
-    float my_S = 0.f, kept[kBatch];
+    // ---- S_j = sum of row j's partial sums, into lane j
+    float my_S = 0.f;
     for (int j0 = 0; j0 < gamma; j0 += kBatch) {
         unsigned sw[kBatch];
 #pragma unroll
@@ -489,14 +609,12 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
 #pragma unroll
         for (int jj = 0; jj < kBatch; ++jj) {
             const int j = j0 + jj;
-            kept[jj] = 0.f;
             if (j >= gamma) continue;
             if (j > 0 && !((have >> (j - 1)) & 1)) continue;      // no partial sums were formed for this row: S stays 0
             const size_t drow = (size_t)b * G + j;
             float acc = 0.f;
             const unsigned w = wait_word32(P.spart + drow * nu + e_lane, sw[jj], lane < nu, P.spin_limit, gave_up);
             if (lane < nu) acc = unpack_partial(w);
-            kept[jj] = acc;
             for (int e = lane + kWave; e < nu; e += kWave) {
                 acc += unpack_partial(wait_word32(P.spart + drow * nu + e, P.spin_limit, gave_up));
             }
@@ -533,151 +651,37 @@ __device__ __forceinline__ void finalize_sequence(const FusedParams &P, int b, i
     if (P.algo == kToken) tau = passed == ~0ull ? 64 : __ffsll((long long)~passed) - 1;    // leading run of passes
     else tau = passed ? 64 - __clzll((long long)passed) : 0;                               // last passing sub-block
     if (lane == 0) P.accept_len[b] = tau;
-
     FSTAMP(10);
-    // ---- inverse-CDF draw of Y: first the wave chunk of row tau that holds t = u * total ...
-    const float u = eta[gamma];
-    int mode = tau < gamma ? 0 : 1;                     // 0: residual weights; 1: p_tau itself
-    float Mrow = 0.f;
-    RowCoef rc = {};
-    float part0 = 0.f;                                  // this lane's entry `lane` of the row's partial sums
-    const u64 *st = P.pstat + (base + tau) * nu;
-    const unsigned *sp = P.spart + ((size_t)b * G + (tau < gamma ? tau : 0)) * nu;
-    if (tau < gamma) {
-        Mrow = __shfl(my_Mp, tau, kWave);
-        rc = make_row_coef(__shfl(my_Lp, tau, kWave) - __shfl(my_lw, tau, kWave), __shfl(my_Lq, tau, kWave));
-        if (gamma <= kBatch) {
-#pragma unroll
-            for (int jj = 0; jj < kBatch; ++jj)
-                if (jj == tau) part0 = kept[jj];
-        } else if (lane < nu) part0 = unpack_partial(ld_u32(sp + lane));
-    } else {
-        // everything accepted: Y comes from p_gamma; its words are polled until they are all there
-        Mrow = row_max_shift(st, nu, P.spin_limit, gave_up);
-    }
-    int slot = -1, last_nonzero = 0;
-    double t_in = 0.0;
-    for (int attempt = 0; attempt < 2 && slot < 0; ++attempt) {
-        double total = 0.0, t = 0.0;
-        for (int pass_no = 0; pass_no < 2; ++pass_no) {           // pass 0: total; pass 1: locate t = u * total
-            double carry = 0.0;
-            for (int e0 = 0; e0 < nu; e0 += kWave) {
-                const int e = e0 + lane;
-                double part = 0.0;
-                if (e < nu) {
-                    if (mode == 0) part = e0 == 0 ? (double)part0 : (double)unpack_partial(ld_u32(sp + e));
-                    else {
-                        const u64 v = ld_u64(st + e);
-                        const float sh = stat_shift(v);
-                        part = sh > -INFINITY ? (double)(stat_sum(v) * fast_exp2(sh - Mrow)) : 0.0;
-                    }
-                }
-                const double inc = wave_scan(part) + carry;
-                if (pass_no == 1 && slot < 0) {
-                    const u64 hit = __ballot(e < nu && inc > t);
-                    const u64 nz = __ballot(e < nu && part > 0.0);
-                    if (nz) last_nonzero = e0 + 63 - __clzll((long long)nz);
-                    if (hit) {
-                        const int first = __ffsll((long long)hit) - 1;
-                        slot = e0 + first;
-                        t_in = t - read_lane_double(inc - part, first);
-                    }
-                }
-                carry = read_lane_double(inc, kWave - 1);
-            }
-            if (pass_no == 0) { total = carry; t = (double)u * total; }
-        }
-        if (slot < 0) {
-            if (mode == 0 && !(total > 0.0)) { mode = 1; continue; }   // no residual mass: draw from p_tau
-            slot = last_nonzero; t_in = INFINITY;                      // rounding pushed t past the end
-        }
-    }
-    if (slot < 0) { slot = 0; t_in = INFINITY; }
 
-    FSTAMP(11);
-    u64 last_first_word = 0;
-    // ---- ... then the token inside that chunk: weights recomputed from the logits, walked in
-    // vocabulary order (vector, lane, element)
-    {
-        const T *prow = target + (base + tau) * P.tstride;
-        const T *qrow = draft + ((size_t)b * G + (tau < gamma ? tau : 0)) * P.dstride;
-        const u64 sv = ld_u64(st + slot);
-        const int first = slot * kUnitLogits + lane * kVec;
-        float xp[kNV][kVec], xq[kNV][kVec];
-#pragma unroll
-        for (int v = 0; v < kNV; ++v) {
-            load_vec<T, ALIGNED>(prow, V, first + v * kWave * kVec, xp[v]);
-            if (mode == 0) load_vec<T, ALIGNED>(qrow, V, first + v * kWave * kVec, xq[v]);
-        }
-        // the last target row's words, wanted at the very end, are asked for now as well
-        last_first_word = ld_u64(P.pstat + (base + gamma) * nu + e_lane);
-        // ---- the sequence's words are left zero for the next call.  Every reader of the row-pair words has published
-        // its partial sum by now and this wave has read all of those, so all but the target rows' words (needed once
-        // more below) can go now; the stores come after the loads, whose data would otherwise queue behind them.
-        for (int e = lane; e < G * nu; e += kWave) {
-            st_u32(P.spart + (size_t)b * G * nu + e, 0);
-        }
-        for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
-        for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); }
-        for (int e = lane; e < 3 * G; e += kWave) st_u64(P.rowstat + (size_t)b * G * 3 + e, 0);
-        const float shift = stat_shift(sv), scale = fast_exp2(shift - Mrow);
-        float t = mode == 0 ? (float)(t_in / (double)rc.cq) : (float)t_in;
-        int y = -1, last_positive = -1;
-#pragma unroll
-        for (int v = 0; v < kNV; ++v) {
-            const int idx = first + v * kWave * kVec;
-            float wgt[kVec];
-            if (mode == 0) {
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) wgt[e] = fmaxf(residual_term(xp[v][e], xq[v][e], k, rc), 0.f);
-            } else {
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) wgt[e] = fast_exp2(__builtin_fmaf(xp[v][e], k, -shift)) * scale;
-            }
-            float mine = 0.f;
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) {
-                mine += wgt[e];
-                if (wgt[e] > 0.f) last_positive = idx + e;
-            }
-            const float inc = wave_scan(mine);
-            const float total = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(inc), kWave - 1));
-            const u64 hit = __ballot(inc > t);
-            if (y < 0 && hit) {
-                const int first_lane = __ffsll((long long)hit) - 1;
-                int cand = -1;
-                if (lane == first_lane) {
-                    float run = inc - mine;
-                    int lastpos = 0;
-#pragma unroll
-                    for (int e = 0; e < kVec; ++e) {
-                        run += wgt[e];
-                        if (wgt[e] > 0.f) lastpos = e;
-                        if (cand < 0 && run > t) cand = e;
-                    }
-                    if (cand < 0) cand = lastpos;     // scan and walk rounded differently: last positive weight
-                    cand += idx;
-                }
-                y = __builtin_amdgcn_readlane(cand, first_lane);
-            }
-            t -= total;
-        }
-        if (y < 0) {
-            // t lies beyond the chunk's recomputed total: the last token of positive weight
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) last_positive = max(last_positive, __shfl_xor(last_positive, off, kWave));
-            y = last_positive < 0 ? 0 : last_positive;
-        }
-        if (lane == 0) P.next_token[b] = y;
-    }
+    // ---- the tokens that the leaders of the row pairs before the last one have drawn: all of them are waited
+    // for (not only tau's), because their leaders read the partial sums that are zeroed when the sequence is done
+    const bool drawn = lane <= gamma - 2 && (lane == 0 || ((have >> (lane - 1)) & 1));
+    const unsigned cand = wait_word32(P.ycand + drow_l, cand_first, drawn, P.spin_limit, gave_up);
+    y_out = tau <= gamma - 2 ? __builtin_amdgcn_readlane((int)cand, tau) - 2 : -1;
+    lw_own = read_lane_double(my_lw, gamma - 1);
+    return tau;
+}
 
-    FSTAMP(12);
-    // ---- the target rows' words: those of the last target row must all be written first
-    wait_word(P.pstat + (base + gamma) * nu + e_lane, last_first_word, lane < nu, P.spin_limit, gave_up);
-    for (int e = lane + kWave; e < nu; e += kWave) wait_word(P.pstat + (base + gamma) * nu + e, P.spin_limit, gave_up);
-    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
+// The sequence's control words are left zero for the next call (one wave, after Y is known).  Every reader of
+// the row-pair words has published something this wave has waited for: the units their partial sums (or, where
+// no residual mass is formed, nothing was read but by the leader), the leaders their ratio and their token.
+__device__ __forceinline__ void finalize_cleanup(const FusedParams &P, int b, int gamma, u64 last_first, bool &gave_up)
+{
+    const int lane = threadIdx.x & 63;
+    const int G = P.gamma, nu = P.nu;
+    const size_t base = (size_t)b * (G + 1);
+    const int e_lane = lane < nu ? lane : nu - 1;
+    // the last target row's words must all be written before the target rows' words can go (`last_first`: what
+    // was there when the tests began)
+    const u64 *last = P.pstat + (base + gamma) * nu;
+    for (int e = lane; e < G * nu; e += kWave) st_u32(P.spart + (size_t)b * G * nu + e, 0);
+    for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
+    for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); st_u32(P.ycand + (size_t)b * G + e, 0); }
+    wait_word(last + e_lane, last_first, lane < nu, P.spin_limit, gave_up);
+    for (int e = lane + kWave; e < nu; e += kWave) wait_word(last + e, P.spin_limit, gave_up);
     for (int e = lane; e < (G + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
 }
+#undef FSTAMP
 
 // ------------------------------------------------------------------ the kernel
 template <typename T, bool ALIGNED, int NW, int LANE>
@@ -830,12 +834,8 @@ void fused_verify_kernel(const FusedParams P)
             lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
             if (lane == 0) {
                 if (finisher) {                     // nobody else reads the last row pair's words
-                    own_values[0] = unpack_ratio(pack_ratio(lr)); own_values[1] = unpack_ratio(pack_ratio(Lp));
-                    own_values[2] = unpack_ratio(pack_ratio(Lq)); own_values[3] = (double)Mp;
+                    own_values[0] = unpack_ratio(pack_ratio(lr)); own_values[1] = Lp; own_values[2] = Lq;
                 } else {
-                    st_u64(P.rowstat + drow * 3, pack_ratio(Lp));
-                    st_u64(P.rowstat + drow * 3 + 1, pack_ratio(Lq));
-                    st_u64(P.rowstat + drow * 3 + 2, ((u64)__float_as_uint(Mp) << 32) | 1ull);
                     st_u64(P.ratio + drow, pack_ratio(lr));
                 }
             }
@@ -862,6 +862,9 @@ void fused_verify_kernel(const FusedParams P)
         SV_STAMP(2);
     }
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
+    // a draw that this wave makes: row, mode and the two row constants (see draw_from_row); -1: none
+    int draw_row = -1, draw_mode = 0;
+    double draw_ap = 0.0, draw_aq = 0.0;
     if (needed) {
     __syncthreads();
     const double Lp = row_values[0], Lq = row_values[1];
@@ -893,16 +896,41 @@ void fused_verify_kernel(const FusedParams P)
         st_u32(P.spart + drow * nu + U.c, pack_partial(acc));
     }
     SV_STAMP(4);
+    // the row's leader draws the token that follows if this position becomes tau, while the later positions are
+    // still streaming: whoever finishes the sequence then only picks it up
+    if (leader && !finisher) { draw_row = U.i; draw_ap = Lp - log2w; draw_aq = Lq; }
 
     }
+    if (!leader) return;
     // the leader of a sequence's last row pair finishes the sequence: the earlier positions come before
     // it in the workgroup order, the last target row (needed only if every token is accepted) right after
+    int y = -1;
+    u64 last_first = 0;
     if (finisher) {
         SV_STAMP(5);
         __builtin_amdgcn_wave_barrier();                     // own_values: written by lane 0 above, read by another lane below
-        finalize_sequence<T, ALIGNED, LANE>(P, U.b, gb, own_values);
+        double lw_own;
+        const int tau = finalize_tests(P, U.b, gb, own_values, y, lw_own, last_first, gave_up);
+        if (y < 0) {
+            // tau is the last row pair (its residual: this wave has the row's constants) or every token was
+            // accepted (Y comes from the last target row itself)
+            draw_row = tau; draw_mode = tau == gb ? 1 : 0;
+            draw_ap = own_values[1] - lw_own; draw_aq = own_values[2];
+        }
+    }
+    if (draw_row >= 0) {
+        const float u = P.uniforms[(size_t)U.b * (gamma + 1) + gb];
+        const int drawn = draw_from_row<T, ALIGNED, LANE>(P, U.b, draw_row, draw_mode, draw_ap, draw_aq, u, gave_up);
+        if (finisher) y = drawn;
+        else if (lane == 0) st_u32(P.ycand + (size_t)U.b * gamma + draw_row, (unsigned)drawn + 2u);
+    }
+    if (finisher) {
+        if (lane == 0) P.next_token[U.b] = y;
+        SV_STAMP(12);
+        finalize_cleanup(P, U.b, gb, last_first, gave_up);
         SV_STAMP(6);
     }
+    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
 #undef SV_STAMP
 }
 
