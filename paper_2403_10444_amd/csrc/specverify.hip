@@ -102,7 +102,7 @@ sv_status_t launch_staged(int algo, const void *target_v, const void *draft_v, c
         target, draft, tstride, dstride, B, gamma, V, k, L.nchunks, stats);
     const size_t sm2 = 2 * (gamma + 1) * sizeof(double) + 2 * (gamma + 1) * sizeof(float);
     prefix_weights_kernel<T><<<B, 64, sm2, stream>>>(target, draft, tstride, dstride, tokens, gamma, V, k, kd, kd / (double)k - 1.0, L.nchunks,
-                                                    n_target_rows, algo, stats, coef, draft_lens);
+                                                    n_target_rows, algo, stats, coef, draft_lens, uniforms, debug_out ? 1 : 0);
     const unsigned pair_blocks = (unsigned)((size_t)B * gamma * L.nchunks);
     residual_kernel<T, ALIGNED><<<pair_blocks, kThreads, 0, stream>>>(
         target, draft, tstride, dstride, gamma, V, k, L.nchunks, coef, spart);

@@ -23,7 +23,7 @@ struct SeqCoef {
     double one_minus_w;
     double log2r;        // log2 r_i (ratio of draft token i, judged with rows i-1); 0 at i = 0
     float row_max;       // maximum over the target row's chunks of (chunk max * k)
-    float pad;
+    int needed;          // whether S_i can matter (see prefix_weights_kernel); where not, no partial sums are formed
 };
 
 template <typename T, bool ALIGNED>
@@ -65,7 +65,8 @@ __global__ __launch_bounds__(64) void prefix_weights_kernel(
     const T *__restrict__ target, const T *__restrict__ draft, size_t tstride, size_t dstride,
     const int32_t *__restrict__ tokens,
     int gamma, int V, float k, double kd, double k_eps, int nchunks, int n_target_rows, int algo,
-    const float2 *__restrict__ stats, SeqCoef *__restrict__ coef, const int32_t *__restrict__ draft_lens)
+    const float2 *__restrict__ stats, SeqCoef *__restrict__ coef, const int32_t *__restrict__ draft_lens,
+    const float *__restrict__ uniforms, int every_residual)
 {
     extern __shared__ double sm[];          // [2*(gamma+1)] log2-normalisers, then row maxima
     double *L_p = sm, *L_q = sm + (gamma + 1);
@@ -93,16 +94,25 @@ __global__ __launch_bounds__(64) void prefix_weights_kernel(
 
     // Alg. 2, the recursion for w_i (the paper's p_i), carried as log2 w_i so that products of
     // ratios neither overflow nor lose 1 - w_i when w_i is close to 1.
+    // Which residual masses can matter: h_i = S_i / (S_i + 1 - w_i) <= w_i because S_i <= w_i, so a test with
+    // eta_i >= w_i fails whatever S_i is and position i cannot become tau (margin far above the rounding of h_i);
+    // Alg. 1 stops at the first failed test, so only positions that all earlier tests let through can.
+    // Position 0 is where tau = 0 draws from.  `every_residual`: the caller wants every S_i reported.
     double log2w = 0.0, log2r = 0.0;
+    bool prefix_pass = true;
+    const float *eta = uniforms + (size_t)b * (gamma + 1);
     for (int i = 0; i <= gb; ++i) {
         SeqCoef sc;
+        if (i >= 1) prefix_pass = prefix_pass && (double)eta[i - 1] < exp2(fmin(log2r, 0.0));
+        sc.needed = (i == 0 || every_residual) ? 1
+                  : algo == kToken ? (prefix_pass ? 1 : 0)
+                  : (log2((double)eta[i - 1]) < log2w + 1.0e-3 ? 1 : 0);
         const double lw = (algo == kToken) ? 0.0 : log2w;     // token verification: residual is p - q
         sc.rc = make_row_coef(L_p[i] - lw, i < gb ? L_q[i] : 0.0);
         sc.w = exp2(lw);
         sc.one_minus_w = -expm1(lw * 0.69314718055994530942);
         sc.log2r = log2r;
         sc.row_max = M_p[i];
-        sc.pad = 0.f;
         coef[(size_t)b * (gamma + 1) + i] = sc;
         if (i < gb) {
             // r_{i+1} = p_i(X_{i+1}) / q_i(X_{i+1}) from the two gathered logits.  The sweeps scale
@@ -131,6 +141,7 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
     __shared__ float lds[kWaves];
     const int pr = blockIdx.x / nchunks, c = blockIdx.x - pr * nchunks, tid = threadIdx.x;
     const int b = pr / gamma, i = pr - b * gamma;
+    if (!coef[(size_t)b * (gamma + 1) + i].needed) return;      // this position's residual mass cannot matter (whole workgroup)
     const RowCoef rc = coef[(size_t)b * (gamma + 1) + i].rc;
     const T *prow = target + ((size_t)b * (gamma + 1) + i) * tstride;
     const T *qrow = draft + ((size_t)b * gamma + i) * dstride;
@@ -176,7 +187,8 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
         if (i < gb) {
             double acc = 0.0;
             const float *sp = spart + ((size_t)b * gamma + i) * nchunks;
-            for (int c = 0; c < nchunks; ++c) acc += (double)sp[c];
+            if (scb[i].needed)                      // otherwise no partial sums were formed: the test fails whatever S_i is
+                for (int c = 0; c < nchunks; ++c) acc += (double)sp[c];
             S[i] = acc * (double)scb[i].rc.cq;
         } else {
             S[i] = scb[i].w;       // q_gamma == 0: the residual mass of the last row is w_gamma
@@ -198,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(
             // one (w unclipped; at w >= 1 the ratio is >= 1 and every eta in [0, 1) passes)
             else h = scb[i].w >= 1.0 ? 1.0 : S[i] / (S[i] + scb[i].one_minus_w);
             if (i >= 1) {
-                const bool pass = (double)eta[i - 1] < h;
+                const bool pass = (double)eta[i - 1] < h && (i == gb || scb[i].needed);
                 if (algo == kToken) { if (pass && tau == i - 1) tau = i; }              // stops at the first failure
                 else if (pass) tau = i;                                                 // last passing sub-block
             }
