@@ -26,6 +26,7 @@ struct ProbWeight {
     double one_minus_w;
     double h_token;      // min(r_i, 1), r_i the ratio of drafted token i judged with rows i-1; 1 at i = 0
     float w_hi, w_lo;    // w_i split into two floats
+    int needed;          // whether the sums over rows i can matter (see probs_weights_kernel); where not, none are formed
 };
 
 // kVec consecutive probabilities of a row; elements at or beyond V count as 0
@@ -59,7 +60,7 @@ template <typename T>
 __global__ __launch_bounds__(64) void probs_weights_kernel(
     const T *__restrict__ target, const T *__restrict__ draft, size_t tstride, size_t dstride,
     const int32_t *__restrict__ tokens, const int32_t *__restrict__ draft_lens, int gamma, int algo,
-    ProbWeight *__restrict__ weights)
+    ProbWeight *__restrict__ weights, const float *__restrict__ uniforms, int every_sum)
 {
     const int b = blockIdx.x, lane = threadIdx.x;
     const int gb = clamped_draft_len(draft_lens, b, gamma);
@@ -84,9 +85,11 @@ __global__ __launch_bounds__(64) void probs_weights_kernel(
     if (lane == 0) {
         ProbWeight first;
         first.w = 1.0; first.one_minus_w = 0.0; first.h_token = 1.0; first.w_hi = 1.f; first.w_lo = 0.f;
+        first.needed = 1;                                  // tau = 0 draws from the residual of rows 0
         wb[0] = first;
     }
-    if (lane >= gb) return;
+    const int i = lane + 1;
+    const double w_block = exp2(log2w);
     if (algo == kToken) log2w = 0.0;
     ProbWeight pw;
     pw.w = exp2(log2w);
@@ -94,7 +97,18 @@ __global__ __launch_bounds__(64) void probs_weights_kernel(
     pw.h_token = exp2(fmin(log2r, 0.0));
     pw.w_hi = (float)pw.w;
     pw.w_lo = (float)(pw.w - (double)pw.w_hi);
-    wb[lane + 1] = pw;
+    // Which sums can matter (exact, whatever the rows sum to).  Alg. 1 stops at the first failed test, so only a
+    // position that every earlier test let through can become tau; the last target row is summed (and drawn
+    // from) only if tau = gamma: every test passed (Alg. 1), or the last one did (Alg. 2 / 4: eta < w_gamma).
+    // The tests are evaluated with the expressions the finishing kernel uses, on the same stored values.
+    const float eta_i = i <= gb ? uniforms[(size_t)b * (gamma + 1) + i - 1] : 1.f;
+    const unsigned long long failed = __ballot(i <= gb && !((double)eta_i < pw.h_token));
+    const bool prefix_pass = (failed & ((2ull << lane) - 1ull)) == 0;     // tests 1 .. i
+    if (i > gb) return;
+    if (every_sum) pw.needed = 1;
+    else if (algo == kToken) pw.needed = prefix_pass ? 1 : 0;
+    else pw.needed = (i < gb || (double)eta_i < fmin(w_block, 1.0)) ? 1 : 0;
+    wb[i] = pw;
 }
 
 template <typename T, bool ALIGNED, bool GREEDY>
@@ -110,6 +124,7 @@ __global__ __launch_bounds__(kThreads) void probs_residual_kernel(
     const int b = pr / (gamma + 1), i = pr - b * (gamma + 1);
     const int gb = clamped_draft_len(draft_lens, b, gamma);
     if (i > gb) return;                                          // a position this sequence does not use
+    if (!weights[pr].needed) return;                             // sums that cannot matter (whole workgroup)
     const T *target_seq = target + (size_t)b * (gamma + 1) * tstride;
     const T *draft_seq = draft + (size_t)b * gamma * dstride;
     const T *prow = target_seq + (size_t)i * tstride;
@@ -214,7 +229,8 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
     // S_i = sum over the chunks: wave (i mod 4) takes position i, lanes stride over the chunks
     for (int i = wave; i <= gb; i += kWaves) {
         double acc = 0.0, rej = 0.0;
-        for (int c = lane; c < nchunks; c += 64) {
+        // (rows whose sums were not formed: S stays 0, their tests are decided without it and they cannot become tau)
+        if (wb[i].needed) for (int c = lane; c < nchunks; c += 64) {
             const float2 v = pb[(size_t)i * nchunks + c];
             if (keep) kept[i * nchunks + c] = v.x;
             acc += (double)v.x; rej += (double)v.y;

@@ -126,7 +126,7 @@ sv_status_t launch_probs(int algo, const void *target_v, const void *draft_v, co
     float2 *part = reinterpret_cast<float2 *>(ws + L.off_stats);
     ProbWeight *weights = reinterpret_cast<ProbWeight *>(ws + L.off_coef);
     const unsigned blocks = (unsigned)((size_t)B * (gamma + 1) * L.nchunks);
-    probs_weights_kernel<T><<<B, 64, 0, stream>>>(target, draft, tstride, dstride, tokens, draft_lens, gamma, algo, weights);
+    probs_weights_kernel<T><<<B, 64, 0, stream>>>(target, draft, tstride, dstride, tokens, draft_lens, gamma, algo, weights, uniforms, debug_out ? 1 : 0);
     if (algo == kGreedy)
         probs_residual_kernel<T, ALIGNED, true><<<blocks, kThreads, 0, stream>>>(
             target, draft, tstride, dstride, draft_lens, gamma, V, L.nchunks, part, weights);
