@@ -405,3 +405,24 @@ def test_greedy_rejected_mass_equals_residual_mass_plus_one_minus_w():
     assert below.any() and (~below).any()
     np.testing.assert_allclose(h[below], np.minimum(S[below] / (S[below] + 1.0 - w[below]), 1.0), rtol=1e-9, atol=1e-12)
     assert np.all(h[~below] == 1.0)
+
+
+@pytest.mark.parametrize("algo", [oracle.BLOCK, oracle.GREEDY])
+def test_acceptance_probability_never_exceeds_w(algo):
+    """S_i = sum_x max(w_i p_i - q_i, 0) <= sum_x w_i p_i = w_i, and S / (S + 1 - w) grows with S, so
+    h_i <= w_i / (w_i + 1 - w_i) = w_i (Alg. 2; Alg. 4 with its unclipped weight, where h_i = 1 <= w_i once w_i >= 1).
+    A test with eta_i >= w_i therefore fails whatever S_i is - what lets the kernels leave such a position's
+    residual mass unformed.  Checked on the oracle's own w, S and h, and on its decisions: no position whose
+    uniform is at or above w_i is ever the accepted length."""
+    rng = np.random.default_rng(1234)
+    tl, dl, tok, uni = _random_call(rng, 200, 6, 300)
+    out = oracle.verify(algo, tl, dl, tok, uni, 0.8)
+    w, S, h = out["dbg"][:, 1:, 0], out["dbg"][:, 1:, 1], out["dbg"][:, 1:, 2]         # positions 1 .. gamma
+    assert np.all(S <= w * (1 + 1e-12))
+    assert np.all(h <= np.maximum(w, 0.0) * (1 + 1e-12) + 1e-300)
+    hopeless = uni[:, :6] >= w                                  # eta_i >= w_i
+    assert hopeless.any() and (~hopeless).any()
+    tau = out["accept_len"]
+    for b in range(len(tau)):
+        if tau[b] >= 1:
+            assert not hopeless[b, tau[b] - 1]
