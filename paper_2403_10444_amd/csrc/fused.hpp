@@ -13,18 +13,21 @@
 //   2. turns them into exp2(y - shift) with a wave-uniform shift per row and KEEPS those 2 x LANE
 //      floats per lane in registers; its partial normalisers (shift, sum) meet those of the
 //      workgroup's other waves in LDS,
-//   3. sleeps at a barrier while the workgroup's first wave publishes the workgroup's two words,
-//      waits for the words of the other workgroups of the row, which give L_p and L_q, and for
-//      log2 w_i, which the previous position's leader published (Alg. 2: w_i = min(w_{i-1} r_i, 1));
-//      the first wave of the row's last workgroup is the row's leader: it also publishes the
-//      row's ratio, normalisers and log2 w_{i+1},
-//   4. forms its share of S_i from the registers and publishes it.
+//   3. sleeps at a barrier while the workgroup's first wave publishes the workgroup's two words and
+//      looks at log2 w_i, which the previous position's leader published (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
+//      The acceptance probability of Alg. 2 / 4 never exceeds w_i, so where the position's uniform is not below
+//      w_i its residual mass cannot matter (residual_needed) and the workgroup is done.  Otherwise the first wave
+//      waits for the words of the other workgroups of the row, which give L_p and L_q.  The first wave of the
+//      row's last workgroup is the row's leader and always stays: it publishes the row's ratio and log2 w_{i+1},
+//   4. forms its share of S_i from the registers and publishes it; the row's leader then draws the token that
+//      follows if this position becomes tau (draw_from_row) and publishes it.
 // Workgroups start position-major inside groups of sequences (all row pairs of position 0, then
 // position 1, ..., then the last target rows), so what an earlier position publishes is there
-// long before a later one asks for it, and a workgroup only ever waits for the workgroups of
-// its own row, which start next to it.  The first wave of a sequence's last row pair then
-// finishes the sequence: it waits for all of the sequence's partial sums and runs the accept
-// tests and the inverse-CDF draw.
+// before a later one asks for it, and a workgroup only ever waits for the workgroups of
+// its own row, which start next to it.  The leader of a sequence's last row pair finishes the
+// sequence: it collects the ratios and the partial sums, runs the accept tests (finalize_tests), picks up the
+// token drawn for position tau (or draws it, if tau is its own position or every token was accepted) and
+// zeroes the sequence's words (finalize_cleanup).
 //
 // Everything that crosses workgroups is a self-announcing word: it is zero between calls and
 // non-zero once written (a packed (shift, sum) pair always has a non-zero sum or a -inf shift;
@@ -82,13 +85,14 @@ struct FusedParams {
     int *header;
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
     unsigned *ycand;      // [B, gamma]               token drawn from the row pair's residual by its leader, + 2
-    u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy), same encoding; not for token verification
+    u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy), same encoding; token verification:
+                          //                          0 while every test up to i+1 has passed, kLog2RatioFloor afterwards
     u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
     int32_t *accept_len, *next_token;
     float *debug_out;
-    long long *prof;      // NULL, or [workgroups, 8] timestamps (100 MHz ticks) for tuning
+    long long *prof;      // NULL, or [workgroups, 16] timestamps (100 MHz ticks) for tuning
 };
 
 // ---- agent-scope accessors for words that other waves (on any XCD) write or read
