@@ -85,7 +85,9 @@ struct FusedParams {
     int *header;
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
     unsigned *ycand;      // [B, gamma]               token drawn from the row pair's residual by its leader, + 2
-    u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy), same encoding; token verification:
+    int *gen;             // [B]                      calls this sequence slot has finished (only its parity is used); never zeroed
+    u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy) as double bits with bit 0 set and the
+                          //                          parity of gen in bit 1 (pack_lw); token verification:
                           //                          0 while every test up to i+1 has passed, kLog2RatioFloor afterwards
     u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
@@ -111,6 +113,16 @@ __device__ __forceinline__ float stat_shift(u64 v) { return __uint_as_float((uns
 __device__ __forceinline__ float stat_sum(u64 v) { return __uint_as_float((unsigned)(v >> 32)); }
 __device__ __forceinline__ u64 pack_ratio(double log2r) { return (u64)__double_as_longlong(log2r) | 1ull; }
 __device__ __forceinline__ double unpack_ratio(u64 v) { return __longlong_as_double((long long)v); }
+// The words that carry log2 w from one position to the next are read by workgroups that publish nothing
+// afterwards (those whose residual mass is not formed), so nobody could tell when it is safe to zero them.
+// They are not zeroed: bit 1 carries the parity of the sequence's call count (`gen`, flipped by the wave that
+// finishes the sequence, after everybody who reads these words has read the count), and a word of the other
+// parity - the previous call's - counts as not written yet.  Positions that a call does not use are zeroed.
+__device__ __forceinline__ u64 pack_lw(double log2w, unsigned par)
+{
+    return ((u64)__double_as_longlong(log2w) & ~3ull) | 1ull | ((u64)par << 1);
+}
+__device__ __forceinline__ bool lw_there(u64 v, unsigned par) { return (v & 1ull) != 0 && ((unsigned)(v >> 1) & 1u) == par; }
 
 // The value a given lane holds (lane index uniform over the wave).
 __device__ __forceinline__ u64 read_lane_u64(u64 v, int lane)
@@ -135,6 +147,17 @@ __device__ __forceinline__ u64 wait_word(const u64 *p, u64 v, bool need, int lim
 __device__ __forceinline__ u64 wait_word(const u64 *p, int limit, bool &gave_up)
 {
     return wait_word(p, ld_u64(p), true, limit, gave_up);
+}
+
+__device__ __forceinline__ u64 wait_lw(const u64 *p, u64 v, unsigned par, bool need, int limit, bool &gave_up)
+{
+    int spins = 0;
+    while (__any(need && !lw_there(v, par))) {
+        if (++spins > limit) { gave_up = true; break; }
+        __builtin_amdgcn_s_sleep(1);
+        if (need && !lw_there(v, par)) v = ld_u64(p);
+    }
+    return v;
 }
 
 __device__ __forceinline__ unsigned wait_word32(const unsigned *p, unsigned v, bool need, int limit, bool &gave_up)
@@ -538,7 +561,7 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int ro
 // last row pair or beyond (then the caller draws); lw_own is log2 w of the last row pair.
 // `own` (LDS, written by this same wave): log2 r, L_p, L_q and the word for the next position of the
 // sequence's last row pair - they need no trip through device memory.
-__device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int gamma, const double *own, int &y_out,
+__device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int gamma, const double *own, unsigned par, int &y_out,
                                               double &lw_own, u64 &last_first, bool &gave_up)
 {
     constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
@@ -572,7 +595,7 @@ __device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int g
     // drops the min); lw_last is log2 w_gamma
     double my_lw = 0.0, my_lw_raw = 0.0, lw_last = 0.0;
     {
-        double next = unpack_ratio(wait_word(lw_word, lw_first, lane < gamma - 1, P.spin_limit, gave_up));   // log2 w_{lane+1}
+        double next = unpack_ratio(wait_lw(lw_word, lw_first, par, lane < gamma - 1, P.spin_limit, gave_up));   // log2 w_{lane+1}
         if (lane == gamma - 1) next = own[4];
         const double prev = __shfl_up(next, 1, kWave);
         my_lw_raw = lane ? prev : 0.0;
@@ -669,7 +692,7 @@ __device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int g
 // The sequence's control words are left zero for the next call (one wave, after Y is known).  Every reader of
 // the row-pair words has published something this wave has waited for: the units their partial sums (or, where
 // no residual mass is formed, nothing was read but by the leader), the leaders their ratio and their token.
-__device__ __forceinline__ void finalize_cleanup(const FusedParams &P, int b, int gamma, u64 last_first, bool &gave_up)
+__device__ __forceinline__ void finalize_cleanup(const FusedParams &P, int b, int gamma, u64 last_first, unsigned par, bool &gave_up)
 {
     const int lane = threadIdx.x & 63;
     const int G = P.gamma, nu = P.nu;
@@ -680,10 +703,15 @@ __device__ __forceinline__ void finalize_cleanup(const FusedParams &P, int b, in
     const u64 *last = P.pstat + (base + gamma) * nu;
     for (int e = lane; e < G * nu; e += kWave) st_u32(P.spart + (size_t)b * G * nu + e, 0);
     for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
-    for (int e = lane; e < G; e += kWave) { st_u64(P.ratio + (size_t)b * G + e, 0); st_u64(P.lw + (size_t)b * G + e, 0); st_u32(P.ycand + (size_t)b * G + e, 0); }
+    for (int e = lane; e < G; e += kWave) {
+        st_u64(P.ratio + (size_t)b * G + e, 0); st_u32(P.ycand + (size_t)b * G + e, 0);
+        if (e >= gamma - 1) st_u64(P.lw + (size_t)b * G + e, 0);     // only where this call had no reader (see pack_lw)
+    }
     wait_word(last + e_lane, last_first, lane < nu, P.spin_limit, gave_up);
     for (int e = lane + kWave; e < nu; e += kWave) wait_word(last + e, P.spin_limit, gave_up);
     for (int e = lane; e < (G + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
+    // the sequence's next call: every workgroup that reads the count has read it (their words were waited for)
+    if (lane == 0) __hip_atomic_store(P.gen + b, (int)(par ^ 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 #undef FSTAMP
 
@@ -727,17 +755,23 @@ void fused_verify_kernel(const FusedParams P)
     // fewest logits) publishes the row's ratio from them
     const int nwg = nu / kWaves;
     const bool leader = wave == 0 && wg_x == nwg - 1;
-    int tok = 0;
-    if (!U.last_row && leader) tok = P.tokens[drow];
     // log2 w_i (published by the previous position's leader, usually long ago) and the uniform of position i's
     // test: what decides whether this row's residual mass can matter at all
     const bool need_w = U.i > 0 && !U.last_row;
     const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 && !U.last_row ? U.i - 1 : 0);
-    u64 wt = 1;
-    float eta_i = 0.f;
-    if (wave == 0 && need_w) { wt = ld_u64(lw_word); eta_i = P.uniforms[(size_t)U.b * (gamma + 1) + U.i - 1]; }
-    float eta_next = 0.f;                                    // the uniform of test i + 1, which the leader judges for Alg. 1
-    if (leader && !U.last_row && P.algo == kToken) eta_next = P.uniforms[(size_t)U.b * (gamma + 1) + U.i];
+    // (the sequence's call count rides in the same block of loads as the word itself: a load in a block of its own
+    // makes the compiler wait for it, and for every load before it, at the end of that block)
+    int gen_count = 0;
+#define par ((unsigned)gen_count & 1u)
+    u64 wt = 0;
+    float eta_i = 0.f, eta_next = 0.f;
+    int tok = 0;                                             // the drafted token X_{i+1}, for the leader
+    if (wave == 0 && !U.last_row) {
+        tok = P.tokens[drow];
+        wt = ld_u64(lw_word); gen_count = P.gen[U.b];          // (the count does not change while the call runs: an ordinary load)
+        eta_i = P.uniforms[(size_t)U.b * (gamma + 1) + (U.i > 0 ? U.i - 1 : 0)];
+        eta_next = P.uniforms[(size_t)U.b * (gamma + 1) + U.i];      // the uniform of test i + 1, which the leader judges for Alg. 1
+    }
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     __shared__ u64 wave_words[2][kWaves];
@@ -780,7 +814,7 @@ void fused_verify_kernel(const FusedParams P)
         // can this row's residual mass matter?  Needs log2 w_i; a row that is not needed costs its workgroups no wait
         bool needed = true;
         if (need_w && P.prune && !P.debug_out) {
-            wt = wait_word(lw_word, wt, true, P.spin_limit, gave_up);
+            wt = wait_lw(lw_word, wt, par, true, P.spin_limit, gave_up);
             needed = residual_needed(P, U.i, unpack_ratio(wt), eta_i);
         }
         if (lane == 0) row_needed = needed ? 1 : 0;
@@ -805,11 +839,11 @@ void fused_verify_kernel(const FusedParams P)
             u64 v = ld_u64(word);
             if (need_w) wt = ld_u64(lw_word);
             int spins = 0;
-            while (__any((need && v == 0) || wt == 0)) {
+            while (__any((need && v == 0) || (need_w && !lw_there(wt, par)))) {
                 if (++spins > P.spin_limit) { gave_up = true; break; }
                 __builtin_amdgcn_s_sleep(1);
                 if (need && v == 0) v = ld_u64(word);
-                if (wt == 0) wt = ld_u64(lw_word);
+                if (need_w && !lw_there(wt, par)) wt = ld_u64(lw_word);
             }
             StatAcc acc;
             if (need) acc.add(v);
@@ -845,7 +879,7 @@ void fused_verify_kernel(const FusedParams P)
             }
         }
         double log2w = 0.0;
-        if (need_w) log2w = unpack_ratio(wait_word(lw_word, wt, true, P.spin_limit, gave_up));
+        if (need_w) log2w = unpack_ratio(wait_lw(lw_word, wt, par, true, P.spin_limit, gave_up));
         if (leader) {
             // w_{i+1} for the workgroups of the next position
             double next = log2w + lr;
@@ -858,7 +892,7 @@ void fused_verify_kernel(const FusedParams P)
             }
             if (lane == 0) {
                 if (finisher) own_values[4] = unpack_ratio(pack_ratio(next));
-                else st_u64(P.lw + drow, pack_ratio(next));
+                else st_u64(P.lw + drow, pack_lw(next, par));
             }
         }
         if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
@@ -914,7 +948,7 @@ void fused_verify_kernel(const FusedParams P)
         SV_STAMP(5);
         __builtin_amdgcn_wave_barrier();                     // own_values: written by lane 0 above, read by another lane below
         double lw_own;
-        const int tau = finalize_tests(P, U.b, gb, own_values, y, lw_own, last_first, gave_up);
+        const int tau = finalize_tests(P, U.b, gb, own_values, par, y, lw_own, last_first, gave_up);
         if (y < 0) {
             // tau is the last row pair (its residual: this wave has the row's constants) or every token was
             // accepted (Y comes from the last target row itself)
@@ -931,11 +965,12 @@ void fused_verify_kernel(const FusedParams P)
     if (finisher) {
         if (lane == 0) P.next_token[U.b] = y;
         SV_STAMP(12);
-        finalize_cleanup(P, U.b, gb, last_first, gave_up);
+        finalize_cleanup(P, U.b, gb, last_first, par, gave_up);
         SV_STAMP(6);
     }
     if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
 #undef SV_STAMP
+#undef par
 }
 
 // Clears the control words of a workspace and marks it initialised.

@@ -35,7 +35,7 @@ struct Layout {
     int nu;                       // wave chunks per row = 4 * workgroups per row
     size_t fused_grid;            // workgroups of the fused kernel
     size_t control_words;         // header and all words that cross waves: in ints, at offset 0, zero between calls
-    size_t off_ratio, off_lw, off_ycand, off_pstat, off_pgrp, off_qgrp, off_spart;
+    size_t off_ratio, off_lw, off_ycand, off_gen, off_pstat, off_pgrp, off_qgrp, off_spart;
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -58,6 +58,7 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.off_ratio = off;  off += rows_d * sizeof(u64);
     L.off_lw = off;     off += rows_d * sizeof(u64);
     L.off_ycand = off; off += align_up(rows_d * sizeof(unsigned), 8);
+    L.off_gen = off;   off += align_up((size_t)B * sizeof(int), 8);
     L.off_pstat = off;  off += rows_t * L.nu * sizeof(u64);
     L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_qgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
@@ -190,6 +191,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
     P.ycand = reinterpret_cast<unsigned *>(ws + L.off_ycand);
     P.lw = reinterpret_cast<u64 *>(ws + L.off_lw);
+    P.gen = reinterpret_cast<int *>(ws + L.off_gen);
     P.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
     P.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
     P.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
