@@ -301,6 +301,36 @@ def test_ragged_draft_lengths(algo, B, gamma, V, dtype):
     assert n_safe >= 0.8 * B
 
 
+@pytest.mark.parametrize("algo", ["block", "token"])
+def test_one_workspace_through_calls_with_changing_draft_lengths(algo):
+    """The same workspace in a row of calls whose draft lengths change from call to call (long, short, long, one,
+    long) and whose inputs change too: words that an earlier call left behind at positions a later call uses again
+    (or no longer uses) must never be taken for the later call's.  Every call is compared with the oracle."""
+    B, gamma, V = 20, 8, 12000
+    cfg = _custom(B, gamma, V, "bf16", sigma_t=2.5, sigma_d=1.0, T=0.8)
+    ws = sv.alloc_workspace(B, gamma, V, DEV)
+    rng = np.random.default_rng(77)
+    patterns = [np.full(B, gamma), np.full(B, 3), rng.integers(1, gamma + 1, size=B), np.full(B, 1),
+                np.full(B, gamma), rng.integers(1, gamma + 1, size=B), np.full(B, gamma)]
+    for call, lens in enumerate(patterns):
+        lens = lens.astype(np.int32)
+        inp = workloads.generate(cfg, seed=900 + call, device=DEV)
+        tau, y = sv.spec_verify_ex(algo, inp["target_logits"], inp["draft_logits"], inp["draft_tokens"], inp["uniforms"],
+                                   cfg.temperature, draft_lens=torch.as_tensor(lens, device=DEV), workspace=ws)
+        torch.cuda.synchronize()
+        assert sv.spec_verify_workspace_check(ws, B, gamma, V) == 0
+        tau, y = tau.cpu().numpy(), y.cpu().numpy()
+        host = workloads.to_numpy(inp)
+        for g in np.unique(lens):
+            sel = np.nonzero(lens == g)[0]
+            ref = oracle.verify(parity.ALGOS[algo][0], host["target_logits"][sel, :g + 1], host["draft_logits"][sel, :g],
+                                host["draft_tokens"][sel, :g], host["uniforms"][sel, :g + 1], cfg.temperature, dtype=oracle.BF16)
+            safe = ref["margins"].min(axis=1) >= parity.MARGIN
+            assert np.array_equal(tau[sel][safe], ref["accept_len"][safe]), (call, g)
+            same_tau = safe & (tau[sel] == ref["accept_len"])
+            assert np.array_equal(y[sel][same_tau], ref["next_token"][same_tau]), (call, g)
+
+
 def test_ragged_with_full_lengths_equals_the_plain_call():
     cfg = _custom(12, 6, 10000, "bf16")
     inp = workloads.generate(cfg, seed=41, device=DEV)
