@@ -768,9 +768,10 @@ void fused_verify_kernel(const FusedParams P)
     int tok = 0;                                             // the drafted token X_{i+1}, for the leader
     if (wave == 0 && !U.last_row) {
         tok = P.tokens[drow];
-        wt = ld_u64(lw_word); gen_count = P.gen[U.b];          // (the count does not change while the call runs: an ordinary load)
+        gen_count = P.gen[U.b];                                       // (does not change while the call runs: an ordinary load)
         eta_i = P.uniforms[(size_t)U.b * (gamma + 1) + (U.i > 0 ? U.i - 1 : 0)];
         eta_next = P.uniforms[(size_t)U.b * (gamma + 1) + U.i];      // the uniform of test i + 1, which the leader judges for Alg. 1
+        wt = ld_u64(lw_word);
     }
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
