@@ -66,8 +66,11 @@ size_t spec_verify_workspace_bytes(int32_t B, int32_t gamma, int32_t V);
 /* Prepares a workspace for calls of exactly the shape (B, gamma, V): enqueues one small
  * kernel on `stream` that clears the control words the verification kernel synchronises
  * its workgroups with.  Required once after allocation (and again before using the same
- * memory for another shape); every verification call leaves the control words clear for
- * the next one.  A verification call on a workspace that was not initialised for its shape
+ * memory for another shape); every verification call leaves the control words ready for
+ * the next one (the workspace's contents between calls are the library's business: do not
+ * clear or copy parts of it).  Calls that share a workspace must not overlap; calls on
+ * different streams need workspaces of their own.
+ * A verification call on a workspace that was not initialised for its shape
  * touches nothing else and writes -1 to every accept_len and next_token.                  */
 sv_status_t spec_verify_workspace_init(void *workspace, size_t workspace_bytes,
                                        int32_t B, int32_t gamma, int32_t V, void *stream);
