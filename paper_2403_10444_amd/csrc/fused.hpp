@@ -249,14 +249,20 @@ __device__ __forceinline__ float row_max_shift(const u64 *words, int n, int limi
 // its second sweep nor its partial sums are needed.  Decided on log2 w_i as published and the uniform as stored,
 // with a margin far above the rounding of h_i; the units of a row and the wave that finishes the sequence evaluate
 // this same function on the same values, so they always agree on which partial sums exist.
-__device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i)
+__device__ __forceinline__ bool can_become_tau(const FusedParams &P, int i, double log2w_i, float eta_i)
 {
-    if (i == 0 || !P.prune || P.debug_out) return true;   // tau = 0 draws from row 0; the debug block reports every S_i
+    if (i == 0) return true;                               // tau = 0: nothing accepted
     // token verification (Alg. 1) stops at the first failure: the word that carries log2 w_i for the other two
     // algorithms carries 0 while every test up to position i has passed and kLog2RatioFloor afterwards; only a
     // position that all earlier tests let through can become tau
     if (P.algo == kToken) return log2w_i > 0.5 * kLog2RatioFloor;
     return (double)__builtin_amdgcn_logf(eta_i) < log2w_i + 1.0e-3;
+}
+// Whether position i's residual mass is formed: where the position can become tau, and everywhere when the caller
+// wants every S_i reported or the call is too small for leaving any out to pay.
+__device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i)
+{
+    return !P.prune || P.debug_out || can_become_tau(P, i, log2w_i, eta_i);
 }
 
 struct Unit {
@@ -619,6 +625,8 @@ __device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int g
     // always has it.  The rule is evaluated on log2 w as published (before the cap that greedy applies above)
     const double lw_rule = __shfl_down(my_lw_raw, 1, kWave);
     const u64 have = __ballot(j < gamma && residual_needed(P, j, j < gamma ? lw_rule : 0.0, eta_j));
+    // the positions that can become tau: their leaders draw the token that would follow (bit l: position l + 1)
+    const u64 may = __ballot(j < gamma && can_become_tau(P, j, j < gamma ? lw_rule : 0.0, eta_j));
 
     // ---- S_j = sum of row j's partial sums, into lane j
     float my_S = 0.f;
@@ -663,7 +671,7 @@ __device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int g
         // is the same number: it equals S - sum_x (w p - q) = S + 1 - w because both rows sum to one (w unclipped;
         // at w >= 1 the ratio is >= 1 and every eta in [0, 1) passes)
         else h = lw_j >= 0.0 ? 1.0 : S / (S + one_minus_w);
-        pass = (double)eta_j < h && (j == gamma || ((have >> (j - 1)) & 1));
+        pass = (double)eta_j < h && (j == gamma || ((have & may) >> (j - 1)) & 1);
         if (P.debug_out) {
             float *d = P.debug_out + (base + j) * 3;
             d[0] = (float)w_j; d[1] = (float)S; d[2] = (float)h;
@@ -682,7 +690,7 @@ __device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int g
 
     // ---- the tokens that the leaders of the row pairs before the last one have drawn: all of them are waited
     // for (not only tau's), because their leaders read the partial sums that are zeroed when the sequence is done
-    const bool drawn = lane <= gamma - 2 && (lane == 0 || ((have >> (lane - 1)) & 1));
+    const bool drawn = lane <= gamma - 2 && (lane == 0 || ((may >> (lane - 1)) & 1));
     const unsigned cand = wait_word32(P.ycand + drow_l, cand_first, drawn, P.spin_limit, gave_up);
     y_out = tau <= gamma - 2 ? __builtin_amdgcn_readlane((int)cand, tau) - 2 : -1;
     lw_own = read_lane_double(my_lw, gamma - 1);
@@ -828,6 +836,7 @@ void fused_verify_kernel(const FusedParams P)
     // last one finishes the sequence) stays; everybody else is done and frees its registers
     if (!needed && !leader) return;
 
+    bool candidate = true;           // whether this position can become tau: then its leader draws the token that would follow
     if (wave == 0 && (needed || leader)) {
         float Mp, Mq;
         double Lp, Lq;
@@ -881,6 +890,7 @@ void fused_verify_kernel(const FusedParams P)
         }
         double log2w = 0.0;
         if (need_w) log2w = unpack_ratio(wait_lw(lw_word, wt, par, true, P.spin_limit, gave_up));
+        candidate = can_become_tau(P, U.i, log2w, eta_i);       // (on the word as published, like the finishing wave)
         if (leader) {
             // w_{i+1} for the workgroups of the next position
             double next = log2w + lr;
@@ -937,7 +947,7 @@ void fused_verify_kernel(const FusedParams P)
     SV_STAMP(4);
     // the row's leader draws the token that follows if this position becomes tau, while the later positions are
     // still streaming: whoever finishes the sequence then only picks it up
-    if (leader && !finisher) { draw_row = U.i; draw_ap = Lp - log2w; draw_aq = Lq; }
+    if (leader && !finisher && candidate) { draw_row = U.i; draw_ap = Lp - log2w; draw_aq = Lq; }
 
     }
     if (!leader) return;
