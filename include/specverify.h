@@ -95,13 +95,17 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
  * default).                                                                               */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);
 
-/* Tuning hook, process-wide: when `device_buffer` is not NULL the fused kernel stores up to
- * sixteen 64-bit timestamps (100 MHz ticks) per workgroup into it, [workgroups, 16], taken
- * by the workgroup's first wave: 0 start, 1 partial normalisers announced, 2 the row's
- * normalisers known, 3 w_i known, 4 second sweep done; for the workgroup that finishes a
- * sequence also 5 begin, 7..12 its phases, 6 done.  The buffer must hold 128 bytes per
- * workgroup, B * (gamma + 1) * ceil(V / 8192) workgroups, and be zeroed by the caller.    */
+#ifdef SPECVERIFY_PROFILE_BUILD
+/* Tuning builds of the library only (compiled with -DSV_PROFILE; the product library exports no such symbol and
+ * its kernels hold no such stores).  Process-wide: when `device_buffer` is not NULL the fused kernel stores up to
+ * sixteen 64-bit timestamps (100 MHz ticks) per workgroup into it, taken by the workgroup's first wave: 0 start,
+ * 1 partial normalisers announced, 2 the row's normalisers and w_i known, 3 second sweep begins, 4 second sweep
+ * done; for the workgroup that finishes a sequence also 5 begin, 7..12 its phases, 6 done.  Record r of the buffer
+ * belongs to workgroup x of row slot i (gamma: the last target row) of sequence b, r = (b * (gamma + 1) + i) *
+ * ceil(V / 8192) + x: the buffer holds B * (gamma + 1) * ceil(V / 8192) records of 128 bytes and is zeroed by the
+ * caller.                                                                                  */
 void spec_verify_debug_profile(void *device_buffer);
+#endif
 
 /*
  * The drafting step of the outer loop of speculative decoding (Alg. 3: "sample X_1 .. X_gamma from

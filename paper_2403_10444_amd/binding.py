@@ -12,7 +12,9 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libspecverify.so")
+# the product library; SPECVERIFY_LIBRARY names another build of it in this folder (the tuning build
+# libspecverify_profile.so, which adds spec_verify_debug_profile)
+LIB_PATH = os.path.join(_HERE, os.environ.get("SPECVERIFY_LIBRARY", "libspecverify.so"))
 
 SV_OK = 0
 SV_ERR_INVALID_ARG = 1
@@ -28,7 +30,6 @@ EXPORTED = (
     "spec_verify_workspace_init",
     "spec_verify_workspace_check",
     "spec_verify_debug_config",
-    "spec_verify_debug_profile",
     "spec_verify_debug_copy",
     "spec_sample_tokens",
     "spec_verify_block",
@@ -83,8 +84,9 @@ def load() -> ctypes.CDLL:
                                                     ctypes.c_int32, ctypes.c_void_p]
         lib.spec_verify_debug_config.restype = None
         lib.spec_verify_debug_config.argtypes = [ctypes.c_int32, ctypes.c_int32]
-        lib.spec_verify_debug_profile.restype = None
-        lib.spec_verify_debug_profile.argtypes = [ctypes.c_void_p]
+        if hasattr(lib, "spec_verify_debug_profile"):          # tuning builds only
+            lib.spec_verify_debug_profile.restype = None
+            lib.spec_verify_debug_profile.argtypes = [ctypes.c_void_p]
         lib.spec_verify_debug_copy.restype = ctypes.c_int
         lib.spec_verify_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         lib.spec_sample_tokens.restype = ctypes.c_int
@@ -125,9 +127,13 @@ def spec_verify_debug_config(path: int = 0, spin_limit: int = -1) -> None:
 
 
 def spec_verify_debug_profile(buffer) -> None:
-    """Per-workgroup timestamps of the fused kernel go to `buffer` (a zeroed int64 device tensor) until
-    called again with None."""
-    load().spec_verify_debug_profile(buffer.data_ptr() if buffer is not None else None)
+    """Tuning builds only (see build.py): per-workgroup timestamps of the fused kernel go to `buffer` (a zeroed
+    int64 device tensor [B * (gamma + 1) * workgroups per row, 16]) until called again with None."""
+    lib = load()
+    if not hasattr(lib, "spec_verify_debug_profile"):
+        raise RuntimeError("this build of the library has no profiling hook; build with build.py --profile and "
+                           "set SPECVERIFY_LIBRARY=libspecverify_profile.so")
+    lib.spec_verify_debug_profile(buffer.data_ptr() if buffer is not None else None)
 
 
 def spec_verify_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -23,16 +23,22 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
+PROFILE_LIB = os.path.join(HERE, "libspecverify_profile.so")
+
+
+def build(verbose: bool = False, profile: bool = False) -> str:
+    """Builds the library.  `profile`: a second library for tuning, libspecverify_profile.so, whose fused kernel
+    also stores per-workgroup timestamps (-DSV_PROFILE adds the entry point spec_verify_debug_profile and the
+    stores); the product library holds neither."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB, SRC]
+    out = PROFILE_LIB if profile else LIB
+    cmd = [hipcc, *HIPCC_FLAGS, *(["-DSV_PROFILE"] if profile else []), "-o", out, SRC]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    build(verbose=True)
-    print(LIB)
+    print(build(verbose=True, profile="--profile" in sys.argv[1:]))
     sys.exit(0)

@@ -66,11 +66,13 @@ __device__ __forceinline__ float bf16_lo(uint32_t word) { return __uint_as_float
 __device__ __forceinline__ float bf16_hi(uint32_t word) { return __uint_as_float(word & 0xffff0000u); }
 
 template <typename T>
-__device__ __forceinline__ double logit_as_double(const T *p)
+__device__ __forceinline__ float logit_as_float(const T *p)
 {
-    if constexpr (ElemTraits<T>::kVec == 4) return (double)*reinterpret_cast<const float *>(p);
-    else return (double)__uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(p)[0] << 16);
+    if constexpr (ElemTraits<T>::kVec == 4) return *reinterpret_cast<const float *>(p);
+    else return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(p)[0] << 16);
 }
+template <typename T>
+__device__ __forceinline__ double logit_as_double(const T *p) { return (double)logit_as_float(p); }
 
 // kVec consecutive logits starting at element `idx` of a row of V logits, as floats.
 // Elements at or beyond V come back as -inf (weight zero everywhere downstream).  The aligned

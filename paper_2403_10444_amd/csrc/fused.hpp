@@ -1,4 +1,4 @@
-// Fused path: ONE launch, every logit read from HBM once.
+// Fused path: ONE launch, every logit read from HBM at most once.
 //
 // The method needs two sweeps over each (target row i, draft row i) pair: the residual mass
 // S_i = sum_x max(w_i p_i(x) - q_i(x), 0) of Alg. 2 depends on the rows' normalisers and on
@@ -14,34 +14,42 @@
 //      floats per lane in registers; its partial normalisers (shift, sum) meet those of the
 //      workgroup's other waves in LDS,
 //   3. sleeps at a barrier while the workgroup's first wave publishes the workgroup's two words and
-//      looks at log2 w_i, which the previous position's leader published (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
-//      The acceptance probability of Alg. 2 / 4 never exceeds w_i, so where the position's uniform is not below
-//      w_i its residual mass cannot matter (residual_needed) and the workgroup is done.  Otherwise the first wave
-//      waits for the words of the other workgroups of the row, which give L_p and L_q.  The first wave of the
-//      row's last workgroup is the row's leader and always stays: it publishes the row's ratio and log2 w_{i+1},
-//   4. forms its share of S_i from the registers and publishes it; the row's leader then draws the token that
-//      follows if this position becomes tau (draw_from_row) and publishes it.
+//      forms w_i from the ratios log2 r_1 .. log2 r_i that the leaders of the earlier positions have
+//      published (Alg. 2: w_i = min(w_{i-1} r_i, 1), evaluated as a scan over the ratios: no position waits
+//      for a chain of earlier ones, only for their rows).  The acceptance probability of Alg. 2 / 4 never
+//      exceeds w_i, so where the position's uniform is not below w_i its residual mass cannot matter
+//      (residual_needed) and the workgroup is done.  Otherwise the first wave waits for the words of the other
+//      workgroups of the row, which give L_p and L_q.  The first wave of the row's last workgroup is the
+//      row's leader and always stays: it publishes the row's ratio log2 r_{i+1},
+//   4. forms its share of S_i from the registers and publishes it; the row's leader then sums the row's
+//      shares, draws the token that follows if this position becomes tau (draw_from_row) and publishes
+//      both in one word.
 // Workgroups start position-major inside groups of sequences (all row pairs of position 0, then
 // position 1, ..., then the last target rows), so what an earlier position publishes is there
 // before a later one asks for it, and a workgroup only ever waits for the workgroups of
 // its own row, which start next to it.  The leader of a sequence's last row pair finishes the
-// sequence: it collects the ratios and the partial sums, runs the accept tests (finalize_tests), picks up the
-// token drawn for position tau (or draws it, if tau is its own position or every token was accepted) and
-// zeroes the sequence's words (finalize_cleanup).
+// sequence: it reads one word per earlier position (S_i and the token drawn there), runs the accept
+// tests (finish_sequence) and picks up the token drawn for position tau (or draws it, if tau is its own
+// position or every token was accepted).  The last target row is needed only when every token is accepted
+// (Y ~ p_gamma): its workgroups wait for the ratios, and where eta_gamma >= w_gamma they load nothing.
 //
-// Everything that crosses workgroups is a self-announcing word: it is zero between calls and
-// non-zero once written (a packed (shift, sum) pair always has a non-zero sum or a -inf shift;
-// ratio words and partial sums get their lowest mantissa bit set).  Words are written and read
-// with agent-scope atomic accesses, which go through to device memory instead of living in one
-// XCD's L2; no agent-scope fence is needed (on this part such a fence writes back /
-// invalidates a whole L2 and cost more than the rest of the kernel).
+// Everything that crosses workgroups is a self-announcing word: zero until written, non-zero once written
+// (a packed (shift, sum) pair always has a non-zero sum or a -inf shift; ratio words and partial sums
+// get their lowest mantissa bit set).  Words are written and read with agent-scope atomic accesses, which
+// go through to device memory instead of living in one XCD's L2; no agent-scope fence is needed (on this
+// part such a fence writes back / invalidates a whole L2 and cost more than the rest of the kernel).
+// The words exist twice.  A sequence's calls use the two copies alternately (the parity of gen[b], which the
+// wave that finishes the sequence flips as its last act), and every row's leader clears, in the copy that the
+// call does NOT use, the words of its row - so nobody ever clears a word that somebody may still read, and
+// nothing is cleared on the path that ends the kernel.
 //
 // Progress: the hardware starts workgroups in index order (round-robin over the XCDs, in order
 // within each).  A unit waits only for units of its own row (at most kMaxUnitsPerRow / 4
 // workgroups away; the host refuses rows that do not fit four times into the resident set)
 // and of earlier positions of its sequence (earlier workgroups), and publishing never waits:
-// the grid always drains.  Every wait is also bounded by a spin limit; running into it sets
-// the workspace's error word and goes on instead of hanging.
+// the grid always drains.  Every wait is also bounded by a spin limit.  A wave that runs into it sets the
+// workspace's error word and from then on publishes only the all-ones word, which every reader passes on;
+// the wave that finishes the sequence then writes -1 for tau and Y.  A kernel always exits.
 #pragma once
 
 #include "common.hpp"
@@ -49,6 +57,9 @@
 namespace sv {
 
 constexpr int kWave = 64;
+#ifndef SV_WAVES_SMALL
+#define SV_WAVES_SMALL 5      // waves per SIMD of the bf16 kernel with the small units
+#endif
 // LANE, a template parameter of the kernel: logits of one row that a lane holds of a unit, 32 or 64.  A unit is
 // kWave * LANE contiguous logits of one row; fatter units mean fewer workgroups per row to wait for and the
 // fixed registers of a wave spread over more logits (bf16 rows only: 161 VGPRs, 3 waves per SIMD).
@@ -58,12 +69,22 @@ constexpr int kMaxUnitsPerRow = 512;     // wave chunks per row the fused kernel
 // Word 0 of an initialised workspace: a constant mixed with the shape it was initialised for.
 __host__ __device__ inline int workspace_magic(int B, int gamma, int V)
 {
-    return (int)(0x53564b33u ^ ((unsigned)B * 2654435761u + (unsigned)gamma * 40503u + (unsigned)V * 2246822519u));
+    return (int)(0x53564b34u ^ ((unsigned)B * 2654435761u + (unsigned)gamma * 40503u + (unsigned)V * 2246822519u));
 }
 
 enum HeaderWord : int { kHdrMagic = 0, kHdrError = 1, kHdrWords = 64 };
 
 typedef unsigned long long u64;
+
+// The words of one copy (see the head of this file).
+struct Words {
+    u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, two lowest bits: flags (pack_ratio); by the leader of row pair i
+    u64 *rowres;          // [B, gamma]               low half: S_i as float bits; high half: the token drawn from row pair i's
+                          //                          residual + 2, or 1 if none was drawn; by the leader of row pair i
+    u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
+    u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
+    unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
+};
 
 struct FusedParams {
     const void *target, *draft;
@@ -78,24 +99,43 @@ struct FusedParams {
     int algo;
     int nu;               // units (wave chunks) per row = 4 * workgroups per row
     int group_seqs;       // sequences per group of the row order
-    int prune;            // leave out residual masses that cannot matter (residual_needed); off for calls so small that
-                          // all positions run at once, where asking for log2 w first only lengthens the chain
+    int prune;            // leave out what cannot matter (residual_needed, the last target row); off for calls so small
+                          // that all positions run at once, where asking for the ratios first only lengthens the chain
     int spin_limit;
+    int resident;         // workgroups of this kernel that the device holds at once
+    float pace;           // see pace_first_generation: waits of 64 clocks per row of the first resident set (0: none)
     int magic;            // workspace_magic(B, gamma, V)
     int *header;
-    u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, lowest bit set
-    unsigned *ycand;      // [B, gamma]               token drawn from the row pair's residual by its leader, + 2
-    int *gen;             // [B]                      calls this sequence slot has finished (only its parity is used); never zeroed
-    u64 *lw;              // [B, gamma]               log2 w_{i+1} (unclamped for greedy) as double bits with bit 0 set and the
-                          //                          parity of gen in bit 1 (pack_lw); token verification:
-                          //                          0 while every test up to i+1 has passed, kLog2RatioFloor afterwards
-    u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
-    u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
-    unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
+    int *gen;             // [B]  calls this sequence slot has finished: its parity selects the copy of the words in use
+    Words words;          // copy 0; copy 1 lies copy_bytes further on
+    size_t copy_bytes;
     int32_t *accept_len, *next_token;
     float *debug_out;
-    long long *prof;      // NULL, or [workgroups, 16] timestamps (100 MHz ticks) for tuning
+#ifdef SV_PROFILE
+    long long *prof;      // NULL, or [B * (gamma + 1) * workgroups per row, 16] timestamps (100 MHz ticks) for tuning
+#endif
 };
+
+template <typename X> __device__ __forceinline__ X *shifted(X *p, size_t bytes)
+{
+    return reinterpret_cast<X *>(reinterpret_cast<char *>(p) + bytes);
+}
+__device__ __forceinline__ Words words_of(const FusedParams &P, unsigned copy)
+{
+    const size_t off = copy ? P.copy_bytes : 0;
+    Words W;
+    W.ratio = shifted(P.words.ratio, off); W.rowres = shifted(P.words.rowres, off); W.pstat = shifted(P.words.pstat, off);
+    W.pgrp = shifted(P.words.pgrp, off); W.qgrp = shifted(P.words.qgrp, off); W.spart = shifted(P.words.spart, off);
+    return W;
+}
+
+// A load through the scalar data path for values that do not change while the kernel runs and whose address is the
+// same for the whole wave (inputs; the call count of a sequence, which changes only after its last reader).  It
+// does not queue behind the wave's sixteen-byte loads.
+template <typename X> __device__ __forceinline__ X load_uniform(const X *p)
+{
+    return *reinterpret_cast<const __attribute__((address_space(4))) X *>(reinterpret_cast<uintptr_t>(p));
+}
 
 // ---- agent-scope accessors for words that other waves (on any XCD) write or read
 __device__ __forceinline__ int ld_i32(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -111,18 +151,17 @@ __device__ __forceinline__ u64 pack_stat(float shift, float sum)
 }
 __device__ __forceinline__ float stat_shift(u64 v) { return __uint_as_float((unsigned)(v & 0xffffffffull)); }
 __device__ __forceinline__ float stat_sum(u64 v) { return __uint_as_float((unsigned)(v >> 32)); }
-__device__ __forceinline__ u64 pack_ratio(double log2r) { return (u64)__double_as_longlong(log2r) | 1ull; }
-__device__ __forceinline__ double unpack_ratio(u64 v) { return __longlong_as_double((long long)v); }
-// The words that carry log2 w from one position to the next are read by workgroups that publish nothing
-// afterwards (those whose residual mass is not formed), so nobody could tell when it is safe to zero them.
-// They are not zeroed: bit 1 carries the parity of the sequence's call count (`gen`, flipped by the wave that
-// finishes the sequence, after everybody who reads these words has read the count), and a word of the other
-// parity - the previous call's - counts as not written yet.  Positions that a call does not use are zeroed.
-__device__ __forceinline__ u64 pack_lw(double log2w, unsigned par)
-{
-    return ((u64)__double_as_longlong(log2w) & ~3ull) | 1ull | ((u64)par << 1);
-}
-__device__ __forceinline__ bool lw_there(u64 v, unsigned par) { return (v & 1ull) != 0 && ((unsigned)(v >> 1) & 1u) == par; }
+// (bit 0: the word is there; bit 1: test i + 1 of Alg. 1 passes, eta_{i+1} < min(r_{i+1}, 1), as its row's leader judged it)
+__device__ __forceinline__ u64 pack_ratio(double log2r, bool passes) { return ((u64)__double_as_longlong(log2r) & ~3ull) | 1ull | (passes ? 2ull : 0ull); }
+__device__ __forceinline__ double unpack_ratio(u64 v) { return __longlong_as_double((long long)(v & ~3ull)); }
+__device__ __forceinline__ bool ratio_passes(u64 v) { return (v & 2ull) != 0; }
+__device__ __forceinline__ u64 pack_rowres(float S, int token) { return ((u64)(unsigned)(token + 2) << 32) | (u64)__float_as_uint(S); }
+__device__ __forceinline__ float rowres_S(u64 v) { return __uint_as_float((unsigned)(v & 0xffffffffull)); }
+__device__ __forceinline__ int rowres_token(u64 v) { return (int)(unsigned)(v >> 32) - 2; }
+// What a wave publishes instead of a value once one of its waits has run out (or it has read this word itself):
+// all ones, which no value packs to (as a float, a double or a pair of floats it would be a NaN).
+constexpr u64 kPoison64 = ~0ull;
+constexpr unsigned kPoison32 = ~0u;
 
 // The value a given lane holds (lane index uniform over the wave).
 __device__ __forceinline__ u64 read_lane_u64(u64 v, int lane)
@@ -133,7 +172,8 @@ __device__ __forceinline__ u64 read_lane_u64(u64 v, int lane)
 }
 
 // A word that is zero until its producer has written it: lanes with `need` poll *p until it is
-// non-zero (`v` may already hold it).  One loop for the whole wave; gives up after `limit` polls.
+// non-zero (`v` may already hold it).  One loop for the whole wave; gives up after `limit` polls, and counts a
+// word of all ones (published by a wave that gave up) as having given up too.
 __device__ __forceinline__ u64 wait_word(const u64 *p, u64 v, bool need, int limit, bool &gave_up)
 {
     int spins = 0;
@@ -142,22 +182,12 @@ __device__ __forceinline__ u64 wait_word(const u64 *p, u64 v, bool need, int lim
         __builtin_amdgcn_s_sleep(1);
         if (need && v == 0) v = ld_u64(p);
     }
+    if (__any(need && v == kPoison64)) gave_up = true;
     return v;
 }
 __device__ __forceinline__ u64 wait_word(const u64 *p, int limit, bool &gave_up)
 {
     return wait_word(p, ld_u64(p), true, limit, gave_up);
-}
-
-__device__ __forceinline__ u64 wait_lw(const u64 *p, u64 v, unsigned par, bool need, int limit, bool &gave_up)
-{
-    int spins = 0;
-    while (__any(need && !lw_there(v, par))) {
-        if (++spins > limit) { gave_up = true; break; }
-        __builtin_amdgcn_s_sleep(1);
-        if (need && !lw_there(v, par)) v = ld_u64(p);
-    }
-    return v;
 }
 
 __device__ __forceinline__ unsigned wait_word32(const unsigned *p, unsigned v, bool need, int limit, bool &gave_up)
@@ -168,6 +198,7 @@ __device__ __forceinline__ unsigned wait_word32(const unsigned *p, unsigned v, b
         __builtin_amdgcn_s_sleep(1);
         if (need && v == 0) v = ld_u32(p);
     }
+    if (__any(need && v == kPoison32)) gave_up = true;
     return v;
 }
 __device__ __forceinline__ unsigned wait_word32(const unsigned *p, int limit, bool &gave_up)
@@ -175,22 +206,63 @@ __device__ __forceinline__ unsigned wait_word32(const unsigned *p, int limit, bo
     return wait_word32(p, ld_u32(p), true, limit, gave_up);
 }
 
-// log2 of a positive float with an absolute error of a few 1e-8: exponent + log2(mantissa in [1,2)).
-__device__ __forceinline__ double log2_precise(float z)
+// exp2 of a double of moderate size to a relative error below 1e-12: the integer part goes into the exponent,
+// the fraction f in [-0.5, 0.5] through the series of exp(f ln 2) (|f ln 2| <= 0.347: ten terms).
+__device__ __forceinline__ double exp2_precise(double x)
 {
-    int e;
-    const float m = frexpf(z, &e);            // z = m * 2^e, m in [0.5, 1)
-    return (double)(e - 1) + (double)__builtin_amdgcn_logf(m * 2.0f);
+    const double n = rint(x);
+    const double t = (x - n) * 0.69314718055994530942;
+    double s = 1.0 / 3628800.0;
+    s = s * t + 1.0 / 362880.0;
+    s = s * t + 1.0 / 40320.0;
+    s = s * t + 1.0 / 5040.0;
+    s = s * t + 1.0 / 720.0;
+    s = s * t + 1.0 / 120.0;
+    s = s * t + 1.0 / 24.0;
+    s = s * t + 1.0 / 6.0;
+    s = s * t + 0.5;
+    s = s * t + 1.0;
+    s = s * t + 1.0;
+    return ldexp(s, (int)n);
 }
 
-// Running combination of (shift, sum) pairs: sum of exp2 relative to the largest shift so far.
+// log2 of a positive double to an absolute error below 1e-12: the hardware's float log2 as a first guess g (off by
+// about 1e-7), then log2 z = g + log2(z 2^-g) with z 2^-g - 1 of that size, where two terms of the series are enough.
+__device__ __forceinline__ double log2_precise(double z)
+{
+    int e;
+    const double m = frexp(z, &e);            // z = m * 2^e, m in [0.5, 1)
+    const double g = (double)__builtin_amdgcn_logf((float)m);
+    const double d = m * exp2_precise(-g) - 1.0;
+    return (double)e + g + (d - 0.5 * d * d) * 1.4426950408889634074;
+}
+
+// A unit's exponentials are taken relative to an INTEGER shift, the smallest one that keeps them at or below 1:
+// then sums of different units combine through exact powers of two.  The words carry the unit's largest scaled
+// logit itself (the row's maximum is wanted too); this is the shift that belongs to it.
+__device__ __forceinline__ float shift_of(float largest) { return largest > -INFINITY ? ceilf(largest) : 0.f; }
+
+// Running combination of (largest scaled logit, sum) words: the sum of exp2 relative to the integer shift of the
+// largest so far, in double (the factors between units are exact).
 struct StatAcc {
-    float m = -INFINITY, z = 0.f;
+    float m = -INFINITY;      // largest scaled logit so far
+    double z = 0.0;
     __device__ __forceinline__ void add(u64 word)
     {
-        const float sh = stat_shift(word), s = stat_sum(word);
-        if (sh > m) { z = z * fast_exp2(m - sh) + s; m = sh; }      // exp2(-inf) = 0 covers the first word
-        else if (sh > -INFINITY) z += s * fast_exp2(sh - m);
+        const float mw = stat_shift(word);
+        if (!(mw > -INFINITY)) return;                              // a unit without a finite logit
+        const double s = (double)stat_sum(word);
+        if (mw > m) {
+            z = (m > -INFINITY ? ldexp(z, (int)(shift_of(m) - shift_of(mw))) : 0.0) + s;
+            m = mw;
+        } else {
+            z += ldexp(s, (int)(shift_of(mw) - shift_of(m)));
+        }
+    }
+    // the sum relative to the integer shift of another (larger or equal) maximum
+    __device__ __forceinline__ double relative_to(float M) const
+    {
+        return m > -INFINITY ? ldexp(z, (int)(shift_of(m) - shift_of(M))) : 0.0;
     }
 };
 
@@ -209,6 +281,85 @@ __device__ __forceinline__ void load_row_words(const u64 *words, int n, RowWords
     }
 }
 
+// Largest scaled logit among a row's words, once all of them are there.
+__device__ __forceinline__ float row_max_shift(const u64 *words, int n, int limit, bool &gave_up)
+{
+    const int lane = threadIdx.x & 63;
+    float m = -INFINITY;
+    for (int e0 = 0; e0 < n; e0 += kWave) {
+        const int e = e0 + lane;
+        const u64 w = wait_word(words + (e < n ? e : n - 1), 0, e < n, limit, gave_up);
+        if (e < n) m = fmaxf(m, stat_shift(w));
+    }
+    return wave_max(m);
+}
+
+// ------------------------------------------------------------------ scans over the 64 lanes
+// Inclusive scans through DPP: four shifts inside each row of 16 lanes (lanes without a source get 0), then the
+// two row broadcasts.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_shift(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, true);
+}
+__device__ __forceinline__ float wave_scan(float v)
+{
+    v += __int_as_float(dpp_shift<0x111>(__float_as_int(v)));          // row_shr:1
+    v += __int_as_float(dpp_shift<0x112>(__float_as_int(v)));          // row_shr:2
+    v += __int_as_float(dpp_shift<0x114>(__float_as_int(v)));          // row_shr:4
+    v += __int_as_float(dpp_shift<0x118>(__float_as_int(v)));          // row_shr:8
+    v += __int_as_float(dpp_shift<0x142, 0xa>(__float_as_int(v)));     // row_bcast15 into rows 1 and 3
+    v += __int_as_float(dpp_shift<0x143, 0xc>(__float_as_int(v)));     // row_bcast31 into rows 2 and 3
+    return v;
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ double dpp_shift_double(double v)
+{
+    const long long bits = __double_as_longlong(v);
+    const unsigned lo = (unsigned)dpp_shift<CTRL, ROW_MASK>((int)(unsigned)(bits & 0xffffffffll));
+    const unsigned hi = (unsigned)dpp_shift<CTRL, ROW_MASK>((int)(unsigned)((unsigned long long)bits >> 32));
+    return __longlong_as_double((long long)(((u64)hi << 32) | lo));
+}
+__device__ __forceinline__ double wave_scan(double v)
+{
+    v += dpp_shift_double<0x111>(v);
+    v += dpp_shift_double<0x112>(v);
+    v += dpp_shift_double<0x114>(v);
+    v += dpp_shift_double<0x118>(v);
+    v += dpp_shift_double<0x142, 0xa>(v);
+    v += dpp_shift_double<0x143, 0xc>(v);
+    return v;
+}
+// Lane j gets max(0, v_0, ..., v_j): a lane without a source contributes 0, which the result includes anyway.
+__device__ __forceinline__ double wave_scan_max0(double v)
+{
+    v = fmax(v, 0.0);
+    v = fmax(v, dpp_shift_double<0x111>(v));
+    v = fmax(v, dpp_shift_double<0x112>(v));
+    v = fmax(v, dpp_shift_double<0x114>(v));
+    v = fmax(v, dpp_shift_double<0x118>(v));
+    v = fmax(v, dpp_shift_double<0x142, 0xa>(v));
+    v = fmax(v, dpp_shift_double<0x143, 0xc>(v));
+    return v;
+}
+__device__ __forceinline__ double read_lane_double(double v, int lane)
+{
+    return __longlong_as_double((long long)read_lane_u64((u64)__double_as_longlong(v), lane));
+}
+// Sums over each half of the wave (lanes 0..31 and 32..63) at once, in double, through DPP in a fixed order: the
+// pairs and quads of lanes, the two mirrors inside a row of 16, then the row broadcast that leaves the halves' sums
+// in lanes 31 and 63.
+__device__ __forceinline__ void halves_sum_f64(double v, double &first, double &second)
+{
+    v += dpp_shift_double<0xB1>(v);            // quad_perm:[1,0,3,2]
+    v += dpp_shift_double<0x4E>(v);            // quad_perm:[2,3,0,1]
+    v += dpp_shift_double<0x141>(v);           // row_half_mirror
+    v += dpp_shift_double<0x140>(v);           // row_mirror
+    v += dpp_shift_double<0x142, 0xa>(v);      // row_bcast15 into rows 1 and 3
+    first = read_lane_double(v, 31);
+    second = read_lane_double(v, 63);
+}
+
 // Log2-normaliser of a row from the words of its n <= 64 NW units: every lane combines its entries
 // (in that fixed order), then the wave combines.  Returns L; M_out is the largest shift.
 template <int NW>
@@ -225,44 +376,56 @@ __device__ __forceinline__ double row_normaliser(const u64 *words, int n, int li
         }
     }
     const float M = wave_max(acc.m);
-    const float z = wave_sum(acc.m > -INFINITY ? acc.z * fast_exp2(acc.m - M) : 0.f);
+    double z0, z1;
+    halves_sum_f64(acc.relative_to(M), z0, z1);
+    const double z = z0 + z1;
     M_out = M;
-    return (double)M + log2_precise(z);
+    return (double)shift_of(M) + log2_precise(z);
 }
 
-// Largest shift among a row's words, once all of them are there.
-__device__ __forceinline__ float row_max_shift(const u64 *words, int n, int limit, bool &gave_up)
+// ------------------------------------------------------------------ the sequence's weights and what can matter
+// What a wave knows of a sequence once it holds the ratio words of positions 1 .. n (lane j: the word of log2 r_{j+1}).
+// Every wave that needs any of it - the first waves of the row pairs' workgroups, of the last target row's workgroups
+// and the wave that finishes the sequence - evaluates these same functions on the same published words, so they
+// always agree on which sums and which draws exist.
+struct SeqState {
+    double lw;            // lane j < n: log2 w_{j+1}.  Alg. 2: w_i = min(w_{i-1} r_i, 1), w_0 = 1; Alg. 4: without the min
+    u64 passed;           // Alg. 1: bit j set iff test j + 1 passes (the same in every lane)
+};
+__device__ __forceinline__ SeqState seq_state(int algo, u64 ratio_word, int n)
 {
     const int lane = threadIdx.x & 63;
-    float m = -INFINITY;
-    for (int e0 = 0; e0 < n; e0 += kWave) {
-        const int e = e0 + lane;
-        const u64 w = wait_word(words + (e < n ? e : n - 1), 0, e < n, limit, gave_up);
-        if (e < n) m = fmaxf(m, stat_shift(w));
+    SeqState st;
+    st.lw = 0.0;
+    st.passed = 0;
+    if (algo == kToken) {
+        st.passed = __ballot(lane < n && ratio_passes(ratio_word));
+    } else {
+        // log2 w_i = P_i - max(0, P_1, ..., P_i) with P_i = log2 r_1 + ... + log2 r_i: the recursion's min written out
+        // (each time the product would exceed 1 it restarts from 1)
+        const double P = wave_scan(lane < n ? unpack_ratio(ratio_word) : 0.0);
+        st.lw = algo == kBlock ? P - wave_scan_max0(P) : P;
     }
-    return wave_max(m);
+    return st;
 }
 
-// Whether position i's residual mass S_i can matter.  The acceptance probability of block (and greedy block)
-// verification never exceeds w_i: h_i = S_i / (S_i + 1 - w_i) with S_i <= w_i.  So a test with eta_i >= w_i fails
-// whatever S_i is, the position cannot become tau either (tau is a position whose test passed, or 0), and neither
-// its second sweep nor its partial sums are needed.  Decided on log2 w_i as published and the uniform as stored,
-// with a margin far above the rounding of h_i; the units of a row and the wave that finishes the sequence evaluate
-// this same function on the same values, so they always agree on which partial sums exist.
-__device__ __forceinline__ bool can_become_tau(const FusedParams &P, int i, double log2w_i, float eta_i)
+// Whether position i (1 <= i <= the draft length) can become tau, given log2 w_i (seq_state's lane i - 1), the
+// position's uniform and, for Alg. 1, the tests passed.  The acceptance probability of block (and greedy block)
+// verification never exceeds w_i: h_i = S_i / (S_i + 1 - w_i) with S_i <= w_i, and h_gamma = w_gamma.  So a test with
+// eta_i >= w_i fails whatever S_i is, and tau is a position whose test passed, or 0.  Decided with a margin far above
+// the rounding of h_i.  Token verification (Alg. 1) stops at the first failure: only a position that all tests up to
+// its own let through can become tau.  Position 0 (nothing accepted) always can.
+__device__ __forceinline__ bool can_become_tau(int algo, int i, double log2w_i, float eta_i, u64 passed)
 {
-    if (i == 0) return true;                               // tau = 0: nothing accepted
-    // token verification (Alg. 1) stops at the first failure: the word that carries log2 w_i for the other two
-    // algorithms carries 0 while every test up to position i has passed and kLog2RatioFloor afterwards; only a
-    // position that all earlier tests let through can become tau
-    if (P.algo == kToken) return log2w_i > 0.5 * kLog2RatioFloor;
+    if (i == 0) return true;
+    if (algo == kToken) return (~passed & ((i >= 64 ? 0ull : (1ull << i)) - 1ull)) == 0;
     return (double)__builtin_amdgcn_logf(eta_i) < log2w_i + 1.0e-3;
 }
 // Whether position i's residual mass is formed: where the position can become tau, and everywhere when the caller
 // wants every S_i reported or the call is too small for leaving any out to pay.
-__device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i)
+__device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i, u64 passed)
 {
-    return !P.prune || P.debug_out || can_become_tau(P, i, log2w_i, eta_i);
+    return !P.prune || P.debug_out || can_become_tau(P.algo, i, log2w_i, eta_i, passed);
 }
 
 struct Unit {
@@ -271,8 +434,7 @@ struct Unit {
 };
 
 // Workgroup order: groups of `group_seqs` sequences; inside a group the row pairs position-major
-// (position, sequence, chunk), then the last target rows (which have no draft row and wait for
-// nothing: a light last generation while the sequences are being finished).
+// (position, sequence, chunk), then the last target rows.
 // The grid spells this out, (x, y, z) = (chunk / 4, sequence in group, group * (gamma + 1) + slot)
 // with slot i for position i and slot gamma for the last target row; x runs fastest in the start order.
 // Returns false for the padding of a last, smaller group.
@@ -283,7 +445,7 @@ __device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit
     U.b = grp * P.group_seqs + blockIdx.y;
     // which of the row's workgroups takes which chunk rotates from row to row: a row's workgroups go to the
     // XCDs round-robin, and the last chunk (fewest logits, leader's duties) must not always meet the same XCD
-    const int wpr = gridDim.x;
+    const int wpr = P.nu / kWaves;                        // (= gridDim.x)
     x = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % wpr);
     U.c = x * kWaves + wave;
     U.last_row = slot == P.gamma;
@@ -364,8 +526,8 @@ __device__ __forceinline__ void unpack_slice(const T *row, int unit_first, int V
 }
 
 // First sweep over the logits the wave holds of one row: x[j] becomes exp2(x[j] * k - shift) with
-// the wave-uniform shift = k * (largest logit of the unit), or 0 when the whole unit lies beyond
-// the row.  Returns the unit's word: (k * largest logit, sum of the exponentials); (-inf, 0) beyond.
+// the wave-uniform integer shift that belongs to the unit's largest scaled logit (shift_of; 0 when the whole unit
+// lies beyond the row).  Returns the unit's word: (k * largest logit, sum of the exponentials); (-inf, 0) beyond.
 template <int LANE>
 __device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float &shift)
 {
@@ -373,7 +535,7 @@ __device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float 
 #pragma unroll
     for (int j = 1; j < LANE; ++j) m = fmaxf(m, x[j]);
     const float Mw = wave_max(m * k);
-    shift = Mw > -INFINITY ? Mw : 0.f;
+    shift = shift_of(Mw);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};     // four partial sums: shorter chains, smaller rounding error
 #pragma unroll
     for (int j = 0; j < LANE; ++j) {
@@ -384,58 +546,25 @@ __device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float 
     return pack_stat(Mw, sw);
 }
 
-// ------------------------------------------------------------------ whole sequences
-// Inclusive scans over the 64 lanes through DPP: four shifts inside each row of 16 lanes (lanes
-// without a source add 0), then the two row broadcasts.
-template <int CTRL, int ROW_MASK = 0xf>
-__device__ __forceinline__ int dpp_shift(int v)
-{
-    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, true);
-}
-__device__ __forceinline__ float wave_scan(float v)
-{
-    v += __int_as_float(dpp_shift<0x111>(__float_as_int(v)));          // row_shr:1
-    v += __int_as_float(dpp_shift<0x112>(__float_as_int(v)));          // row_shr:2
-    v += __int_as_float(dpp_shift<0x114>(__float_as_int(v)));          // row_shr:4
-    v += __int_as_float(dpp_shift<0x118>(__float_as_int(v)));          // row_shr:8
-    v += __int_as_float(dpp_shift<0x142, 0xa>(__float_as_int(v)));     // row_bcast15 into rows 1 and 3
-    v += __int_as_float(dpp_shift<0x143, 0xc>(__float_as_int(v)));     // row_bcast31 into rows 2 and 3
-    return v;
-}
-template <int CTRL, int ROW_MASK = 0xf>
-__device__ __forceinline__ double dpp_shift_double(double v)
-{
-    const long long bits = __double_as_longlong(v);
-    const unsigned lo = (unsigned)dpp_shift<CTRL, ROW_MASK>((int)(unsigned)(bits & 0xffffffffll));
-    const unsigned hi = (unsigned)dpp_shift<CTRL, ROW_MASK>((int)(unsigned)((unsigned long long)bits >> 32));
-    return __longlong_as_double((long long)(((u64)hi << 32) | lo));
-}
-__device__ __forceinline__ double wave_scan(double v)
-{
-    v += dpp_shift_double<0x111>(v);
-    v += dpp_shift_double<0x112>(v);
-    v += dpp_shift_double<0x114>(v);
-    v += dpp_shift_double<0x118>(v);
-    v += dpp_shift_double<0x142, 0xa>(v);
-    v += dpp_shift_double<0x143, 0xc>(v);
-    return v;
-}
-__device__ __forceinline__ double read_lane_double(double v, int lane)
-{
-    return __longlong_as_double((long long)read_lane_u64((u64)__double_as_longlong(v), lane));
-}
+// Tuning builds (-DSV_PROFILE) store up to sixteen timestamps per workgroup, taken by its first lane, into the
+// workgroup's record `stamps`; the default build has none of it.
+#ifdef SV_PROFILE
+#define SV_STAMP(slot) do { if (stamps && threadIdx.x == 0) stamps[slot] = wall_clock64(); } while (0)
+#else
+#define SV_STAMP(slot) do { } while (0)
+#endif
 
-#define FSTAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
-
-// Inverse-CDF draw of one token from row `row` of sequence b (one wave), in index order, first token whose
-// running sum exceeds u * total.  mode 0: from the residual max(w p - q, 0) of row pair `row`, located by the
-// partial sums per wave chunk that the pair's units publish (polled here until all are there) and then by
-// the weights of that one chunk, formed again from the logits with alpha_p = L_p - log2 w and alpha_q = L_q;
-// a residual without any mass falls back to mode 1.  mode 1: from p_row itself, by the target row's
-// (shift, sum) words.
+// ------------------------------------------------------------------ the draw of a token
+// Row `row` of sequence b (one wave).  First the sum of the weights: mode 0, the residual max(w p - q, 0) of row pair
+// `row`, by the partial sums per wave chunk that the pair's units publish (polled here until all are there); mode 1,
+// p_row itself, by the target row's (shift, sum) words.  `total_out` gets that sum (mode 0: S_row).  Then, if
+// `want_draw`, the inverse-CDF draw in index order, first token whose running sum exceeds u * total: the wave chunk
+// that holds it by a scan over the chunks' sums, then the token by the weights of that one chunk, formed again from
+// the logits with alpha_p = L_p - log2 w and alpha_q = L_q.  A residual without any mass is drawn from p_row
+// instead.  Returns the token, or -1 if none was asked for.
 template <typename T, bool ALIGNED, int LANE>
-__device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int row, int mode, double alpha_p, double alpha_q,
-                                             float u, bool &gave_up)
+__device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &W, int b, int row, int mode, bool want_draw,
+                                             double alpha_p, double alpha_q, float u, double &total_out, bool &gave_up)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = LANE / kVec;
@@ -447,8 +576,8 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int ro
     const T *draft = static_cast<const T *>(P.draft);
     const size_t base = (size_t)b * (G + 1);
     const size_t drow = (size_t)b * G + (mode == 0 ? row : 0);
-    const u64 *st = P.pstat + (base + row) * nu;
-    const unsigned *sp = P.spart + drow * nu;
+    const u64 *st = W.pstat + (base + row) * nu;
+    const unsigned *sp = W.spart + drow * nu;
 
     // ---- first the wave chunk that holds t = u * total ...
     float Mrow = 0.f;
@@ -457,6 +586,7 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int ro
     else Mrow = row_max_shift(st, nu, P.spin_limit, gave_up);
     int slot = -1, last_nonzero = 0;
     double t_in = 0.0;
+    total_out = 0.0;
     for (int attempt = 0; attempt < 2 && slot < 0; ++attempt) {
         double total = 0.0, t = 0.0;
         for (int pass_no = 0; pass_no < 2; ++pass_no) {           // pass 0: total; pass 1: locate t = u * total
@@ -471,7 +601,7 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int ro
                 } else {
                     const u64 v = ld_u64(st + ee);
                     const float sh = stat_shift(v);
-                    if (e < nu && sh > -INFINITY) part = (double)(stat_sum(v) * fast_exp2(sh - Mrow));
+                    if (e < nu && sh > -INFINITY) part = ldexp((double)stat_sum(v), (int)(shift_of(sh) - shift_of(Mrow)));
                 }
                 const double inc = wave_scan(part) + carry;
                 if (pass_no == 1 && slot < 0) {
@@ -486,7 +616,11 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int ro
                 }
                 carry = read_lane_double(inc, kWave - 1);
             }
-            if (pass_no == 0) { total = carry; t = (double)u * total; }
+            if (pass_no == 0) {
+                total = carry; t = (double)u * total;
+                if (attempt == 0) total_out = total;
+                if (!want_draw) return -1;
+            }
         }
         if (slot < 0) {
             if (mode == 0 && !(total > 0.0)) {                         // no residual mass: draw from p_row
@@ -504,26 +638,44 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int ro
     const T *prow = target + (base + row) * P.tstride;
     const T *qrow = draft + drow * P.dstride;
     const int first = slot * kUnitLogits + lane * kVec;
-    float xp[kNV][kVec], xq[kNV][kVec];
+    // (the sixteen-byte path asks for the whole chunk at once and keeps it as loaded until each vector's turn)
+    uint4 rp[ALIGNED ? kNV : 1], rq[ALIGNED ? kNV : 1];
+    if constexpr (ALIGNED) {
 #pragma unroll
-    for (int v = 0; v < kNV; ++v) {
-        load_vec<T, ALIGNED>(prow, V, first + v * kWave * kVec, xp[v]);
-        if (mode == 0) load_vec<T, ALIGNED>(qrow, V, first + v * kWave * kVec, xq[v]);
+        for (int v = 0; v < kNV; ++v) {
+            const int idx = first + v * kWave * kVec;
+            rp[v] = *reinterpret_cast<const uint4 *>(prow + (idx < V ? idx : 0));
+            if (mode == 0) rq[v] = *reinterpret_cast<const uint4 *>(qrow + (idx < V ? idx : 0));
+        }
     }
-    const u64 sv = wait_word(st + slot, P.spin_limit, gave_up);
-    const float shift = stat_shift(sv), scale = fast_exp2(shift - Mrow);
+    float shift = 0.f, scale = 1.f;
+    if (mode != 0) {
+        const u64 sv = wait_word(st + slot, P.spin_limit, gave_up);
+        shift = shift_of(stat_shift(sv)); scale = ldexpf(1.f, (int)(shift - shift_of(Mrow)));
+    }
     float t = mode == 0 ? (float)(t_in / (double)rc.cq) : (float)t_in;
     int y = -1, last_positive = -1;
 #pragma unroll
     for (int v = 0; v < kNV; ++v) {
         const int idx = first + v * kWave * kVec;
-        float wgt[kVec];
+        float wgt[kVec], xpv[kVec], xqv[kVec];
+        if constexpr (ALIGNED) {
+            unpack_vec<T>(rp[v], xpv);
+            if (mode == 0) unpack_vec<T>(rq[v], xqv);
+            if (idx >= V) {
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) { xpv[e] = -INFINITY; xqv[e] = -INFINITY; }
+            }
+        } else {
+            load_vec<T, false>(prow, V, idx, xpv);
+            if (mode == 0) load_vec<T, false>(qrow, V, idx, xqv);
+        }
         if (mode == 0) {
 #pragma unroll
-            for (int e = 0; e < kVec; ++e) wgt[e] = fmaxf(residual_term(xp[v][e], xq[v][e], k, rc), 0.f);
+            for (int e = 0; e < kVec; ++e) wgt[e] = fmaxf(residual_term(xpv[e], xqv[e], k, rc), 0.f);
         } else {
 #pragma unroll
-            for (int e = 0; e < kVec; ++e) wgt[e] = fast_exp2(__builtin_fmaf(xp[v][e], k, -shift)) * scale;
+            for (int e = 0; e < kVec; ++e) wgt[e] = fast_exp2(__builtin_fmaf(xpv[e], k, -shift)) * scale;
         }
         float mine = 0.f;
 #pragma unroll
@@ -562,103 +714,46 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, int b, int ro
     return y;
 }
 
-// Accept tests of one sequence (one wave: the leader of the sequence's last row pair).  Returns tau and writes
-// it; y_out is the token that the leader of row pair tau has drawn from its residual, or -1 when tau is the
-// last row pair or beyond (then the caller draws); lw_own is log2 w of the last row pair.
-// `own` (LDS, written by this same wave): log2 r, L_p, L_q and the word for the next position of the
-// sequence's last row pair - they need no trip through device memory.
-__device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int gamma, const double *own, unsigned par, int &y_out,
-                                              double &lw_own, u64 &last_first, bool &gave_up)
+// ------------------------------------------------------------------ whole sequences
+// Accept tests of one sequence (one wave: the leader of the sequence's last row pair, position gamma - 1, where `gamma`
+// is this sequence's draft length).  `ratio_word`: lane j < gamma holds the word of log2 r_{j+1} (the last one is this
+// wave's own); S_own: the residual mass of the last row pair, if it was formed.  Writes tau (and the debug
+// block); returns tau.  y_out is the token that the leader of row pair tau has drawn from its residual, or -1 when tau
+// is the last row pair or beyond (then the caller draws); lw_own is log2 w of the last row pair.
+__device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words &W, int b, int gamma, u64 ratio_word, float S_own,
+                                               int &y_out, double &lw_own, bool &gave_up, long long *stamps)
 {
-    constexpr int kBatch = 8;                           // rows whose words are fetched together (one round trip)
     const int lane = threadIdx.x & 63;
-    // `gamma` is this sequence's draft length; G, the call's (largest) draft length, is the stride of every array
-    const int G = P.gamma, nu = P.nu;
+    // G, the call's (largest) draft length, is the stride of every array
+    const int G = P.gamma;
     const size_t base = (size_t)b * (G + 1);
-    const int e_lane = lane < nu ? lane : nu - 1;
-
-    // everything the tests need is asked for at once (one round trip): the rows' ratios, log2 w, the uniforms,
-    // the first batch of partial sums and the tokens the rows' leaders have drawn; what is not there yet is
-    // polled where it is used.  Lane j holds what belongs to row pair j (gamma <= 64).
-    const size_t drow_l = (size_t)b * G + (lane < gamma ? lane : gamma - 1);
-    const u64 *lw_word = P.lw + drow_l;
-    const float *eta = P.uniforms + (size_t)b * (G + 1);
-    u64 w0 = ld_u64(P.ratio + drow_l);
-    const u64 lw_first = ld_u64(lw_word);
-    unsigned sw_first[kBatch];
-#pragma unroll
-    for (int jj = 0; jj < kBatch; ++jj) {
-        const int j = jj < gamma ? jj : gamma - 1;
-        sw_first[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
-    }
-    const unsigned cand_first = ld_u32(P.ycand + drow_l);
-    last_first = ld_u64(P.pstat + (base + gamma) * nu + e_lane);    // for the clean-up at the very end
-    w0 = wait_word(P.ratio + drow_l, w0, lane < gamma - 1, P.spin_limit, gave_up);
-    double my_lr = unpack_ratio(w0);                    // log2 r_{lane+1}
-    if (lane == gamma - 1) my_lr = own[0];
-    FSTAMP(7);
-    // log2 w_j for lane j as the rows' leaders published it (Alg. 2: w_j = min(w_{j-1} r_j, 1); Alg. 4
-    // drops the min); lw_last is log2 w_gamma
-    double my_lw = 0.0, my_lw_raw = 0.0, lw_last = 0.0;
-    {
-        double next = unpack_ratio(wait_lw(lw_word, lw_first, par, lane < gamma - 1, P.spin_limit, gave_up));   // log2 w_{lane+1}
-        if (lane == gamma - 1) next = own[4];
-        const double prev = __shfl_up(next, 1, kWave);
-        my_lw_raw = lane ? prev : 0.0;
-        if (P.algo != kToken) {                              // token verification: the words only say where the tests stopped
-            my_lw = my_lw_raw;
-            lw_last = read_lane_double(next, gamma - 1);
-            if (P.algo == kGreedy) { my_lw = fmin(my_lw, 100.0); lw_last = fmin(lw_last, 100.0); }
-        }
-    }
-    FSTAMP(8);
-    // what the accept tests need of w_j is formed now, before the wait for the partial sums: lane l tests
-    // position j = l + 1, whose row values sit in lane j
+    // one word per earlier position: S_j and the token its leader drew.  Asked for before anything else; what is not
+    // there yet is polled once it is known which positions publish one
+    const u64 *res_word = W.rowres + (size_t)b * G + (lane < gamma - 1 ? lane : 0);
+    u64 res = gamma > 1 ? ld_u64(res_word) : 0;
+    const float eta = P.uniforms[base + (lane < gamma ? lane : gamma - 1)];          // lane l: eta_{l+1}
+    SV_STAMP(7);
+    const SeqState st = seq_state(P.algo, ratio_word, gamma);
+    const double lr = unpack_ratio(ratio_word);
+    // lane l tests position j = l + 1
     const int j = lane + 1;
-    const double lw_below = __shfl_down(my_lw, 1, kWave);
-    const double lw_j = j < gamma ? lw_below : lw_last;
+    double lw_j = st.lw;                                 // log2 w_j as the rule sees it (greedy: unclipped and uncapped)
+    const u64 may = __ballot(j < gamma && can_become_tau(P.algo, j, lw_j, eta, st.passed));
+    const u64 have = __ballot(j < gamma && residual_needed(P, j, lw_j, eta, st.passed));
+    if (P.algo == kGreedy) lw_j = fmin(lw_j, 100.0);
+    if (P.algo == kToken) lw_j = 0.0;
     const double w_j = exp2(lw_j);
     const double one_minus_w = -expm1(lw_j * 0.69314718055994530942);
-    const double h_token = exp2(fmin(my_lr, 0.0));      // min(r_j, 1); lane l holds log2 r_{l+1}
-    const float eta_j = eta[j <= gamma ? j - 1 : 0];
-    // the positions whose residual mass exists (see residual_needed): bit l stands for position l + 1; position 0
-    // always has it.  The rule is evaluated on log2 w as published (before the cap that greedy applies above)
-    const double lw_rule = __shfl_down(my_lw_raw, 1, kWave);
-    const u64 have = __ballot(j < gamma && residual_needed(P, j, j < gamma ? lw_rule : 0.0, eta_j));
-    // the positions that can become tau: their leaders draw the token that would follow (bit l: position l + 1)
-    const u64 may = __ballot(j < gamma && can_become_tau(P, j, j < gamma ? lw_rule : 0.0, eta_j));
+    const double h_token = exp2(fmin(lr, 0.0));         // min(r_j, 1), for the debug block
+    SV_STAMP(8);
 
-    // ---- S_j = sum of row j's partial sums, into lane j
-    float my_S = 0.f;
-    for (int j0 = 0; j0 < gamma; j0 += kBatch) {
-        unsigned sw[kBatch];
-#pragma unroll
-        for (int jj = 0; jj < kBatch; ++jj) {
-            const int j = j0 + jj < gamma ? j0 + jj : gamma - 1;
-            if (j0 == 0) {                               // asked for at the start
-                sw[jj] = sw_first[jj];
-            } else {
-                sw[jj] = ld_u32(P.spart + ((size_t)b * G + j) * nu + e_lane);
-            }
-        }
-#pragma unroll
-        for (int jj = 0; jj < kBatch; ++jj) {
-            const int j = j0 + jj;
-            if (j >= gamma) continue;
-            if (j > 0 && !((have >> (j - 1)) & 1)) continue;      // no partial sums were formed for this row: S stays 0
-            const size_t drow = (size_t)b * G + j;
-            float acc = 0.f;
-            const unsigned w = wait_word32(P.spart + drow * nu + e_lane, sw[jj], lane < nu, P.spin_limit, gave_up);
-            if (lane < nu) acc = unpack_partial(w);
-            for (int e = lane + kWave; e < nu; e += kWave) {
-                acc += unpack_partial(wait_word32(P.spart + drow * nu + e, P.spin_limit, gave_up));
-            }
-            acc = wave_sum(acc);
-            if (lane == j) my_S = acc;
-        }
-    }
+    // ---- S_i of position i into lane i: position 0 and every position of `have` publish theirs
+    const bool published = lane < gamma - 1 && (lane == 0 || ((have >> (lane - 1)) & 1));
+    res = wait_word(res_word, res, published, P.spin_limit, gave_up);
+    float my_S = published ? rowres_S(res) : 0.f;
+    if (lane == gamma - 1) my_S = S_own;
+    SV_STAMP(9);
 
-    FSTAMP(9);
     // ---- accept tests eta_j < h_j
     const double S_row = (double)__shfl_down(my_S, 1, kWave);
     bool pass = false;
@@ -671,7 +766,8 @@ __device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int g
         // is the same number: it equals S - sum_x (w p - q) = S + 1 - w because both rows sum to one (w unclipped;
         // at w >= 1 the ratio is >= 1 and every eta in [0, 1) passes)
         else h = lw_j >= 0.0 ? 1.0 : S / (S + one_minus_w);
-        pass = (double)eta_j < h && (j == gamma || ((have & may) >> (j - 1)) & 1);
+        // (Alg. 1: as the row's leader judged it, with this same expression; the later positions' workgroups went by that)
+        pass = P.algo == kToken ? ratio_passes(ratio_word) : (double)eta < h && (j == gamma || ((have & may) >> (j - 1)) & 1);
         if (P.debug_out) {
             float *d = P.debug_out + (base + j) * 3;
             d[0] = (float)w_j; d[1] = (float)S; d[2] = (float)h;
@@ -686,118 +782,178 @@ __device__ __forceinline__ int finalize_tests(const FusedParams &P, int b, int g
     if (P.algo == kToken) tau = passed == ~0ull ? 64 : __ffsll((long long)~passed) - 1;    // leading run of passes
     else tau = passed ? 64 - __clzll((long long)passed) : 0;                               // last passing sub-block
     if (lane == 0) P.accept_len[b] = tau;
-    FSTAMP(10);
-
-    // ---- the tokens that the leaders of the row pairs before the last one have drawn: all of them are waited
-    // for (not only tau's), because their leaders read the partial sums that are zeroed when the sequence is done
-    const bool drawn = lane <= gamma - 2 && (lane == 0 || ((may >> (lane - 1)) & 1));
-    const unsigned cand = wait_word32(P.ycand + drow_l, cand_first, drawn, P.spin_limit, gave_up);
-    y_out = tau <= gamma - 2 ? __builtin_amdgcn_readlane((int)cand, tau) - 2 : -1;
-    lw_own = read_lane_double(my_lw, gamma - 1);
+    SV_STAMP(10);
+    // the token drawn for position tau: its leader drew one, because a position whose test passes can become tau
+    y_out = tau <= gamma - 2 ? rowres_token(read_lane_u64(res, tau)) : -1;
+    // log2 w of the last row pair, for its residual (token verification: its residual is p - q)
+    lw_own = gamma > 1 && P.algo != kToken ? read_lane_double(lw_j, gamma - 2) : 0.0;
     return tau;
 }
 
-// The sequence's control words are left zero for the next call (one wave, after Y is known).  Every reader of
-// the row-pair words has published something this wave has waited for: the units their partial sums (or, where
-// no residual mass is formed, nothing was read but by the leader), the leaders their ratio and their token.
-__device__ __forceinline__ void finalize_cleanup(const FusedParams &P, int b, int gamma, u64 last_first, unsigned par, bool &gave_up)
+// Clears the words of row slot `slot` of sequence b in one copy (one wave, all lanes, whole rows at a time: full
+// cache lines).  Slot gamma holds row gamma of the target rows' words and nothing else.
+__device__ __forceinline__ void clear_row_words(const FusedParams &P, const Words &W, int b, int slot)
 {
     const int lane = threadIdx.x & 63;
-    const int G = P.gamma, nu = P.nu;
-    const size_t base = (size_t)b * (G + 1);
-    const int e_lane = lane < nu ? lane : nu - 1;
-    // the last target row's words must all be written before the target rows' words can go (`last_first`: what
-    // was there when the tests began)
-    const u64 *last = P.pstat + (base + gamma) * nu;
-    for (int e = lane; e < G * nu; e += kWave) st_u32(P.spart + (size_t)b * G * nu + e, 0);
-    for (int e = lane; e < G * (nu / kWaves); e += kWave) { st_u64(P.pgrp + (size_t)b * G * (nu / kWaves) + e, 0); st_u64(P.qgrp + (size_t)b * G * (nu / kWaves) + e, 0); }
-    for (int e = lane; e < G; e += kWave) {
-        st_u64(P.ratio + (size_t)b * G + e, 0); st_u32(P.ycand + (size_t)b * G + e, 0);
-        if (e >= gamma - 1) st_u64(P.lw + (size_t)b * G + e, 0);     // only where this call had no reader (see pack_lw)
-    }
-    wait_word(last + e_lane, last_first, lane < nu, P.spin_limit, gave_up);
-    for (int e = lane + kWave; e < nu; e += kWave) wait_word(last + e, P.spin_limit, gave_up);
-    for (int e = lane; e < (G + 1) * nu; e += kWave) st_u64(P.pstat + base * nu + e, 0);
-    // the sequence's next call: every workgroup that reads the count has read it (their words were waited for)
-    if (lane == 0) __hip_atomic_store(P.gen + b, (int)(par ^ 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int G = P.gamma, nu = P.nu, nwg = nu / kWaves;
+    u64 *pstat = W.pstat + ((size_t)b * (G + 1) + slot) * nu;
+    for (int e = lane; e < nu; e += kWave) st_u64(pstat + e, 0);
+    if (slot == G) return;
+    const size_t drow = (size_t)b * G + slot;
+    for (int e = lane; e < nu; e += kWave) st_u32(W.spart + drow * nu + e, 0);
+    for (int e = lane; e < nwg; e += kWave) { st_u64(W.pgrp + drow * nwg + e, 0); st_u64(W.qgrp + drow * nwg + e, 0); }
+    if (lane == 0) { st_u64(W.ratio + drow, 0); st_u64(W.rowres + drow, 0); }
 }
-#undef FSTAMP
+
+// A wait of this wave has run out (or it has read a word of a wave that gave up): the workspace's error word says so
+// to whoever checks the workspace.
+__device__ __forceinline__ void report_gave_up(const FusedParams &P)
+{
+    if ((threadIdx.x & 63) == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
+}
 
 // ------------------------------------------------------------------ the kernel
 template <typename T, bool ALIGNED, int NW, int LANE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(LANE == kLaneLarge ? 3 : ElemTraits<T>::kVec == 8 ? 5 : 4)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(LANE == kLaneLarge ? 3 : ElemTraits<T>::kVec == 8 ? SV_WAVES_SMALL : 4)))
 void fused_verify_kernel(const FusedParams P)
 {
-    constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kUnitLogits = kWave * LANE;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int gamma = P.gamma, V = P.V, nu = P.nu;
     const float k = P.k;
 
-    if (__builtin_nontemporal_load(P.header + kHdrMagic) != P.magic) {
+    // Everything the first loads need comes out of the kernel's arguments in one go (one wait for the scalar loads
+    // instead of one per branch below) ...
+    const T *const target = static_cast<const T *>(P.target), *const draft = static_cast<const T *>(P.draft);
+    const size_t tstride = P.tstride, dstride = P.dstride;
+    const int32_t *const draft_lens = P.draft_lens;
+    const int *const header = P.header, *const gen = P.gen;
+    asm volatile("" :: "s"(target), "s"(draft), "s"(tstride), "s"(dstride), "s"(draft_lens), "s"(header), "s"(gen),
+                       "s"(gamma), "s"(V), "s"(nu), "s"(P.B), "s"(P.group_seqs), "s"(P.magic));
+    Unit U;
+    int wg_x;
+    if (!decode_unit(P, wave, U, wg_x)) return;
+    const int slot = U.i;
+    long long *stamps = nullptr;
+#ifdef SV_PROFILE
+    // one record per (sequence, slot, workgroup of the row): never beyond B * (gamma + 1) * workgroups per row records
+    if (P.prof) stamps = P.prof + (((size_t)U.b * (gamma + 1) + slot) * (nu / kWaves) + blockIdx.x) * 16;
+#endif
+    SV_STAMP(0);
+    // a sequence with a shorter draft has no row pairs at its unused positions, and its last target row is row gb
+    int gb = gamma;
+    if (draft_lens) { gb = load_uniform(draft_lens + U.b); gb = gb < 1 ? 1 : gb > gamma ? gamma : gb; }   // kept in range whatever the caller wrote
+    const bool unused = !U.last_row && U.i >= gb;
+    if (U.last_row) U.i = gb;
+
+    // stream A: the unit's chunk of target row i; stream B: the same chunk of draft row i (none for the last row)
+    const size_t seq_d = (size_t)U.b * gamma, seq_u = (size_t)U.b * (gamma + 1);
+    const size_t trow = seq_u + U.i, drow = seq_d + (U.last_row ? 0 : U.i);
+    const T *rowA = target + trow * tstride;
+    const T *rowB = draft + drow * dstride;
+    const int unit_first = U.c * kUnitLogits;
+    const int nwg = nu / kWaves;
+    // ... and a row pair's loads go out before anything is asked of the workspace: they depend on the arguments only
+    RawSlice<T, ALIGNED, LANE> rawA, rawB;
+    if (!U.last_row && !unused) {
+        // The first resident set starts all at once, and the memory system would serve its rows mixed: every row would
+        // be complete only when nearly all of them are, and no workgroup could leave (and none start) before.  So the
+        // workgroups of that set ask for their rows one row after the other, at about the rate the memory delivers
+        // them: the first rows are complete early and their workgroups make room while the later rows still arrive.
+        if (P.pace > 0.f) {
+            const unsigned lin = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+            if (lin < (unsigned)P.resident) {
+                const int waits = (int)((float)(lin / gridDim.x) * P.pace);
+                for (int w = 0; w < waits; ++w) __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        issue_loads<T, ALIGNED, LANE>(rowA, unit_first, V, rawA);
+        issue_loads<T, ALIGNED, LANE>(rowB, unit_first, V, rawB);
+    }
+    asm volatile("" ::: "memory");      // (keeps the two scalar loads below from being waited for in front of them)
+    const int magic_word = load_uniform(header + kHdrMagic);
+    const unsigned par = (unsigned)load_uniform(gen + U.b) & 1u;
+    if (magic_word != P.magic) {
         // the workspace was not initialised for this shape: report it through the outputs and leave
         if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
             for (int b = threadIdx.x; b < P.B; b += kThreads) { P.accept_len[b] = -1; P.next_token[b] = -1; }
         return;
     }
-#define SV_STAMP(slot) do { if (P.prof && threadIdx.x == 0) P.prof[(((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
-    Unit U;
-    int wg_x;
-    if (!decode_unit(P, wave, U, wg_x)) return;
-    SV_STAMP(0);
-    // a sequence with a shorter draft has no row pairs at its unused positions, and its last target row is row gb
-    int gb = gamma;
-    if (P.draft_lens) { gb = P.draft_lens[U.b]; gb = gb < 1 ? 1 : gb > gamma ? gamma : gb; }   // kept in range whatever the caller wrote
-    if (U.last_row) U.i = gb;
-    else if (U.i >= gb) return;
+    // every row slot's words are cleared, in the copy that this call does not use, by the first wave of the slot's
+    // last workgroup (the row's leader, where there is a row)
+    const bool clears = wave == 0 && wg_x == nwg - 1;
+    if (unused) {
+        // the copy in use holds nothing at an unused position; the other may hold an earlier, longer call's words:
+        // both are cleared, which needs no look at the call count
+        if (clears) { clear_row_words(P, P.words, U.b, slot); clear_row_words(P, words_of(P, 1), U.b, slot); }
+        return;
+    }
+    // the copy of the words this call uses for the sequence (see the head of this file)
+    const Words W = words_of(P, par);
 
-    // stream A: the unit's chunk of target row i; stream B: the same chunk of draft row i (none for the last row)
-    const size_t trow = (size_t)U.b * (gamma + 1) + U.i, drow = (size_t)U.b * gamma + (U.last_row ? 0 : U.i);
-    const T *rowA = static_cast<const T *>(P.target) + trow * P.tstride;
-    const T *rowB = static_cast<const T *>(P.draft) + drow * P.dstride;
-    const int unit_first = U.c * kUnitLogits;
-    RawSlice<T, ALIGNED, LANE> rawA, rawB;
-    issue_loads<T, ALIGNED, LANE>(rowA, unit_first, V, rawA);
-    if (!U.last_row) issue_loads<T, ALIGNED, LANE>(rowB, unit_first, V, rawB);
-    // draft token X_{i+1} and its two logits: the first wave of the row's last workgroup (the one with the
-    // fewest logits) publishes the row's ratio from them
-    const int nwg = nu / kWaves;
-    const bool leader = wave == 0 && wg_x == nwg - 1;
-    // log2 w_i (published by the previous position's leader, usually long ago) and the uniform of position i's
-    // test: what decides whether this row's residual mass can matter at all
-    const bool need_w = U.i > 0 && !U.last_row;
-    const u64 *lw_word = P.lw + (size_t)U.b * gamma + (U.i > 0 && !U.last_row ? U.i - 1 : 0);
-    // (the sequence's call count rides in the same block of loads as the word itself: a load in a block of its own
-    // makes the compiler wait for it, and for every load before it, at the end of that block)
-    int gen_count = 0;
-#define par ((unsigned)gen_count & 1u)
-    u64 wt = 0;
-    float eta_i = 0.f, eta_next = 0.f;
-    int tok = 0;                                             // the drafted token X_{i+1}, for the leader
-    if (wave == 0 && !U.last_row) {
-        tok = P.tokens[drow];
-        gen_count = P.gen[U.b];                                       // (does not change while the call runs: an ordinary load)
-        eta_i = P.uniforms[(size_t)U.b * (gamma + 1) + (U.i > 0 ? U.i - 1 : 0)];
-        eta_next = P.uniforms[(size_t)U.b * (gamma + 1) + U.i];      // the uniform of test i + 1, which the leader judges for Alg. 1
-        wt = ld_u64(lw_word);
+    __shared__ u64 wave_words[2][kWaves];
+    __shared__ double row_values[8];
+    __shared__ int row_flag;
+    bool gave_up = false;
+
+    // what the first wave keeps of the sequence: lane j < n_prev holds the word of log2 r_{j+1}
+    const int n_prev = U.i;                                   // ratios that w_i is made of
+#define SV_RATIO_WORD (W.ratio + seq_d + (lane < n_prev ? lane : 0))
+
+    if (U.last_row) {
+        // ---- the last target row: needed only if every token is accepted (then Y ~ p_gamma, Alg. 1 / 2 / 4).  In
+        // calls large enough for it to pay, its workgroups first look at the ratios: where eta_gamma >= w_gamma (Alg. 1:
+        // where some test fails) the row is not read at all, and its words say "no mass here".
+        if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
+        if (P.prune) {
+            if (wave == 0) {
+                const float eta_g = load_uniform(P.uniforms + seq_u + gb - 1);
+                const u64 rw = wait_word(SV_RATIO_WORD, ld_u64(SV_RATIO_WORD), lane < n_prev, P.spin_limit, gave_up);
+                const SeqState st = seq_state(P.algo, rw, n_prev);
+                const bool wanted = can_become_tau(P.algo, gb, read_lane_double(st.lw, gb - 1), eta_g, st.passed);
+                if (lane == 0) row_flag = gave_up ? 2 : wanted ? 0 : 1;
+                if (gave_up) report_gave_up(P);
+            }
+            __syncthreads();
+            const int flag = row_flag;
+            if (flag != 0) {
+                if (lane == 0) st_u64(W.pstat + trow * nu + U.c, flag == 2 ? kPoison64 : pack_stat(-INFINITY, 0.f));
+                return;
+            }
+        }
+        issue_loads<T, ALIGNED, LANE>(rowA, unit_first, V, rawA);
+        float xa[LANE], shiftA;
+        unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
+        const u64 stA = first_sweep_row(xa, k, shiftA);
+        if (lane == 0) st_u64(W.pstat + trow * nu + U.c, stA);
+        return;
     }
 
+    // draft token X_{i+1} and its two logits: the first wave of the row's last workgroup (the one with the
+    // fewest logits) publishes the row's ratio from them
+    const bool leader = wave == 0 && wg_x == nwg - 1;
+    u64 rw = 0;
+    float eta_i = 0.f, eta_next = 0.f;                       // the uniforms of test i (this position's) and test i + 1
+    int tok = 0;                                             // the drafted token X_{i+1}, for the leader
+    if (wave == 0) {
+        tok = load_uniform(P.tokens + drow);
+        eta_i = load_uniform(P.uniforms + seq_u + (n_prev > 0 ? n_prev - 1 : 0));
+        eta_next = load_uniform(P.uniforms + seq_u + n_prev);
+        rw = ld_u64(SV_RATIO_WORD);
+    }
+    if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
+
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
-    __shared__ u64 wave_words[2][kWaves];
-    __shared__ double row_values[3];
-    __shared__ int row_needed;
-    __shared__ double own_values[5];                         // the leader's results for its own use when it finishes the sequence
     float xa[LANE], xb[LANE];
     float shiftA, shiftB;
     unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
     {
         const u64 stA = first_sweep_row(xa, k, shiftA);
-        if (lane == 0) { st_u64(P.pstat + trow * nu + U.c, stA); wave_words[0][wave] = stA; }
+        if (lane == 0) { st_u64(W.pstat + trow * nu + U.c, stA); wave_words[0][wave] = stA; }
     }
-    if (U.last_row) return;          // the last target row has no draft row and no residual (whole workgroup)
     // the two logits of the draft token, asked for only now so that the streams above did not queue behind them
-    double ya = 0.0, yb = 0.0;
-    if (leader) { ya = logit_as_double(rowA + tok); yb = logit_as_double(rowB + tok); }
+    float ya_f = 0.f, yb_f = 0.f;
+    if (leader) { ya_f = logit_as_float(rowA + tok); yb_f = logit_as_float(rowB + tok); }
     unpack_slice<T, ALIGNED, LANE>(rowB, unit_first, V, rawB, xb);
     {
         const u64 stB = first_sweep_row(xb, k, shiftB);
@@ -805,183 +961,191 @@ void fused_verify_kernel(const FusedParams P)
     }
     __syncthreads();
 
-    // ---- L_p, L_q and w_i.  The workgroup's first wave combines the four waves' words into the
-    // workgroup's two words, publishes them, collects the words of all workgroups of the row and combines
-    // those; the other three waves sleep at the barrier meanwhile.  The row's leader also publishes the
-    // row's ratio, normalisers and w_{i+1}.  log2 w_i comes from the leader of the previous position
-    // (Alg. 2: w_i = min(w_{i-1} r_i, 1)).
-    bool gave_up = false;
+    // ---- the workgroup's first wave combines the four waves' words into the workgroup's two words and publishes them;
+    // then, in calls where it pays, it decides from the ratios of the earlier positions whether this row's residual mass
+    // can matter at all: a row that is not needed costs its workgroups no wait for the row
+    SeqState st = {};
+    bool have_state = false;
     if (wave == 0) {
         SV_STAMP(1);
-        StatAcc ga, gb;
+        StatAcc ga, gq;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) { ga.add(wave_words[0][w]); gb.add(wave_words[1][w]); }
+        for (int w = 0; w < kWaves; ++w) { ga.add(wave_words[0][w]); gq.add(wave_words[1][w]); }
         if (lane == 0) {
-            st_u64(P.pgrp + drow * nwg + wg_x, pack_stat(ga.m, ga.z));
-            st_u64(P.qgrp + drow * nwg + wg_x, pack_stat(gb.m, gb.z));
+            st_u64(W.pgrp + drow * nwg + wg_x, pack_stat(ga.m, (float)ga.z));
+            st_u64(W.qgrp + drow * nwg + wg_x, pack_stat(gq.m, (float)gq.z));
         }
-        // can this row's residual mass matter?  Needs log2 w_i; a row that is not needed costs its workgroups no wait
         bool needed = true;
-        if (need_w && P.prune && !P.debug_out) {
-            wt = wait_lw(lw_word, wt, par, true, P.spin_limit, gave_up);
-            needed = residual_needed(P, U.i, unpack_ratio(wt), eta_i);
+        if (n_prev > 0 && P.prune && !P.debug_out) {
+            rw = wait_word(SV_RATIO_WORD, rw, lane < n_prev, P.spin_limit, gave_up);
+            st = seq_state(P.algo, rw, n_prev);
+            have_state = true;
+            needed = gave_up || residual_needed(P, U.i, read_lane_double(st.lw, n_prev - 1), eta_i, st.passed);
         }
-        if (lane == 0) row_needed = needed ? 1 : 0;
+        if (lane == 0) row_flag = needed ? 1 : 0;
     }
     __syncthreads();
-    const bool needed = row_needed != 0;
+    const bool needed = row_flag != 0;
     // the leader of a sequence's last row pair finishes the sequence: what it works out for its row it has at hand
     const bool finisher = leader && U.i == gb - 1;
-    // a row whose residual mass cannot matter: only its leader (the next position needs this row's ratio; the
+    // a row whose residual mass cannot matter: only its leader (the later positions need this row's ratio; the
     // last one finishes the sequence) stays; everybody else is done and frees its registers
     if (!needed && !leader) return;
 
     bool candidate = true;           // whether this position can become tau: then its leader draws the token that would follow
-    if (wave == 0 && (needed || leader)) {
+    u64 own_word = 0;                // the leader's word of log2 r_{i+1}
+    if (wave == 0) {
+        // ---- L_p, L_q: the words of all workgroups of the row
         float Mp, Mq;
         double Lp, Lq;
         if (nwg <= kWave / 2) {
-            // one poll covers the row: the target row's words in lanes 0.., the draft row's in lanes 32..,
-            // log2 w_i beside them; the two halves of the wave are then combined side by side
+            // one poll covers the row: the target row's words in lanes 0.., the draft row's in lanes 32.., the ratios
+            // of the earlier positions (if still missing) beside them; the two halves of the wave are then combined
+            // side by side
             const int e = lane & 31;
             const bool need = e < nwg;
-            const u64 *word = (lane < 32 ? P.pgrp : P.qgrp) + drow * nwg + (need ? e : nwg - 1);
+            const u64 *word = (lane < 32 ? W.pgrp : W.qgrp) + drow * nwg + (need ? e : nwg - 1);
+            const bool need_r = !have_state && lane < n_prev;
             u64 v = ld_u64(word);
-            if (need_w) wt = ld_u64(lw_word);
             int spins = 0;
-            while (__any((need && v == 0) || (need_w && !lw_there(wt, par)))) {
+            while (__any((need && v == 0) || (need_r && rw == 0))) {
                 if (++spins > P.spin_limit) { gave_up = true; break; }
                 __builtin_amdgcn_s_sleep(1);
                 if (need && v == 0) v = ld_u64(word);
-                if (need_w && !lw_there(wt, par)) wt = ld_u64(lw_word);
+                if (need_r && rw == 0) rw = ld_u64(SV_RATIO_WORD);
             }
+            if (__any((need && v == kPoison64) || (need_r && rw == kPoison64))) gave_up = true;
             StatAcc acc;
             if (need) acc.add(v);
             halves_max(acc.m, Mp, Mq);
-            const float Mh = lane < 32 ? Mp : Mq;
-            float zp, zq;
-            halves_sum(acc.m > -INFINITY ? acc.z * fast_exp2(acc.m - Mh) : 0.f, zp, zq);
-            Lp = (double)Mp + log2_precise(zp);
-            Lq = (double)Mq + log2_precise(zq);
+            // each half relative to its own row's maximum
+            double zp, zq;
+            halves_sum_f64(acc.relative_to(lane < 32 ? Mp : Mq), zp, zq);
+            Lp = (double)shift_of(Mp) + log2_precise(zp);
+            Lq = (double)shift_of(Mq) + log2_precise(zq);
         } else {
             RowWords<NW> pw, qw;
-            load_row_words<NW>(P.pgrp + drow * nwg, nwg, pw);
-            load_row_words<NW>(P.qgrp + drow * nwg, nwg, qw);
-            if (need_w) wt = ld_u64(lw_word);
-            Lp = row_normaliser<NW>(P.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
-            Lq = row_normaliser<NW>(P.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
+            load_row_words<NW>(W.pgrp + drow * nwg, nwg, pw);
+            load_row_words<NW>(W.qgrp + drow * nwg, nwg, qw);
+            Lp = row_normaliser<NW>(W.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
+            Lq = row_normaliser<NW>(W.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
+            if (!have_state) rw = wait_word(SV_RATIO_WORD, rw, lane < n_prev, P.spin_limit, gave_up);
         }
-        double lr = 0.0;
         if (leader) {
-            // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for whoever finishes the sequence.  The sweeps
-            // scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To first order that moves a
-            // row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken as the row
-            // maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
+            // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for every later position and for whoever finishes
+            // the sequence.  The sweeps scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To
+            // first order that moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken
+            // as the row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
+            // (the three floats become doubles here and not a moment earlier: registers are scarce until the second sweep)
+            asm volatile("" : "+v"(ya_f), "+v"(yb_f), "+s"(eta_next));
+            const double ya = (double)ya_f, yb = (double)yb_f;
             const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
             const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-            lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
-            if (lane == 0) {
-                if (finisher) {                     // nobody else reads the last row pair's words
-                    own_values[0] = unpack_ratio(pack_ratio(lr)); own_values[1] = Lp; own_values[2] = Lq;
-                } else {
-                    st_u64(P.ratio + drow, pack_ratio(lr));
-                }
-            }
+            double lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
+            // Alg. 1's test of X_{i+1}, judged here once for everybody: eta_{i+1} < min(r_{i+1}, 1)
+            const bool passes = P.algo == kToken && (double)eta_next < exp2(fmin(lr, 0.0));
+            own_word = pack_ratio(lr, passes);
+            if (gave_up) report_gave_up(P);
+            if (lane == 0) st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
         }
+        if (!have_state) st = seq_state(P.algo, rw, n_prev);
         double log2w = 0.0;
-        if (need_w) log2w = unpack_ratio(wait_lw(lw_word, wt, par, true, P.spin_limit, gave_up));
-        candidate = can_become_tau(P, U.i, log2w, eta_i);       // (on the word as published, like the finishing wave)
-        if (leader) {
-            // w_{i+1} for the workgroups of the next position
-            double next = log2w + lr;
-            if (P.algo == kBlock && next > 0.0) next = 0.0;        // the min{., 1}; greedy block verification omits it
-            if (P.algo == kToken) {
-                // token verification: 0 while every test so far has passed (test i+1: eta_{i+1} < min(r_{i+1}, 1), the
-                // expression the finishing wave evaluates too), kLog2RatioFloor from the first failure on
-                const bool pass = log2w > 0.5 * kLog2RatioFloor && (double)eta_next < exp2(fmin(unpack_ratio(pack_ratio(lr)), 0.0));
-                next = pass ? 0.0 : kLog2RatioFloor;
-            }
-            if (lane == 0) {
-                if (finisher) own_values[4] = unpack_ratio(pack_ratio(next));
-                else st_u64(P.lw + drow, pack_lw(next, par));
-            }
-        }
+        if (n_prev > 0) log2w = read_lane_double(st.lw, n_prev - 1);
+        candidate = can_become_tau(P.algo, U.i, log2w, eta_i, st.passed);
         if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
-        if (lane == 0) { row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w; }
+        if (P.algo == kGreedy) log2w = fmin(log2w, 100.0);          // keeps w p finite in float
+        // the second sweep's row constants: w p(x) = 2^(y_p - A) with A = L_p - log2 w, q(x) = 2^(y_q - L_q).  Their
+        // integer parts meet the units' integer shifts in the exponent; the fractions are formed once, here, in double
+        const double A = Lp - log2w, Ai = rint(A), Qi = rint(Lq);
+        const double fq = exp2_precise(Qi - Lq), frho = exp2_precise((Ai - A) - (Qi - Lq));
+        if (lane == 0) {
+            row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w;
+            row_values[3] = Ai; row_values[4] = Qi; row_values[5] = fq; row_values[6] = frho; row_values[7] = 1.0 / frho;
+            row_flag = gave_up ? 2 : 1;
+        }
+        if (gave_up) report_gave_up(P);
         SV_STAMP(2);
     }
-    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
-    // a draw that this wave makes: row, mode and the two row constants (see draw_from_row); -1: none
-    int draw_row = -1, draw_mode = 0;
-    double draw_ap = 0.0, draw_aq = 0.0;
+    double S_own = 0.0;              // the leader's: S_i, summed over the row's partial sums
     if (needed) {
-    __syncthreads();
+        __syncthreads();
+        const double Lp = row_values[0], Lq = row_values[1], log2w = row_values[2];
+        const bool poisoned = row_flag == 2;
+        SV_STAMP(3);
+
+        // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq with the wave-uniform cp = 2^(shiftA - A),
+        // cq = 2^(shiftB - L_q): powers of two times the row's two fractions
+        const int ea = (int)((double)shiftA - row_values[3]), eq = (int)((double)shiftB - row_values[4]);
+        const double fq = row_values[5], frho = row_values[6];
+        float acc = 0.f;
+        {
+            // sum of max(xa cp - xb cq, 0) with the larger factor taken out, so that every term lies in [0, 1]
+            // (xa, xb <= 1) and the clamp of the fma is the max: two instructions per pair.  The factor rho = cp / cq
+            // is rounded once, from double: whatever it is off by multiplies the whole mass of the row's active
+            // tokens, which is what is left of S_i where w p and q nearly agree.
+            const double rho = ldexp(frho, ea - eq);
+            if (rho <= 1.0) {
+                const float rho_f = (float)rho;
+#pragma unroll
+                for (int j = 0; j < LANE; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xa[j], rho_f, -xb[j]), 0.f, 1.f);
+                acc *= (float)ldexp(fq, eq);
+            } else {
+                const float nrho = -(float)ldexp(row_values[7], eq - ea);
+#pragma unroll
+                for (int j = 0; j < LANE; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xb[j], nrho, xa[j]), 0.f, 1.f);
+                acc *= (float)ldexp(fq * frho, ea);
+            }
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) st_u32(W.spart + drow * nu + U.c, poisoned ? kPoison32 : pack_partial(acc));
+        SV_STAMP(4);
+        if (!leader) return;
+        // ---- the row's leader sums the row's partial sums and, if this position can become tau, draws the token that
+        // follows in that case - while the later positions are still streaming: whoever finishes the sequence then
+        // only picks both up
+        if (!finisher) {
+            const float u = load_uniform(P.uniforms + seq_u + gb);
+            const int drawn = draw_from_row<T, ALIGNED, LANE>(P, W, U.b, U.i, 0, candidate, Lp - log2w, Lq, u, S_own, gave_up);
+            if (gave_up) report_gave_up(P);
+            if (lane == 0) st_u64(W.rowres + drow, gave_up ? kPoison64 : pack_rowres((float)S_own, drawn));
+            return;
+        }
+    }
+    if (!finisher) return;
+    // ---- the leader of a sequence's last row pair finishes the sequence
+    SV_STAMP(5);
     const double Lp = row_values[0], Lq = row_values[1];
-    double log2w = row_values[2];
-    if (P.algo == kGreedy) log2w = fmin(log2w, 100.0);      // keeps w p finite in float
-    SV_STAMP(3);
-
-    // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq with wave-uniform cp, cq
-    const double log2cp = (double)shiftA - (Lp - log2w), log2cq = (double)shiftB - Lq;
-    float acc = 0.f;
-    {
-        // sum of max(xa cp - xb cq, 0) with the larger factor taken out, so that every term lies in [0, 1]
-        // (xa, xb <= 1) and the clamp of the fma is the max: two instructions per pair
-        const double log2rho = log2cp - log2cq;
-        if (log2rho <= 0.0) {
-            const float rho = fast_exp2((float)log2rho);
-#pragma unroll
-            for (int j = 0; j < LANE; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xa[j], rho, -xb[j]), 0.f, 1.f);
-            acc *= fast_exp2((float)log2cq);
-        } else {
-            const float nrho = -fast_exp2((float)-log2rho);
-#pragma unroll
-            for (int j = 0; j < LANE; ++j) acc += __builtin_amdgcn_fmed3f(__builtin_fmaf(xb[j], nrho, xa[j]), 0.f, 1.f);
-            acc *= fast_exp2((float)log2cp);
-        }
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) {
-        st_u32(P.spart + drow * nu + U.c, pack_partial(acc));
-    }
-    SV_STAMP(4);
-    // the row's leader draws the token that follows if this position becomes tau, while the later positions are
-    // still streaming: whoever finishes the sequence then only picks it up
-    if (leader && !finisher && candidate) { draw_row = U.i; draw_ap = Lp - log2w; draw_aq = Lq; }
-
-    }
-    if (!leader) return;
-    // the leader of a sequence's last row pair finishes the sequence: the earlier positions come before
-    // it in the workgroup order, the last target row (needed only if every token is accepted) right after
+    const float u = load_uniform(P.uniforms + seq_u + gb);
+    // its own row's mass (the draw, if tau turns out to be this position, comes after the tests)
+    if (needed) draw_from_row<T, ALIGNED, LANE>(P, W, U.b, U.i, 0, false, 0.0, 0.0, u, S_own, gave_up);
+    // the last target row's words, asked for early: they are waited for before the sequence's call count moves on
+    const int e_lane = lane < nu ? lane : nu - 1;
+    const u64 *last = W.pstat + (seq_u + gb) * nu;
+    const u64 last_first = ld_u64(last + e_lane);
     int y = -1;
-    u64 last_first = 0;
-    if (finisher) {
-        SV_STAMP(5);
-        __builtin_amdgcn_wave_barrier();                     // own_values: written by lane 0 above, read by another lane below
-        double lw_own;
-        const int tau = finalize_tests(P, U.b, gb, own_values, par, y, lw_own, last_first, gave_up);
-        if (y < 0) {
-            // tau is the last row pair (its residual: this wave has the row's constants) or every token was
-            // accepted (Y comes from the last target row itself)
-            draw_row = tau; draw_mode = tau == gb ? 1 : 0;
-            draw_ap = own_values[1] - lw_own; draw_aq = own_values[2];
-        }
+    double lw_own;
+    // lane j: the word of log2 r_{j+1}; the last one is this wave's own
+    const int tau = finish_sequence(P, W, U.b, gb, lane == gb - 1 ? own_word : rw, (float)S_own, y, lw_own, gave_up, stamps);
+    if (y < 0) {
+        // tau is the last row pair (its residual: this wave has the row's constants) or every token was
+        // accepted (Y comes from the last target row itself)
+        double total;
+        y = draw_from_row<T, ALIGNED, LANE>(P, W, U.b, tau, tau == gb ? 1 : 0, true, Lp - lw_own, Lq, u, total, gave_up);
     }
-    if (draw_row >= 0) {
-        const float u = P.uniforms[(size_t)U.b * (gamma + 1) + gb];
-        const int drawn = draw_from_row<T, ALIGNED, LANE>(P, U.b, draw_row, draw_mode, draw_ap, draw_aq, u, gave_up);
-        if (finisher) y = drawn;
-        else if (lane == 0) st_u32(P.ycand + (size_t)U.b * gamma + draw_row, (unsigned)drawn + 2u);
+    SV_STAMP(12);
+    // every workgroup of the sequence has read the call count once the last target row's words are there (the row
+    // pairs' workgroups published words that this wave, or a leader it heard from, has waited for)
+    wait_word(last + e_lane, last_first, lane < nu, P.spin_limit, gave_up);
+    for (int e = lane + kWave; e < nu; e += kWave) wait_word(last + e, P.spin_limit, gave_up);
+    if (gave_up) report_gave_up(P);
+    if (lane == 0) {
+        // a wait that ran out anywhere on the way here leaves nothing to trust
+        if (gave_up) { P.accept_len[U.b] = -1; y = -1; }
+        P.next_token[U.b] = y;
+        __hip_atomic_store(P.gen + U.b, (int)(par ^ 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (finisher) {
-        if (lane == 0) P.next_token[U.b] = y;
-        SV_STAMP(12);
-        finalize_cleanup(P, U.b, gb, last_first, par, gave_up);
-        SV_STAMP(6);
-    }
-    if (gave_up && lane == 0 && ld_i32(P.header + kHdrError) == 0) atomicOr(P.header + kHdrError, 1);
-#undef SV_STAMP
-#undef par
+    SV_STAMP(6);
+#undef SV_RATIO_WORD
 }
 
 // Clears the control words of a workspace and marks it initialised.

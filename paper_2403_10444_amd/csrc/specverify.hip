@@ -9,6 +9,7 @@
 #include <stdint.h>
 #include <math.h>
 #include <atomic>
+#include <stdlib.h>
 
 #include "../../include/specverify.h"
 #include "common.hpp"
@@ -26,7 +27,9 @@ constexpr int kDefaultSpinLimit = 1 << 20;
 std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused; 3 / 4: fused with small / large units (testing hook)
 std::atomic<int> g_spin_limit{kDefaultSpinLimit};
 std::atomic<int> g_lane{0};                        // 0 auto, 32 or 64: logits per lane of the fused kernel's units (testing hook)
-std::atomic<long long *> g_prof{nullptr};          // device buffer for per-unit timestamps (tuning hook)
+#ifdef SV_PROFILE
+std::atomic<long long *> g_prof{nullptr};          // device buffer for per-workgroup timestamps (tuning builds only)
+#endif
 
 struct Layout {
     size_t total;
@@ -34,8 +37,9 @@ struct Layout {
     bool fused_ok;
     int nu;                       // wave chunks per row = 4 * workgroups per row
     size_t fused_grid;            // workgroups of the fused kernel
-    size_t control_words;         // header and all words that cross waves: in ints, at offset 0, zero between calls
-    size_t off_ratio, off_lw, off_ycand, off_gen, off_pstat, off_pgrp, off_qgrp, off_spart;
+    size_t control_words;         // header, call counts and both copies of the words that cross waves: in ints, at offset 0
+    size_t off_gen, copy_bytes;   // the call counts; bytes from one copy of the words to the other
+    size_t off_ratio, off_rowres, off_pstat, off_pgrp, off_qgrp, off_spart;     // copy 0
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -55,14 +59,16 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.fused_grid = rows_t * (size_t)(L.nu / kWaves);
     L.fused_ok = L.nu <= kMaxUnitsPerRow && L.fused_grid <= 0x7fffffffull;
     size_t off = kHdrWords * sizeof(int);
+    L.off_gen = off;    off = align_up(off + (size_t)B * sizeof(int), 256);
+    const size_t copy0 = off;
     L.off_ratio = off;  off += rows_d * sizeof(u64);
-    L.off_lw = off;     off += rows_d * sizeof(u64);
-    L.off_ycand = off; off += align_up(rows_d * sizeof(unsigned), 8);
-    L.off_gen = off;   off += align_up((size_t)B * sizeof(int), 8);
+    L.off_rowres = off; off += rows_d * sizeof(u64);
     L.off_pstat = off;  off += rows_t * L.nu * sizeof(u64);
     L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_qgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
+    L.copy_bytes = align_up(off - copy0, 256);
+    off = copy0 + 2 * L.copy_bytes;
     L.control_words = off / sizeof(int);
     off = align_up(off, 256);
     // the staged path's scratch follows, so that it never touches the control words
@@ -73,17 +79,34 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     return true;
 }
 
-// Workgroups of a kernel that the current device keeps resident at once (cached per kernel).
-template <typename K>
-int resident_workgroups(K kernel, int &cache)
+template <typename T> constexpr int dtype_bytes() { return ElemTraits<T>::kVec == 4 ? 4 : 2; }
+
+// Waits (of 64 clocks) per row between the load requests of the first resident set's rows; SPECVERIFY_PACE overrides
+// the factor for tuning.
+float pace_units(double row_pair_bytes)
 {
-    if (cache > 0) return cache;
+    static const double factor = [] { const char *e = getenv("SPECVERIFY_PACE"); return e ? atof(e) : 0.75; }();
+    return (float)(factor * row_pair_bytes / 6.0e12 * 2.1e9 / 64.0);
+}
+
+// Workgroups of a kernel that the current device keeps resident at once (cached per kernel).
+// (tuning: SPECVERIFY_LDS bytes of dynamic LDS per workgroup, which lowers the number of resident workgroups)
+size_t tuning_lds_bytes()
+{
+    static const size_t bytes = [] { const char *e = getenv("SPECVERIFY_LDS"); return e ? (size_t)atol(e) : (size_t)0; }();
+    return bytes;
+}
+
+template <typename K>
+int resident_workgroups(K kernel, std::atomic<int> &cache)
+{
+    if (cache.load() > 0) return cache.load();
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess) return 0;
-    cache = cus * per_cu;
-    return cache;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, tuning_lds_bytes()) != hipSuccess) return 0;
+    cache.store(cus * per_cu);
+    return cus * per_cu;
 }
 
 template <typename T, bool ALIGNED>
@@ -157,7 +180,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     const int nu = (V + kWaves * kWave * lane_logits - 1) / (kWaves * kWave * lane_logits) * kWaves;
     // the instantiation for this row width (one or two words of a row per lane of the collecting wave) and its
     // resident workgroups
-    static int cap[2][2] = {{0, 0}, {0, 0}};
+    static std::atomic<int> cap[2][2];
     const int nwg = nu / kWaves;
     const int nw_log = nwg <= kWave ? 0 : 1;
     void (*kernel)(const FusedParams) = nullptr;
@@ -186,19 +209,25 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     // (the testing hook's forced unit sizes also force the pruning, so that small test shapes exercise it)
     P.prune = g_lane.load() != 0 || (size_t)wpr * P.group_seqs * n_groups * (gamma + 1) > (size_t)capacity ? 1 : 0;
     P.spin_limit = g_spin_limit.load();
+    P.resident = capacity;
+    // pacing of the first resident set (only where there is a second one): one row pair's bytes at about 6 TB/s, in
+    // units of 64 clocks at about 2.1 GHz, less the rate at which the workgroups start anyway
+    P.pace = P.prune ? pace_units((double)V * (dtype_bytes<T>() * 2)) : 0.f;
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);
-    P.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
-    P.ycand = reinterpret_cast<unsigned *>(ws + L.off_ycand);
-    P.lw = reinterpret_cast<u64 *>(ws + L.off_lw);
     P.gen = reinterpret_cast<int *>(ws + L.off_gen);
-    P.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
-    P.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
-    P.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
-    P.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
+    P.words.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
+    P.words.rowres = reinterpret_cast<u64 *>(ws + L.off_rowres);
+    P.words.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
+    P.words.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
+    P.words.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
+    P.words.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
+    P.copy_bytes = L.copy_bytes;
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
+#ifdef SV_PROFILE
     P.prof = g_prof.load();
-    kernel<<<grid, kThreads, 0, stream>>>(P);
+#endif
+    kernel<<<grid, kThreads, tuning_lds_bytes(), stream>>>(P);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
@@ -336,10 +365,12 @@ sv_status_t spec_sample_tokens(const void *logits, int64_t rows, int32_t V, sv_d
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
+#ifdef SV_PROFILE
 void spec_verify_debug_profile(void *device_buffer)
 {
     g_prof.store(static_cast<long long *>(device_buffer));
 }
+#endif
 
 sv_status_t spec_verify_block(const void *target_logits, const void *draft_logits,
                               const int32_t *draft_tokens, const float *uniforms,

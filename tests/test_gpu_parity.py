@@ -455,9 +455,17 @@ def test_a_wait_that_runs_out_is_reported_not_hung(path):
         tau, y = sv.spec_verify_block(inp["target_logits"], inp["draft_logits"], inp["draft_tokens"],
                                       inp["uniforms"], cfg.temperature, workspace=ws)
         torch.cuda.synchronize()                 # the kernel ends normally whatever it computed
-        assert torch.all((tau >= 0) & (tau <= cfg.gamma)) and torch.all((y >= 0) & (y < cfg.V))
         status = sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V)
         assert status in (0, 5)                  # 5 = SV_ERR_INTERNAL when some unit really had to wait
+        # a sequence any of whose waits ran out reports -1 for both outputs; every other one is complete and right
+        tau, y = tau.cpu().numpy(), y.cpu().numpy()
+        failed = tau < 0
+        assert np.array_equal(failed, y < 0)
+        if status == 0:
+            assert not failed.any()
+        ref = parity.run_oracle("block", inp, cfg.temperature)
+        safe = ~failed & (ref["margins"].min(axis=1) >= parity.MARGIN)
+        assert np.array_equal(tau[safe], ref["accept_len"][safe]) and np.array_equal(y[safe], ref["next_token"][safe])
     finally:
         sv.spec_verify_debug_config(PATHS[path], -1)
     sv.spec_verify_workspace_init(ws, cfg.B, cfg.gamma, cfg.V)
