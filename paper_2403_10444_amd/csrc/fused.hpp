@@ -79,6 +79,9 @@ typedef unsigned long long u64;
 // The words of one copy (see the head of this file).
 struct Words {
     u64 *ratio;           // [B, gamma]               log2 r_{i+1} as double bits, two lowest bits: flags (pack_ratio); by the leader of row pair i
+    u64 *lw;              // [B, gamma]               calls larger than one resident set: log2 w_{i+1} as double bits, lowest bit set
+                          //                          (Alg. 1: 0 while every test up to i + 1 has passed, kLog2RatioFloor afterwards); by
+                          //                          the leader of row pair i
     u64 *rowres;          // [B, gamma]               low half: S_i as float bits; high half: the token drawn from row pair i's
                           //                          residual + 2, or 1 if none was drawn; by the leader of row pair i
     u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
@@ -124,7 +127,7 @@ __device__ __forceinline__ Words words_of(const FusedParams &P, unsigned copy)
 {
     const size_t off = copy ? P.copy_bytes : 0;
     Words W;
-    W.ratio = shifted(P.words.ratio, off); W.rowres = shifted(P.words.rowres, off); W.pstat = shifted(P.words.pstat, off);
+    W.ratio = shifted(P.words.ratio, off); W.lw = shifted(P.words.lw, off); W.rowres = shifted(P.words.rowres, off); W.pstat = shifted(P.words.pstat, off);
     W.pgrp = shifted(P.words.pgrp, off); W.qgrp = shifted(P.words.qgrp, off); W.spart = shifted(P.words.spart, off);
     return W;
 }
@@ -384,48 +387,65 @@ __device__ __forceinline__ double row_normaliser(const u64 *words, int n, int li
 }
 
 // ------------------------------------------------------------------ the sequence's weights and what can matter
-// What a wave knows of a sequence once it holds the ratio words of positions 1 .. n (lane j: the word of log2 r_{j+1}).
-// Every wave that needs any of it - the first waves of the row pairs' workgroups, of the last target row's workgroups
-// and the wave that finishes the sequence - evaluates these same functions on the same published words, so they
-// always agree on which sums and which draws exist.
-struct SeqState {
-    double lw;            // lane j < n: log2 w_{j+1}.  Alg. 2: w_i = min(w_{i-1} r_i, 1), w_0 = 1; Alg. 4: without the min
-    u64 passed;           // Alg. 1: bit j set iff test j + 1 passes (the same in every lane)
-};
-__device__ __forceinline__ SeqState seq_state(int algo, u64 ratio_word, int n)
+// log2 w_i for every position from the ratio words of positions 1 .. n (lane j holds the word of log2 r_{j+1} and gets
+// log2 w_{j+1}).  Alg. 2: w_i = min(w_{i-1} r_i, 1), w_0 = 1; Alg. 4: without the min.  Alg. 1 has no w: there the value
+// is 0 while every test up to the position has passed and kLog2RatioFloor afterwards (what the rule below asks).
+__device__ __forceinline__ double weights_from_ratios(int algo, u64 ratio_word, int n)
 {
     const int lane = threadIdx.x & 63;
-    SeqState st;
-    st.lw = 0.0;
-    st.passed = 0;
     if (algo == kToken) {
-        st.passed = __ballot(lane < n && ratio_passes(ratio_word));
-    } else {
-        // log2 w_i = P_i - max(0, P_1, ..., P_i) with P_i = log2 r_1 + ... + log2 r_i: the recursion's min written out
-        // (each time the product would exceed 1 it restarts from 1)
-        const double P = wave_scan(lane < n ? unpack_ratio(ratio_word) : 0.0);
-        st.lw = algo == kBlock ? P - wave_scan_max0(P) : P;
+        const u64 passed = __ballot(lane < n && ratio_passes(ratio_word));
+        return (~passed & ((2ull << lane) - 1ull)) == 0 ? 0.0 : kLog2RatioFloor;
     }
-    return st;
+    // log2 w_i = P_i - max(0, P_1, ..., P_i) with P_i = log2 r_1 + ... + log2 r_i: the recursion's min written out
+    // (each time the product would exceed 1 it restarts from 1)
+    const double P = wave_scan(lane < n ? unpack_ratio(ratio_word) : 0.0);
+    return algo == kBlock ? P - wave_scan_max0(P) : P;
+}
+// The same one position further, as the leader of row pair i forms it for the workgroups of position i + 1 (calls in
+// which the positions follow each other at a distance: one word to read instead of i + 1).
+__device__ __forceinline__ double next_weight(int algo, double log2w_i, double log2r, bool passes)
+{
+    if (algo == kToken) return log2w_i > 0.5 * kLog2RatioFloor && passes ? 0.0 : kLog2RatioFloor;
+    const double next = log2w_i + log2r;
+    return algo == kBlock && next > 0.0 ? 0.0 : next;
 }
 
-// Whether position i (1 <= i <= the draft length) can become tau, given log2 w_i (seq_state's lane i - 1), the
-// position's uniform and, for Alg. 1, the tests passed.  The acceptance probability of block (and greedy block)
-// verification never exceeds w_i: h_i = S_i / (S_i + 1 - w_i) with S_i <= w_i, and h_gamma = w_gamma.  So a test with
-// eta_i >= w_i fails whatever S_i is, and tau is a position whose test passed, or 0.  Decided with a margin far above
-// the rounding of h_i.  Token verification (Alg. 1) stops at the first failure: only a position that all tests up to
-// its own let through can become tau.  Position 0 (nothing accepted) always can.
-__device__ __forceinline__ bool can_become_tau(int algo, int i, double log2w_i, float eta_i, u64 passed)
+// Whether position i (1 <= i <= the draft length) can become tau, given log2 w_i and the position's uniform.  The
+// acceptance probability of block (and greedy block) verification never exceeds w_i: h_i = S_i / (S_i + 1 - w_i) with
+// S_i <= w_i, and h_gamma = w_gamma.  So a test with eta_i >= w_i fails whatever S_i is, and tau is a position whose
+// test passed, or 0.  Decided with a margin far above the rounding of h_i.  Token verification (Alg. 1) stops at the
+// first failure: only a position that all tests up to its own let through can become tau.  Position 0 (nothing
+// accepted) always can.  Every wave that asks - the waves of the position's workgroups, of the last target row's
+// workgroups and the wave that finishes the sequence - evaluates this on the same numbers (the same published word, or
+// the same scan over the same published ratios), so they always agree on which sums and which draws exist.
+__device__ __forceinline__ bool can_become_tau(int algo, int i, double log2w_i, float eta_i)
 {
     if (i == 0) return true;
-    if (algo == kToken) return (~passed & ((i >= 64 ? 0ull : (1ull << i)) - 1ull)) == 0;
+    if (algo == kToken) return log2w_i > 0.5 * kLog2RatioFloor;
     return (double)__builtin_amdgcn_logf(eta_i) < log2w_i + 1.0e-3;
 }
 // Whether position i's residual mass is formed: where the position can become tau, and everywhere when the caller
 // wants every S_i reported or the call is too small for leaving any out to pay.
-__device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i, u64 passed)
+__device__ __forceinline__ bool residual_needed(const FusedParams &P, int i, double log2w_i, float eta_i)
 {
-    return !P.prune || P.debug_out || can_become_tau(P.algo, i, log2w_i, eta_i, passed);
+    return !P.prune || P.debug_out || can_become_tau(P.algo, i, log2w_i, eta_i);
+}
+
+// The workgroup's two words from its four waves' words in LDS (one wave: lanes 0..3 take the target row's, lanes 4..7
+// the draft row's; each quad combines its four in a fixed order, the sums through exact powers of two).
+__device__ __forceinline__ void publish_group_words(const u64 (&wave_words)[2][kWaves], u64 *pgrp_word, u64 *qgrp_word)
+{
+    const int lane = threadIdx.x & 63;
+    const u64 w = wave_words[(lane >> 2) & 1][lane & 3];
+    const float m = stat_shift(w);
+    float M = fmaxf(m, __int_as_float(dpp_shift<0xB1>(__float_as_int(m))));            // quad_perm:[1,0,3,2]
+    M = fmaxf(M, __int_as_float(dpp_shift<0x4E>(__float_as_int(M))));                   // quad_perm:[2,3,0,1]
+    double z = m > -INFINITY ? ldexp((double)stat_sum(w), (int)(shift_of(m) - shift_of(M))) : 0.0;
+    z += dpp_shift_double<0xB1>(z);
+    z += dpp_shift_double<0x4E>(z);
+    if (lane == 0) st_u64(pgrp_word, pack_stat(M, (float)z));
+    if (lane == 4) st_u64(qgrp_word, pack_stat(M, (float)z));
 }
 
 struct Unit {
@@ -717,10 +737,11 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &
 // ------------------------------------------------------------------ whole sequences
 // Accept tests of one sequence (one wave: the leader of the sequence's last row pair, position gamma - 1, where `gamma`
 // is this sequence's draft length).  `ratio_word`: lane j < gamma holds the word of log2 r_{j+1} (the last one is this
-// wave's own); S_own: the residual mass of the last row pair, if it was formed.  Writes tau (and the debug
+// wave's own); `lw`: lane j < gamma holds log2 w_{j+1} as the positions' workgroups saw it; S_own: the residual mass of
+// the last row pair, if it was formed.  Writes tau (and the debug
 // block); returns tau.  y_out is the token that the leader of row pair tau has drawn from its residual, or -1 when tau
 // is the last row pair or beyond (then the caller draws); lw_own is log2 w of the last row pair.
-__device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words &W, int b, int gamma, u64 ratio_word, float S_own,
+__device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words &W, int b, int gamma, u64 ratio_word, double lw, float S_own,
                                                int &y_out, double &lw_own, bool &gave_up, long long *stamps)
 {
     const int lane = threadIdx.x & 63;
@@ -733,13 +754,12 @@ __device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words
     u64 res = gamma > 1 ? ld_u64(res_word) : 0;
     const float eta = P.uniforms[base + (lane < gamma ? lane : gamma - 1)];          // lane l: eta_{l+1}
     SV_STAMP(7);
-    const SeqState st = seq_state(P.algo, ratio_word, gamma);
     const double lr = unpack_ratio(ratio_word);
     // lane l tests position j = l + 1
     const int j = lane + 1;
-    double lw_j = st.lw;                                 // log2 w_j as the rule sees it (greedy: unclipped and uncapped)
-    const u64 may = __ballot(j < gamma && can_become_tau(P.algo, j, lw_j, eta, st.passed));
-    const u64 have = __ballot(j < gamma && residual_needed(P, j, lw_j, eta, st.passed));
+    double lw_j = lw;                                    // log2 w_j as the rule sees it (greedy: unclipped and uncapped)
+    const u64 may = __ballot(j < gamma && can_become_tau(P.algo, j, lw_j, eta));
+    const u64 have = __ballot(j < gamma && residual_needed(P, j, lw_j, eta));
     if (P.algo == kGreedy) lw_j = fmin(lw_j, 100.0);
     if (P.algo == kToken) lw_j = 0.0;
     const double w_j = exp2(lw_j);
@@ -802,7 +822,7 @@ __device__ __forceinline__ void clear_row_words(const FusedParams &P, const Word
     const size_t drow = (size_t)b * G + slot;
     for (int e = lane; e < nu; e += kWave) st_u32(W.spart + drow * nu + e, 0);
     for (int e = lane; e < nwg; e += kWave) { st_u64(W.pgrp + drow * nwg + e, 0); st_u64(W.qgrp + drow * nwg + e, 0); }
-    if (lane == 0) { st_u64(W.ratio + drow, 0); st_u64(W.rowres + drow, 0); }
+    if (lane == 0) { st_u64(W.ratio + drow, 0); st_u64(W.lw + drow, 0); st_u64(W.rowres + drow, 0); }
 }
 
 // A wait of this wave has run out (or it has read a word of a wave that gave up): the workspace's error word says so
@@ -896,21 +916,25 @@ void fused_verify_kernel(const FusedParams P)
     __shared__ int row_flag;
     bool gave_up = false;
 
-    // what the first wave keeps of the sequence: lane j < n_prev holds the word of log2 r_{j+1}
+    // Two ways to w_i.  Calls larger than one resident set ("chain"): the leader of row pair i - 1 publishes log2 w_i
+    // itself, one word that the workgroups of position i read - position i starts a resident set after position i - 1, the
+    // word is there long before it is asked for.  Smaller calls, where all positions run at once: the first wave of a
+    // workgroup reads the ratios of all earlier positions (lane j: the word of log2 r_{j+1}) and forms w_i from them.
     const int n_prev = U.i;                                   // ratios that w_i is made of
+    const bool chain = P.prune != 0;
 #define SV_RATIO_WORD (W.ratio + seq_d + (lane < n_prev ? lane : 0))
+    const u64 *const lw_word = W.lw + seq_d + (n_prev > 0 ? n_prev - 1 : 0);
 
     if (U.last_row) {
         // ---- the last target row: needed only if every token is accepted (then Y ~ p_gamma, Alg. 1 / 2 / 4).  In
-        // calls large enough for it to pay, its workgroups first look at the ratios: where eta_gamma >= w_gamma (Alg. 1:
+        // calls large enough for it to pay, its workgroups first look at w_gamma: where eta_gamma >= w_gamma (Alg. 1:
         // where some test fails) the row is not read at all, and its words say "no mass here".
         if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
-        if (P.prune) {
+        if (chain) {
             if (wave == 0) {
                 const float eta_g = load_uniform(P.uniforms + seq_u + gb - 1);
-                const u64 rw = wait_word(SV_RATIO_WORD, ld_u64(SV_RATIO_WORD), lane < n_prev, P.spin_limit, gave_up);
-                const SeqState st = seq_state(P.algo, rw, n_prev);
-                const bool wanted = can_become_tau(P.algo, gb, read_lane_double(st.lw, gb - 1), eta_g, st.passed);
+                const u64 wt = wait_word(lw_word, P.spin_limit, gave_up);
+                const bool wanted = can_become_tau(P.algo, gb, unpack_ratio(wt), eta_g);
                 if (lane == 0) row_flag = gave_up ? 2 : wanted ? 0 : 1;
                 if (gave_up) report_gave_up(P);
             }
@@ -932,14 +956,19 @@ void fused_verify_kernel(const FusedParams P)
     // draft token X_{i+1} and its two logits: the first wave of the row's last workgroup (the one with the
     // fewest logits) publishes the row's ratio from them
     const bool leader = wave == 0 && wg_x == nwg - 1;
-    u64 rw = 0;
+    // whether the workgroup finds out right after its first sweep if the row's residual mass can matter at all
+    const bool early = chain && !P.debug_out && n_prev > 0;
+    u64 wt = 0;                                              // chain: the word of log2 w_i; else, first wave: lane j's ratio word
     float eta_i = 0.f, eta_next = 0.f;                       // the uniforms of test i (this position's) and test i + 1
     int tok = 0;                                             // the drafted token X_{i+1}, for the leader
     if (wave == 0) {
-        tok = load_uniform(P.tokens + drow);
         eta_i = load_uniform(P.uniforms + seq_u + (n_prev > 0 ? n_prev - 1 : 0));
+        if (chain) { if (n_prev > 0) wt = ld_u64(lw_word); }
+        else wt = ld_u64(SV_RATIO_WORD);
+    }
+    if (wave == 0) {
+        tok = load_uniform(P.tokens + drow);
         eta_next = load_uniform(P.uniforms + seq_u + n_prev);
-        rw = ld_u64(SV_RATIO_WORD);
     }
     if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
 
@@ -947,42 +976,29 @@ void fused_verify_kernel(const FusedParams P)
     float xa[LANE], xb[LANE];
     float shiftA, shiftB;
     unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
-    {
-        const u64 stA = first_sweep_row(xa, k, shiftA);
-        if (lane == 0) { st_u64(W.pstat + trow * nu + U.c, stA); wave_words[0][wave] = stA; }
-    }
+    const u64 stA = first_sweep_row(xa, k, shiftA);
+    if (lane == 0) st_u64(W.pstat + trow * nu + U.c, stA);
     // the two logits of the draft token, asked for only now so that the streams above did not queue behind them
     float ya_f = 0.f, yb_f = 0.f;
     if (leader) { ya_f = logit_as_float(rowA + tok); yb_f = logit_as_float(rowB + tok); }
     unpack_slice<T, ALIGNED, LANE>(rowB, unit_first, V, rawB, xb);
-    {
-        const u64 stB = first_sweep_row(xb, k, shiftB);
-        if (lane == 0) wave_words[1][wave] = stB;
-    }
+    const u64 stB = first_sweep_row(xb, k, shiftB);
+    // the wave's two words meet the other waves' in LDS; the first wave publishes the workgroup's two words and, in
+    // calls larger than one resident set, decides whether this row's residual mass can matter: a row that is not needed
+    // costs its workgroups no wait for the row
+    if (lane == 0) { wave_words[0][wave] = stA; wave_words[1][wave] = stB; }
     __syncthreads();
-
-    // ---- the workgroup's first wave combines the four waves' words into the workgroup's two words and publishes them;
-    // then, in calls where it pays, it decides from the ratios of the earlier positions whether this row's residual mass
-    // can matter at all: a row that is not needed costs its workgroups no wait for the row
-    SeqState st = {};
-    bool have_state = false;
+    double log2w = 0.0;
     if (wave == 0) {
         SV_STAMP(1);
-        StatAcc ga, gq;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) { ga.add(wave_words[0][w]); gq.add(wave_words[1][w]); }
-        if (lane == 0) {
-            st_u64(W.pgrp + drow * nwg + wg_x, pack_stat(ga.m, (float)ga.z));
-            st_u64(W.qgrp + drow * nwg + wg_x, pack_stat(gq.m, (float)gq.z));
+        publish_group_words(wave_words, W.pgrp + drow * nwg + wg_x, W.qgrp + drow * nwg + wg_x);
+        bool wanted = true;
+        if (early) {
+            wt = wait_word(lw_word, wt, true, P.spin_limit, gave_up);
+            log2w = unpack_ratio(read_lane_u64(wt, 0));
+            wanted = gave_up || can_become_tau(P.algo, U.i, log2w, eta_i);
         }
-        bool needed = true;
-        if (n_prev > 0 && P.prune && !P.debug_out) {
-            rw = wait_word(SV_RATIO_WORD, rw, lane < n_prev, P.spin_limit, gave_up);
-            st = seq_state(P.algo, rw, n_prev);
-            have_state = true;
-            needed = gave_up || residual_needed(P, U.i, read_lane_double(st.lw, n_prev - 1), eta_i, st.passed);
-        }
-        if (lane == 0) row_flag = needed ? 1 : 0;
+        if (lane == 0) row_flag = wanted ? 1 : 0;
     }
     __syncthreads();
     const bool needed = row_flag != 0;
@@ -994,27 +1010,29 @@ void fused_verify_kernel(const FusedParams P)
 
     bool candidate = true;           // whether this position can become tau: then its leader draws the token that would follow
     u64 own_word = 0;                // the leader's word of log2 r_{i+1}
+    double lw_next = 0.0;            // the leader's log2 w_{i+1}
     if (wave == 0) {
         // ---- L_p, L_q: the words of all workgroups of the row
         float Mp, Mq;
         double Lp, Lq;
+        const bool need_w = n_prev > 0 && !early;            // w_i still to come: the chain's word, or the ratios
+        const bool need_lane = need_w && (chain || lane < n_prev);
+        const u64 *const w_word = chain ? lw_word : SV_RATIO_WORD;
         if (nwg <= kWave / 2) {
-            // one poll covers the row: the target row's words in lanes 0.., the draft row's in lanes 32.., the ratios
-            // of the earlier positions (if still missing) beside them; the two halves of the wave are then combined
-            // side by side
+            // one poll covers the row: the target row's words in lanes 0.., the draft row's in lanes 32.., what w_i is
+            // made of (if still missing) beside them; the two halves of the wave are then combined side by side
             const int e = lane & 31;
             const bool need = e < nwg;
             const u64 *word = (lane < 32 ? W.pgrp : W.qgrp) + drow * nwg + (need ? e : nwg - 1);
-            const bool need_r = !have_state && lane < n_prev;
             u64 v = ld_u64(word);
             int spins = 0;
-            while (__any((need && v == 0) || (need_r && rw == 0))) {
+            while (__any((need && v == 0) || (need_lane && wt == 0))) {
                 if (++spins > P.spin_limit) { gave_up = true; break; }
                 __builtin_amdgcn_s_sleep(1);
                 if (need && v == 0) v = ld_u64(word);
-                if (need_r && rw == 0) rw = ld_u64(SV_RATIO_WORD);
+                if (need_lane && wt == 0) wt = ld_u64(w_word);
             }
-            if (__any((need && v == kPoison64) || (need_r && rw == kPoison64))) gave_up = true;
+            if (__any((need && v == kPoison64) || (need_lane && wt == kPoison64))) gave_up = true;
             StatAcc acc;
             if (need) acc.add(v);
             halves_max(acc.m, Mp, Mq);
@@ -1029,8 +1047,10 @@ void fused_verify_kernel(const FusedParams P)
             load_row_words<NW>(W.qgrp + drow * nwg, nwg, qw);
             Lp = row_normaliser<NW>(W.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
             Lq = row_normaliser<NW>(W.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
-            if (!have_state) rw = wait_word(SV_RATIO_WORD, rw, lane < n_prev, P.spin_limit, gave_up);
+            if (need_w) wt = wait_word(w_word, wt, need_lane, P.spin_limit, gave_up);
         }
+        if (need_w) log2w = chain ? unpack_ratio(read_lane_u64(wt, 0)) : read_lane_double(weights_from_ratios(P.algo, wt, n_prev), n_prev - 1);
+        candidate = can_become_tau(P.algo, U.i, log2w, eta_i);
         if (leader) {
             // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for every later position and for whoever finishes
             // the sequence.  The sweeps scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To
@@ -1041,17 +1061,17 @@ void fused_verify_kernel(const FusedParams P)
             const double ya = (double)ya_f, yb = (double)yb_f;
             const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
             const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
-            double lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
+            const double lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
             // Alg. 1's test of X_{i+1}, judged here once for everybody: eta_{i+1} < min(r_{i+1}, 1)
             const bool passes = P.algo == kToken && (double)eta_next < exp2(fmin(lr, 0.0));
             own_word = pack_ratio(lr, passes);
+            lw_next = unpack_ratio(pack_ratio(next_weight(P.algo, log2w, unpack_ratio(own_word), passes), false));
             if (gave_up) report_gave_up(P);
-            if (lane == 0) st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
+            if (lane == 0) {
+                st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
+                if (chain) st_u64(W.lw + drow, gave_up ? kPoison64 : pack_ratio(lw_next, false));
+            }
         }
-        if (!have_state) st = seq_state(P.algo, rw, n_prev);
-        double log2w = 0.0;
-        if (n_prev > 0) log2w = read_lane_double(st.lw, n_prev - 1);
-        candidate = can_become_tau(P.algo, U.i, log2w, eta_i, st.passed);
         if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
         if (P.algo == kGreedy) log2w = fmin(log2w, 100.0);          // keeps w p finite in float
         // the second sweep's row constants: w p(x) = 2^(y_p - A) with A = L_p - log2 w, q(x) = 2^(y_q - L_q).  Their
@@ -1069,8 +1089,8 @@ void fused_verify_kernel(const FusedParams P)
     double S_own = 0.0;              // the leader's: S_i, summed over the row's partial sums
     if (needed) {
         __syncthreads();
-        const double Lp = row_values[0], Lq = row_values[1], log2w = row_values[2];
-        const bool poisoned = row_flag == 2;
+        const double Lp = row_values[0], Lq = row_values[1], log2w_row = row_values[2];
+        const bool poisoned = row_flag == 2 || gave_up;
         SV_STAMP(3);
 
         // ---- second sweep, from registers: w p(x) = xa * cp, q(x) = xb * cq with the wave-uniform cp = 2^(shiftA - A),
@@ -1105,7 +1125,7 @@ void fused_verify_kernel(const FusedParams P)
         // only picks both up
         if (!finisher) {
             const float u = load_uniform(P.uniforms + seq_u + gb);
-            const int drawn = draw_from_row<T, ALIGNED, LANE>(P, W, U.b, U.i, 0, candidate, Lp - log2w, Lq, u, S_own, gave_up);
+            const int drawn = draw_from_row<T, ALIGNED, LANE>(P, W, U.b, U.i, 0, candidate, Lp - log2w_row, Lq, u, S_own, gave_up);
             if (gave_up) report_gave_up(P);
             if (lane == 0) st_u64(W.rowres + drow, gave_up ? kPoison64 : pack_rowres((float)S_own, drawn));
             return;
@@ -1116,16 +1136,32 @@ void fused_verify_kernel(const FusedParams P)
     SV_STAMP(5);
     const double Lp = row_values[0], Lq = row_values[1];
     const float u = load_uniform(P.uniforms + seq_u + gb);
+    // what the tests need of the earlier positions, asked for at once: their ratios and (calls larger than one resident
+    // set) the weights their workgroups went by; in smaller calls those came from these same ratios
+    const u64 *const r_word = W.ratio + seq_d + (lane < gb - 1 ? lane : 0);
+    const u64 *const l_word = W.lw + seq_d + (lane > 0 && lane < gb ? lane - 1 : 0);        // lane j: the word of log2 w_j
+    u64 rw_all = gb > 1 ? ld_u64(r_word) : 0, lw_all = chain && gb > 1 ? ld_u64(l_word) : 0;
     // its own row's mass (the draw, if tau turns out to be this position, comes after the tests)
     if (needed) draw_from_row<T, ALIGNED, LANE>(P, W, U.b, U.i, 0, false, 0.0, 0.0, u, S_own, gave_up);
     // the last target row's words, asked for early: they are waited for before the sequence's call count moves on
     const int e_lane = lane < nu ? lane : nu - 1;
     const u64 *last = W.pstat + (seq_u + gb) * nu;
     const u64 last_first = ld_u64(last + e_lane);
+    rw_all = wait_word(r_word, rw_all, lane < gb - 1, P.spin_limit, gave_up);
+    if (lane == gb - 1) rw_all = own_word;
+    // lane j: log2 w_{j+1} as position j + 1's workgroups saw it (lane gb - 1: this wave's own w_{gb})
+    double lw_seen;
+    if (chain) {
+        lw_all = wait_word(l_word, lw_all, lane > 0 && lane < gb, P.spin_limit, gave_up);
+        const double lw_j = lane > 0 && lane < gb ? unpack_ratio(lw_all) : 0.0;           // lane j: log2 w_j
+        lw_seen = __shfl_down(lw_j, 1, kWave);
+        if (lane == gb - 1) lw_seen = lw_next;
+    } else {
+        lw_seen = weights_from_ratios(P.algo, rw_all, gb);
+    }
     int y = -1;
     double lw_own;
-    // lane j: the word of log2 r_{j+1}; the last one is this wave's own
-    const int tau = finish_sequence(P, W, U.b, gb, lane == gb - 1 ? own_word : rw, (float)S_own, y, lw_own, gave_up, stamps);
+    const int tau = finish_sequence(P, W, U.b, gb, rw_all, lw_seen, (float)S_own, y, lw_own, gave_up, stamps);
     if (y < 0) {
         // tau is the last row pair (its residual: this wave has the row's constants) or every token was
         // accepted (Y comes from the last target row itself)
