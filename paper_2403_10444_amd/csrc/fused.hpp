@@ -84,7 +84,8 @@ struct Words {
                           //                          the leader of row pair i
     u64 *rowres;          // [B, gamma]               low half: S_i as float bits; high half: the token drawn from row pair i's
                           //                          residual + 2, or 1 if none was drawn; by the leader of row pair i
-    u64 *pstat;           // [B, gamma+1, nu]         packed (shift, sum) per wave chunk of a target row
+    u64 *pstat;           // [B, gamma, nu]           (largest scaled logit, sum) per wave chunk of a row pair's target row
+    u64 *plast;           // [B, nu]                  the same of the sequence's last target row (row draft_lens[b])
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
 };
@@ -127,7 +128,7 @@ __device__ __forceinline__ Words words_of(const FusedParams &P, unsigned copy)
 {
     const size_t off = copy ? P.copy_bytes : 0;
     Words W;
-    W.ratio = shifted(P.words.ratio, off); W.lw = shifted(P.words.lw, off); W.rowres = shifted(P.words.rowres, off); W.pstat = shifted(P.words.pstat, off);
+    W.ratio = shifted(P.words.ratio, off); W.lw = shifted(P.words.lw, off); W.rowres = shifted(P.words.rowres, off); W.pstat = shifted(P.words.pstat, off); W.plast = shifted(P.words.plast, off);
     W.pgrp = shifted(P.words.pgrp, off); W.qgrp = shifted(P.words.qgrp, off); W.spart = shifted(P.words.spart, off);
     return W;
 }
@@ -577,13 +578,13 @@ __device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float 
 // ------------------------------------------------------------------ the draw of a token
 // Row `row` of sequence b (one wave).  First the sum of the weights: mode 0, the residual max(w p - q, 0) of row pair
 // `row`, by the partial sums per wave chunk that the pair's units publish (polled here until all are there); mode 1,
-// p_row itself, by the target row's (shift, sum) words.  `total_out` gets that sum (mode 0: S_row).  Then, if
+// p_row itself, by the target row's words `st` (one per wave chunk).  `total_out` gets that sum (mode 0: S_row).  Then, if
 // `want_draw`, the inverse-CDF draw in index order, first token whose running sum exceeds u * total: the wave chunk
 // that holds it by a scan over the chunks' sums, then the token by the weights of that one chunk, formed again from
 // the logits with alpha_p = L_p - log2 w and alpha_q = L_q.  A residual without any mass is drawn from p_row
 // instead.  Returns the token, or -1 if none was asked for.
 template <typename T, bool ALIGNED, int LANE>
-__device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &W, int b, int row, int mode, bool want_draw,
+__device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &W, const u64 *st, int b, int row, int mode, bool want_draw,
                                              double alpha_p, double alpha_q, float u, double &total_out, bool &gave_up)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
@@ -596,7 +597,6 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &
     const T *draft = static_cast<const T *>(P.draft);
     const size_t base = (size_t)b * (G + 1);
     const size_t drow = (size_t)b * G + (mode == 0 ? row : 0);
-    const u64 *st = W.pstat + (base + row) * nu;
     const unsigned *sp = W.spart + drow * nu;
 
     // ---- first the wave chunk that holds t = u * total ...
@@ -811,16 +811,17 @@ __device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words
 }
 
 // Clears the words of row slot `slot` of sequence b in one copy (one wave, all lanes, whole rows at a time: full
-// cache lines).  Slot gamma holds row gamma of the target rows' words and nothing else.
+// cache lines).  Slot gamma holds the words of the sequence's last target row and nothing else.
 __device__ __forceinline__ void clear_row_words(const FusedParams &P, const Words &W, int b, int slot)
 {
     const int lane = threadIdx.x & 63;
     const int G = P.gamma, nu = P.nu, nwg = nu / kWaves;
-    u64 *pstat = W.pstat + ((size_t)b * (G + 1) + slot) * nu;
-    for (int e = lane; e < nu; e += kWave) st_u64(pstat + e, 0);
-    if (slot == G) return;
+    if (slot == G) {
+        for (int e = lane; e < nu; e += kWave) st_u64(W.plast + (size_t)b * nu + e, 0);
+        return;
+    }
     const size_t drow = (size_t)b * G + slot;
-    for (int e = lane; e < nu; e += kWave) st_u32(W.spart + drow * nu + e, 0);
+    for (int e = lane; e < nu; e += kWave) { st_u64(W.pstat + drow * nu + e, 0); st_u32(W.spart + drow * nu + e, 0); }
     for (int e = lane; e < nwg; e += kWave) { st_u64(W.pgrp + drow * nwg + e, 0); st_u64(W.qgrp + drow * nwg + e, 0); }
     if (lane == 0) { st_u64(W.ratio + drow, 0); st_u64(W.lw + drow, 0); st_u64(W.rowres + drow, 0); }
 }
@@ -941,7 +942,7 @@ void fused_verify_kernel(const FusedParams P)
             __syncthreads();
             const int flag = row_flag;
             if (flag != 0) {
-                if (lane == 0) st_u64(W.pstat + trow * nu + U.c, flag == 2 ? kPoison64 : pack_stat(-INFINITY, 0.f));
+                if (lane == 0) st_u64(W.plast + (size_t)U.b * nu + U.c, flag == 2 ? kPoison64 : pack_stat(-INFINITY, 0.f));
                 return;
             }
         }
@@ -949,7 +950,7 @@ void fused_verify_kernel(const FusedParams P)
         float xa[LANE], shiftA;
         unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
         const u64 stA = first_sweep_row(xa, k, shiftA);
-        if (lane == 0) st_u64(W.pstat + trow * nu + U.c, stA);
+        if (lane == 0) st_u64(W.plast + (size_t)U.b * nu + U.c, stA);
         return;
     }
 
@@ -977,7 +978,7 @@ void fused_verify_kernel(const FusedParams P)
     float shiftA, shiftB;
     unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
     const u64 stA = first_sweep_row(xa, k, shiftA);
-    if (lane == 0) st_u64(W.pstat + trow * nu + U.c, stA);
+    if (lane == 0) st_u64(W.pstat + drow * nu + U.c, stA);
     // the two logits of the draft token, asked for only now so that the streams above did not queue behind them
     float ya_f = 0.f, yb_f = 0.f;
     if (leader) { ya_f = logit_as_float(rowA + tok); yb_f = logit_as_float(rowB + tok); }
@@ -1125,7 +1126,7 @@ void fused_verify_kernel(const FusedParams P)
         // only picks both up
         if (!finisher) {
             const float u = load_uniform(P.uniforms + seq_u + gb);
-            const int drawn = draw_from_row<T, ALIGNED, LANE>(P, W, U.b, U.i, 0, candidate, Lp - log2w_row, Lq, u, S_own, gave_up);
+            const int drawn = draw_from_row<T, ALIGNED, LANE>(P, W, W.pstat + drow * nu, U.b, U.i, 0, candidate, Lp - log2w_row, Lq, u, S_own, gave_up);
             if (gave_up) report_gave_up(P);
             if (lane == 0) st_u64(W.rowres + drow, gave_up ? kPoison64 : pack_rowres((float)S_own, drawn));
             return;
@@ -1142,10 +1143,10 @@ void fused_verify_kernel(const FusedParams P)
     const u64 *const l_word = W.lw + seq_d + (lane > 0 && lane < gb ? lane - 1 : 0);        // lane j: the word of log2 w_j
     u64 rw_all = gb > 1 ? ld_u64(r_word) : 0, lw_all = chain && gb > 1 ? ld_u64(l_word) : 0;
     // its own row's mass (the draw, if tau turns out to be this position, comes after the tests)
-    if (needed) draw_from_row<T, ALIGNED, LANE>(P, W, U.b, U.i, 0, false, 0.0, 0.0, u, S_own, gave_up);
+    if (needed) draw_from_row<T, ALIGNED, LANE>(P, W, W.pstat + drow * nu, U.b, U.i, 0, false, 0.0, 0.0, u, S_own, gave_up);
     // the last target row's words, asked for early: they are waited for before the sequence's call count moves on
     const int e_lane = lane < nu ? lane : nu - 1;
-    const u64 *last = W.pstat + (seq_u + gb) * nu;
+    const u64 *last = W.plast + (size_t)U.b * nu;
     const u64 last_first = ld_u64(last + e_lane);
     rw_all = wait_word(r_word, rw_all, lane < gb - 1, P.spin_limit, gave_up);
     if (lane == gb - 1) rw_all = own_word;
@@ -1166,7 +1167,7 @@ void fused_verify_kernel(const FusedParams P)
         // tau is the last row pair (its residual: this wave has the row's constants) or every token was
         // accepted (Y comes from the last target row itself)
         double total;
-        y = draw_from_row<T, ALIGNED, LANE>(P, W, U.b, tau, tau == gb ? 1 : 0, true, Lp - lw_own, Lq, u, total, gave_up);
+        y = draw_from_row<T, ALIGNED, LANE>(P, W, tau == gb ? last : W.pstat + drow * nu, U.b, tau, tau == gb ? 1 : 0, true, Lp - lw_own, Lq, u, total, gave_up);
     }
     SV_STAMP(12);
     // every workgroup of the sequence has read the call count once the last target row's words are there (the row

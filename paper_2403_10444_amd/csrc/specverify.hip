@@ -39,7 +39,7 @@ struct Layout {
     size_t fused_grid;            // workgroups of the fused kernel
     size_t control_words;         // header, call counts and both copies of the words that cross waves: in ints, at offset 0
     size_t off_gen, copy_bytes;   // the call counts; bytes from one copy of the words to the other
-    size_t off_ratio, off_lw, off_rowres, off_pstat, off_pgrp, off_qgrp, off_spart;     // copy 0
+    size_t off_ratio, off_lw, off_rowres, off_pstat, off_plast, off_pgrp, off_qgrp, off_spart;     // copy 0
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -64,7 +64,8 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.off_ratio = off;  off += rows_d * sizeof(u64);
     L.off_lw = off;     off += rows_d * sizeof(u64);
     L.off_rowres = off; off += rows_d * sizeof(u64);
-    L.off_pstat = off;  off += rows_t * L.nu * sizeof(u64);
+    L.off_pstat = off;  off += rows_d * L.nu * sizeof(u64);
+    L.off_plast = off;  off += (size_t)B * L.nu * sizeof(u64);
     L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_qgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
@@ -221,6 +222,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.words.lw = reinterpret_cast<u64 *>(ws + L.off_lw);
     P.words.rowres = reinterpret_cast<u64 *>(ws + L.off_rowres);
     P.words.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
+    P.words.plast = reinterpret_cast<u64 *>(ws + L.off_plast);
     P.words.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
     P.words.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
     P.words.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
