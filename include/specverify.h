@@ -52,7 +52,8 @@ typedef enum {
     SV_ERR_UNSUPPORTED = 2,          /* gamma above SV_MAX_GAMMA, or sizes that overflow 32-bit grids  */
     SV_ERR_WORKSPACE_TOO_SMALL = 3,
     SV_ERR_HIP = 4,                  /* a launch or copy failed; see hipGetLastError                   */
-    SV_ERR_INTERNAL = 5              /* workspace_check: a bounded wait inside a kernel ran out        */
+    SV_ERR_INTERNAL = 5,             /* workspace_check: a bounded wait inside a kernel ran out        */
+    SV_ERR_STATIC_SCRATCH_TOO_SMALL = 6  /* spec_verify_ex_noalloc: sizes beyond SV_STATIC_SCRATCH_BYTES  */
 } sv_status_t;
 
 typedef enum { SV_DTYPE_F32 = 0, SV_DTYPE_BF16 = 1 } sv_dtype_t;
@@ -198,6 +199,27 @@ sv_status_t spec_verify_ex(sv_algo_t algo, const void *target_logits, const void
                            int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype,
                            float temperature, void *workspace, size_t workspace_bytes,
                            int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream);
+
+/*
+ * spec_verify_ex for callers that cannot allocate device memory or keep a workspace of their own: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace; the
+ * verification's scratch memory is an array of SV_STATIC_SCRATCH_BYTES inside the library's code object instead.  Every
+ * GPU that the library runs on holds one copy of it until the process ends.  The call allocates and frees nothing
+ * (its first use on a device looks the array's address up).  SV_ERR_STATIC_SCRATCH_TOO_SMALL when
+ * spec_verify_workspace_bytes(B, gamma, V) exceeds SV_STATIC_SCRATCH_BYTES (32 MiB: B = 256, gamma = 16, V = 152064 needs
+ * 12 MiB and fits; B = 1024, gamma = 8, V = 256000 needs 40 MiB and does not).
+ * All calls on one GPU share that one array, which keeps whatever the last call left: when the shape (B, gamma, V)
+ * differs from the previous call's on that device, a small kernel that prepares the control words goes onto `stream`
+ * in front of the verification (so the first call of a shape launches two kernels); calls that overlap on one GPU -
+ * from two streams or two threads - race on the array and give undefined results.  A call whose kernel gave up a wait
+ * (accept_len -1) leaves the array unusable until a call with another shape has run.
+ */
+#define SV_STATIC_SCRATCH_BYTES (32u << 20)
+sv_status_t spec_verify_ex_noalloc(sv_algo_t algo, const void *target_logits, const void *draft_logits,
+                                   const int32_t *draft_tokens, const int32_t *draft_lens,
+                                   int64_t target_row_stride, int64_t draft_row_stride, const float *uniforms,
+                                   int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype, float temperature,
+                                   int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream);
 
 /*
  * The three algorithms with the distributions themselves as inputs, the form of the arrays in the

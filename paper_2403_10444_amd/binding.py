@@ -22,6 +22,8 @@ SV_ERR_UNSUPPORTED = 2
 SV_ERR_WORKSPACE_TOO_SMALL = 3
 SV_ERR_HIP = 4
 SV_ERR_INTERNAL = 5
+SV_ERR_STATIC_SCRATCH_TOO_SMALL = 6
+SV_STATIC_SCRATCH_BYTES = 32 << 20
 SV_DTYPE_F32 = 0
 SV_DTYPE_BF16 = 1
 
@@ -36,6 +38,7 @@ EXPORTED = (
     "spec_verify_token",
     "spec_verify_greedy",
     "spec_verify_ex",
+    "spec_verify_ex_noalloc",
     "spec_verify_probs",
     "spec_verify_status_string",
 )
@@ -74,6 +77,8 @@ def load() -> ctypes.CDLL:
         lib.spec_verify_ex.restype = ctypes.c_int
         lib.spec_verify_ex.argtypes = ([ctypes.c_int] + _VERIFY_ARGTYPES[:3]
                                        + [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64] + _VERIFY_ARGTYPES[3:])
+        lib.spec_verify_ex_noalloc.restype = ctypes.c_int
+        lib.spec_verify_ex_noalloc.argtypes = [a for j, a in enumerate(lib.spec_verify_ex.argtypes) if j not in (13, 14)]   # no workspace
         lib.spec_verify_probs.restype = ctypes.c_int
         lib.spec_verify_probs.argtypes = [a for j, a in enumerate(lib.spec_verify_ex.argtypes) if j != 12]   # no temperature
         lib.spec_verify_workspace_init.restype = ctypes.c_int
@@ -216,14 +221,15 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
     for t, want in ((draft_tokens, torch.int32), (uniforms, torch.float32)):
         if t.dtype != want:
             raise TypeError(f"expected {want}, got {t.dtype}")
-    extended = name in ("spec_verify_ex", "spec_verify_probs")
+    extended = name in ("spec_verify_ex", "spec_verify_ex_noalloc", "spec_verify_probs")
+    own_workspace = name != "spec_verify_ex_noalloc"
     for t in (target_logits, draft_logits, draft_tokens, uniforms):
         if t.device != dev:
             raise ValueError("inputs must be on one device")
     for t in (draft_tokens, uniforms) + (() if extended else (target_logits, draft_logits)):
         if not t.is_contiguous():
             raise ValueError("inputs must be contiguous")
-    if workspace is None:
+    if workspace is None and own_workspace:
         workspace = alloc_workspace(B, gamma, V, dev)
     if accept_len is None:
         accept_len = torch.empty(B, dtype=torch.int32, device=dev)
@@ -244,7 +250,7 @@ def _call(name, target_logits, draft_logits, draft_tokens, uniforms, temperature
         *head, target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), *after_tokens,
         uniforms.data_ptr(),
         B, gamma, V, _dtype_code(target_logits), *(() if name == "spec_verify_probs" else (float(temperature),)),
-        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        *((workspace.data_ptr(), workspace.numel() * workspace.element_size()) if own_workspace else ()),
         accept_len.data_ptr(), next_token.data_ptr(),
         debug_out.data_ptr() if debug_out is not None else None, stream)
     if code != SV_OK:
@@ -259,6 +265,16 @@ def spec_verify_ex(algo, target_logits, draft_logits, draft_tokens, uniforms, te
     padded (the row strides are taken from the tensors)."""
     return _call("spec_verify_ex", target_logits, draft_logits, draft_tokens, uniforms, temperature,
                  draft_lens=draft_lens, algo=algo, **kw)
+
+
+def spec_verify_ex_noalloc(algo, target_logits, draft_logits, draft_tokens, uniforms, temperature, accept_len, next_token,
+                           draft_lens=None, debug_out=None, stream=None):
+    """`spec_verify_ex` on the library's built-in scratch memory instead of a workspace (see the header): the call
+    allocates nothing, so the outputs must be preallocated int32 device tensors [B].  Calls on one GPU must not
+    overlap."""
+    return _call("spec_verify_ex_noalloc", target_logits, draft_logits, draft_tokens, uniforms, temperature,
+                 accept_len=accept_len, next_token=next_token, debug_out=debug_out, stream=stream,
+                 draft_lens=draft_lens, algo=algo)
 
 
 def spec_verify_probs(algo, target_probs, draft_probs, draft_tokens, uniforms, draft_lens=None, **kw):

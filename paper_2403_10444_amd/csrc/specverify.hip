@@ -9,6 +9,7 @@
 #include <stdint.h>
 #include <math.h>
 #include <atomic>
+#include <mutex>
 #include <stdlib.h>
 
 #include "../../include/specverify.h"
@@ -292,6 +293,19 @@ sv_status_t verify_entry(int algo, bool probs, const void *target, const void *d
 #undef SV_ARGS
 }
 
+// ---- the workspace of spec_verify_ex_noalloc: device memory that belongs to the library's code object, one copy per
+// GPU that runs it, alive until the process ends.  The name below is only a handle for hipGetSymbolAddress: the
+// address that kernels get is looked up once per device and kept.
+__device__ __align__(256) unsigned char g_static_scratch[SV_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+    void *ptr = nullptr;                 // the array's address on this device
+    int32_t B = 0, gamma = 0, V = 0;     // the shape its control words were last prepared for (0: never)
+};
+std::mutex g_static_mutex;
+StaticScratch g_static[kMaxDevices];
+
 }  // namespace
 
 extern "C" {
@@ -434,6 +448,45 @@ sv_status_t spec_verify_probs(sv_algo_t algo, const void *target_probs, const vo
                         debug_out, stream);
 }
 
+sv_status_t spec_verify_ex_noalloc(sv_algo_t algo, const void *target_logits, const void *draft_logits,
+                                   const int32_t *draft_tokens, const int32_t *draft_lens,
+                                   int64_t target_row_stride, int64_t draft_row_stride, const float *uniforms,
+                                   int32_t B, int32_t gamma, int32_t V, sv_dtype_t dtype, float temperature,
+                                   int32_t *accept_len, int32_t *next_token, float *debug_out, void *stream)
+{
+    if (algo != SV_ALGO_BLOCK && algo != SV_ALGO_TOKEN && algo != SV_ALGO_GREEDY) return SV_ERR_INVALID_ARG;
+    if (B < 1 || gamma < 1 || V < 1) return SV_ERR_INVALID_ARG;
+    Layout L;
+    if (!make_layout(B, gamma, V, L)) return SV_ERR_UNSUPPORTED;
+    if (L.total > (size_t)SV_STATIC_SCRATCH_BYTES) return SV_ERR_STATIC_SCRATCH_TOO_SMALL;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SV_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return SV_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        StaticScratch &st = g_static[dev];
+        if (!st.ptr) {
+            // once per device, with that device current: every GPU holds its own copy of the array at its own address
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) return SV_ERR_HIP;
+            st.ptr = p;
+        }
+        ws = st.ptr;
+        if (st.B != B || st.gamma != gamma || st.V != V) {
+            // the array keeps what the last call left: its control words are prepared again whenever the shape changes
+            // (a kernel on the caller's stream, in front of the verification's)
+            const sv_status_t rc = spec_verify_workspace_init(ws, SV_STATIC_SCRATCH_BYTES, B, gamma, V, stream);
+            if (rc != SV_OK) return rc;
+            st.B = B; st.gamma = gamma; st.V = V;
+        }
+    }
+    const int a = algo == SV_ALGO_BLOCK ? kBlock : algo == SV_ALGO_TOKEN ? kToken : kGreedy;
+    return verify_entry(a, false, target_logits, draft_logits, draft_tokens, draft_lens, target_row_stride, draft_row_stride,
+                        uniforms, B, gamma, V, dtype, temperature, ws, SV_STATIC_SCRATCH_BYTES, accept_len, next_token,
+                        debug_out, stream);
+}
+
 const char *spec_verify_status_string(sv_status_t status)
 {
     switch (status) {
@@ -443,6 +496,7 @@ const char *spec_verify_status_string(sv_status_t status)
     case SV_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case SV_ERR_HIP: return "HIP call failed";
     case SV_ERR_INTERNAL: return "a bounded wait inside the kernel ran out";
+    case SV_ERR_STATIC_SCRATCH_TOO_SMALL: return "the sizes need more than the library's built-in scratch memory";
     }
     return "unknown status";
 }
