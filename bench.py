@@ -67,6 +67,8 @@ def main():
                     help="probs: the same workload handed over as probabilities (spec_verify_probs); a side "
                          "measurement, the headline metric is quoted on logits")
     ap.add_argument("--sets", type=int, default=4, help="distinct input sets rotated through")
+    ap.add_argument("--sigma-draft", type=float, default=None,
+                    help="draft noise of the workload (configuration 4 is swept over 0.5, 1.5, 3.0; 0.5 = high acceptance)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", default="default", choices=["default", "staged", "fused", "fused-small", "fused-large"],
                     help="kernel path (testing hook of the library)")
@@ -91,6 +93,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = workloads.CONFIGS[args.config]
+    if args.sigma_draft is not None:
+        cfg = workloads.with_overrides(cfg, sigma_draft=args.sigma_draft, name=f"{cfg.name}_sigma{args.sigma_draft}")
     fn = {"block": sv.spec_verify_block, "token": sv.spec_verify_token, "greedy": sv.spec_verify_greedy}[args.algo]
 
     sets = [workloads.generate(cfg, seed=9000 + s, device=dev) for s in range(args.sets)]
@@ -122,18 +126,71 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    def timed(n, fn_step):
+        """n calls back to back on the stream: (wall seconds, device milliseconds per call by HIP events on that stream)."""
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for i in range(n):
+            fn_step(i)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ev0.elapsed_time(ev1) / n
+
+    def healthy(what):
+        """No number from a run whose kernels did not do the work: the workspace's error word must be clear and every
+        sequence must have a result."""
+        code = sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V)
+        if args.input == "logits" and args.path != "staged" and code != 0:
+            print(f"bench.py: {what}: workspace check failed ({sv.status_string(code)}); no result", file=sys.stderr)
+            sys.exit(3)
+        if bool((tau < 0).any()) or bool((y < 0).any()) or bool((tau > cfg.gamma).any()) or bool((y >= cfg.V).any()):
+            print(f"bench.py: {what}: outputs out of range; no result", file=sys.stderr)
+            sys.exit(3)
+
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for i in range(args.steps):
-        step(i)
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    dev_ms = ev0.elapsed_time(ev1) / args.steps          # device time per call, HIP events on the launch stream
+    wall, dev_ms = timed(args.steps, step)
+    healthy("timed region")
+    mean_tau = float(tau.float().mean().item())
+
+    # What the measured time depends on besides the bytes: the kernels leave out residual masses that cannot matter
+    # (positions whose test fails whatever S_i is) and do not read a last target row that cannot be drawn from.  So the
+    # same kernel is also timed with every S_i formed (the debug block asks for them), and the share of what was left
+    # out on this workload is reported beside it.
+    extra = {}
+    if args.input == "logits":
+        dbg = torch.empty((cfg.B, cfg.gamma + 1, 3), dtype=torch.float32, device=dev)
+
+        def step_all(i):
+            s = sets[i % len(sets)]
+            fn(s["target_logits"], s["draft_logits"], s["draft_tokens"], s["uniforms"], cfg.temperature,
+               workspace=ws, accept_len=tau, next_token=y, debug_out=dbg, stream=stream.cuda_stream)
+
+        n_all = max(args.steps // 4, 1)
+        for i in range(min(args.warmup, 10)):
+            step_all(i)
+        _, dev_ms_all = timed(n_all, step_all)
+        healthy("timed region with every residual mass formed")
+        left_out, last_skipped = [], []
+        for i, s in enumerate(sets):
+            step_all(i)
+            torch.cuda.synchronize()
+            w = dbg[..., 0].double()                       # w_0 .. w_gamma as the kernel formed them
+            eta = s["uniforms"][:, :cfg.gamma].double()    # eta_1 .. eta_gamma
+            if args.algo == "token":
+                h = dbg[:, 1:, 2].double()                  # min(r_i, 1)
+                alive = torch.cumprod((eta < h).to(torch.int32), dim=1).bool()      # tests 1..i all passed
+            else:
+                alive = torch.log2(eta.clamp_min(1e-45)) < torch.log2(w[:, 1:].clamp_min(1e-300)) + 1e-3
+            # row pair i (0 <= i < gamma) keeps its second sweep iff position i can become tau; position 0 always can
+            left_out.append(float((~alive[:, :cfg.gamma - 1]).sum().item()) / (cfg.B * cfg.gamma))
+            last_skipped.append(float((~alive[:, cfg.gamma - 1]).float().mean().item()))
+        extra = {"frac_all_S": cfg.algorithmic_bytes / (dev_ms_all * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "device_ms_per_launch_all_S": dev_ms_all,
+                 "pruned_row_pairs": sum(left_out) / len(left_out),
+                 "last_target_rows_not_read": sum(last_skipped) / len(last_skipped)}
 
     ms_per_step = wall / args.steps * 1e3
     calls_per_s = args.steps / wall
@@ -147,7 +204,7 @@ def main():
                    "logit_dtype": cfg.dtype, "temperature": cfg.temperature, "input_sets": len(sets), "path": args.path,
                    "input": args.input},
         "seq_verifications_per_s": calls_per_s * cfg.B,
-        "mean_accept_len": float(tau.float().mean().item()),
+        "mean_accept_len": mean_tau,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(cfg.name, args.algo)
@@ -155,7 +212,7 @@ def main():
                      "kernel": "whole call: fused_verify_kernel, the call's only kernel on the default path "
                                "(four staged kernels with --path staged)" if args.input == "logits" else
                                "whole call: probs_weights_kernel, probs_residual_kernel, probs_finalize_kernel",
-                     "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms},
+                     "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms, **extra},
     }
     if not args.no_cpu_baseline and args.input == "logits":
         out["cpu_baseline"] = cpu_baseline(cfg, sets[0])

@@ -103,8 +103,10 @@ struct FusedParams {
     int algo;
     int nu;               // units (wave chunks) per row = 4 * workgroups per row
     int group_seqs;       // sequences per group of the row order
+    unsigned inv_slots, inv_wpr;   // floor(2^32 / d) + 1 for d = gamma + 1 and d = workgroups per row: n / d = mulhi(n, .) for the n that occur
     int prune;            // leave out what cannot matter (residual_needed, the last target row); off for calls so small
                           // that all positions run at once, where asking for the ratios first only lengthens the chain
+    int skip_last;        // the last target row is read only where every token can be accepted (its workgroups ask first)
     int spin_limit;
     int resident;         // workgroups of this kernel that the device holds at once
     float pace;           // see pace_first_generation: waits of 64 clocks per row of the first resident set (0: none)
@@ -228,6 +230,27 @@ __device__ __forceinline__ double exp2_precise(double x)
     s = s * t + 1.0;
     s = s * t + 1.0;
     return ldexp(s, (int)n);
+}
+
+// 1 - 2^x for x <= 0 without the cancellation next to x = 0: the series of -expm1(x ln 2) where |x ln 2| < 0.35.
+__device__ __forceinline__ double one_minus_exp2(double x)
+{
+    const double t = x * 0.69314718055994530942;
+    if (t > -0.35) {
+        double s = 1.0 / 39916800.0;
+        s = s * t + 1.0 / 3628800.0;
+        s = s * t + 1.0 / 362880.0;
+        s = s * t + 1.0 / 40320.0;
+        s = s * t + 1.0 / 5040.0;
+        s = s * t + 1.0 / 720.0;
+        s = s * t + 1.0 / 120.0;
+        s = s * t + 1.0 / 24.0;
+        s = s * t + 1.0 / 6.0;
+        s = s * t + 0.5;
+        s = s * t + 1.0;
+        return -(s * t);
+    }
+    return 1.0 - exp2_precise(x);
 }
 
 // log2 of a positive double to an absolute error below 1e-12: the hardware's float log2 as a first guess g (off by
@@ -462,12 +485,13 @@ struct Unit {
 __device__ __forceinline__ bool decode_unit(const FusedParams &P, int wave, Unit &U, int &x)
 {
     int grp = 0, slot = blockIdx.z;
-    if (P.B > P.group_seqs) { grp = blockIdx.z / (P.gamma + 1); slot = blockIdx.z - grp * (P.gamma + 1); }
+    if (P.B > P.group_seqs) { grp = (int)__umulhi(blockIdx.z, P.inv_slots); slot = blockIdx.z - grp * (P.gamma + 1); }
     U.b = grp * P.group_seqs + blockIdx.y;
     // which of the row's workgroups takes which chunk rotates from row to row: a row's workgroups go to the
     // XCDs round-robin, and the last chunk (fewest logits, leader's duties) must not always meet the same XCD
     const int wpr = P.nu / kWaves;                        // (= gridDim.x)
-    x = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % wpr);
+    const unsigned turn = blockIdx.x + blockIdx.y + blockIdx.z;
+    x = wpr == 1 ? 0 : (int)(turn - __umulhi(turn, P.inv_wpr) * (unsigned)wpr);      // (2^32 / 1 + 1 does not fit the word)
     U.c = x * kWaves + wave;
     U.last_row = slot == P.gamma;
     U.i = slot;
@@ -762,9 +786,9 @@ __device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words
     const u64 have = __ballot(j < gamma && residual_needed(P, j, lw_j, eta));
     if (P.algo == kGreedy) lw_j = fmin(lw_j, 100.0);
     if (P.algo == kToken) lw_j = 0.0;
-    const double w_j = exp2(lw_j);
-    const double one_minus_w = -expm1(lw_j * 0.69314718055994530942);
-    const double h_token = exp2(fmin(lr, 0.0));         // min(r_j, 1), for the debug block
+    const double w_j = exp2_precise(lw_j);
+    const double one_minus_w = one_minus_exp2(fmin(lw_j, 0.0));
+    const double h_token = exp2_precise(fmin(lr, 0.0)); // min(r_j, 1), for the debug block
     SV_STAMP(8);
 
     // ---- S_i of position i into lane i: position 0 and every position of `have` publish theirs
@@ -931,7 +955,7 @@ void fused_verify_kernel(const FusedParams P)
         // calls large enough for it to pay, its workgroups first look at w_gamma: where eta_gamma >= w_gamma (Alg. 1:
         // where some test fails) the row is not read at all, and its words say "no mass here".
         if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
-        if (chain) {
+        if (P.skip_last) {
             if (wave == 0) {
                 const float eta_g = load_uniform(P.uniforms + seq_u + gb - 1);
                 const u64 wt = wait_word(lw_word, P.spin_limit, gave_up);
@@ -1064,7 +1088,7 @@ void fused_verify_kernel(const FusedParams P)
             const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
             const double lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
             // Alg. 1's test of X_{i+1}, judged here once for everybody: eta_{i+1} < min(r_{i+1}, 1)
-            const bool passes = P.algo == kToken && (double)eta_next < exp2(fmin(lr, 0.0));
+            const bool passes = P.algo == kToken && (double)eta_next < exp2_precise(fmin(lr, 0.0));
             own_word = pack_ratio(lr, passes);
             lw_next = unpack_ratio(pack_ratio(next_weight(P.algo, log2w, unpack_ratio(own_word), passes), false));
             if (gave_up) report_gave_up(P);

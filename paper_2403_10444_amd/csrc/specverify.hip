@@ -202,6 +202,8 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.tstride = tstride; P.dstride = dstride;
     P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
     P.nu = nu;
+    P.inv_slots = (unsigned)(0x100000000ull / (unsigned)(gamma + 1)) + 1u;
+    P.inv_wpr = (unsigned)(0x100000000ull / (unsigned)(nu / kWaves)) + 1u;
     // groups of sequences so large that one position of a group fills the device at least once
     const int min_seqs = (capacity + wpr - 1) / wpr;
     const int groups = B / min_seqs > 1 ? B / min_seqs : 1;
@@ -211,6 +213,10 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     const dim3 grid((unsigned)wpr, (unsigned)P.group_seqs, (unsigned)(n_groups * (gamma + 1)));
     // (the testing hook's forced unit sizes also force the pruning, so that small test shapes exercise it)
     P.prune = g_lane.load() != 0 || (size_t)wpr * P.group_seqs * n_groups * (gamma + 1) > (size_t)capacity ? 1 : 0;
+    {
+        static const int mode = [] { const char *e = getenv("SPECVERIFY_SKIP_LAST"); return e ? atoi(e) : 2; }();
+        P.skip_last = P.prune && (mode == 2 || (mode == 1 && n_groups == 1)) ? 1 : 0;
+    }
     P.spin_limit = g_spin_limit.load();
     P.resident = capacity;
     // pacing of the first resident set (only where there is a second one): one row pair's bytes at about 6 TB/s, in

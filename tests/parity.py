@@ -12,14 +12,25 @@ import workloads
 # boundary (|eta_i - h_i| for the tests that fixed tau; distance of u*total to the edge of the
 # chosen token's CDF cell, relative to the total).
 MARGIN = 1e-6
-# Residual masses: relative tolerance, plus a floor proportional to w_i.  The floor is what
-# fp32 cancels away when w p and q nearly agree on the tokens that carry the mass (S << w):
-# a term w p(x) - q(x) is formed from two hardware exp2 (1 ulp = 2^-23 each) and about four
-# roundings (2^-24 each), so its absolute error is at most ~4.8e-7 * (w p(x) + q(x)); over
-# the active tokens (w p > q) both sums are at most w, which bounds the row's error by
-# ~1e-6 * w, and the fp32 normalisers add a common factor error of a few 1e-7 on top.
+# Residual masses: 1e-5 relative, plus a floor proportional to w_i for the rows where S_i is a small difference of
+# large numbers (S_i << w_i: w_i p_i and q_i nearly agree on the tokens that carry the mass).  There fp32 cannot give
+# 1e-5 of S_i: the row's two normalisers and w_i itself come out of fp32 sums of hardware exp2 values and are good to
+# about 1e-7 relative each, and an error of that size in w_i or a normaliser moves S_i by that fraction of the whole
+# active mass (<= w_i), whatever S_i is.  Measured over the five configurations: |dS| <= 4.5e-7 w_i, 99 % of rows below
+# 1.8e-7 w_i.  Every comparison counts the rows that are outside 1e-5 relative (and so pass by the floor only); the
+# counts per configuration are written out at the end of a test session (see record()).
 S_RTOL = 1e-5
-S_FLOOR = 1.5e-6
+S_FLOOR = 6e-7
+
+# reports of this session's comparisons, for the per-configuration summaries
+RECORDS = []
+
+
+def record(report):
+    """Keeps a comparison's report for the summaries that tests/conftest.py writes when the session ends."""
+    RECORDS.append(dict(report))
+    return report
+
 
 ALGOS = {"block": (oracle.BLOCK, sv.spec_verify_block),
          "token": (oracle.TOKEN, sv.spec_verify_token),
@@ -73,15 +84,27 @@ def compare(gpu, ref, rows=None, label="", greedy=False):
     s_err = np.abs(gS - S)
     s_tol = S_RTOL * S + S_FLOOR * np.maximum(w, 1e-30)
     s_rel = s_err / np.maximum(S, 1e-300)
+    # h_i = S_i / (S_i + 1 - w_i) is ill-conditioned where S_i and 1 - w_i are both small: its tolerance is 2e-5 plus
+    # what the tolerance of S_i and an error of 5e-6 w_i in w_i can move it by (rows with w_i < 1 only; h_i = 1 otherwise,
+    # and Alg. 1's h_i = min(r_i, 1) has w_i = 1 throughout)
+    u = np.maximum(1.0 - w, 0.0)
+    with np.errstate(invalid="ignore", over="ignore", divide="ignore"):
+        h_tol = 2e-5 + np.where(u > 0, (u * s_tol + S * 5e-6 * w) / np.maximum(S + u, 1e-300) ** 2, 0.0)
+    s_rows = S > 0            # (row gamma, where S = w, included)
     report = {
         "label": label, "n": int(n),
         "tau_mismatch": int(tau_bad.sum()), "y_mismatch": int(y_bad.sum()),
         "excused": int(excused.sum()), "unexcused": int(unexcused.sum()),
         "max_S_rel_err": float(np.max(np.where(S > 1e-12, s_rel, 0.0))),
         "frac_S_within_1e-5_rel": float(np.mean(s_rel[S > 0] <= S_RTOL)) if np.any(S > 0) else 1.0,
+        "S_rows": int(s_rows.sum()),
+        "S_rows_outside_1e-5_rel": int((s_rel[s_rows] > S_RTOL).sum()),
+        # (positions below gamma: at gamma S is w itself)
+        "max_dS_over_w": float(np.max((s_err / np.maximum(w, 1e-300))[:, :-1], initial=0.0, where=(w > 1e-30)[:, :-1])),
         # w below float32's normal range cannot be reported in the float32 debug block
         "max_w_rel_err": float(np.max(np.where(w > 1e-30, np.abs(gw - w) / np.maximum(w, 1e-300), 0.0))),
         "max_h_abs_err": float(np.max(np.where(greedy & (S < 1e-12), 0.0, np.abs(gh - h)))),
+        "max_h_err_over_tol": float(np.max(np.where(greedy & (S < 1e-12), 0.0, np.abs(gh - h) / h_tol))),
         "mean_tau": float(np.mean(g_tau)),
         "n_fallback_oracle": int(ref["n_fallback"]),
     }
@@ -89,5 +112,5 @@ def compare(gpu, ref, rows=None, label="", greedy=False):
     assert np.all((g_tau >= 0) & (g_tau <= r_dbg.shape[1] - 1)), report
     assert np.all(s_err <= s_tol), f"residual mass out of tolerance: {report}"
     assert report["max_w_rel_err"] <= 2e-5, report
-    assert report["max_h_abs_err"] <= 2e-5, report
+    assert report["max_h_err_over_tol"] <= 1.0, report
     return report

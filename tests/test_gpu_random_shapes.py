@@ -15,7 +15,7 @@ from tests import parity
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-PATHS = {"staged": 1, "fused": 3, "fused-large": 4}
+PATHS = {"default": 0, "staged": 1, "fused": 3, "fused-large": 4}
 
 
 def _draw_case(rng, it, probs):
