@@ -149,6 +149,25 @@ def main():
             print(f"bench.py: {what}: outputs out of range; no result", file=sys.stderr)
             sys.exit(3)
 
+    # the floor of the kernel's launch shape for this call's bytes, in this same run: the library's streaming probe
+    # (first sweep only, no traffic between workgroups) over buffers of the call's size, rotated like the inputs
+    floor = None
+    if args.input == "logits" and cfg.dtype == "bf16":
+        half = (cfg.algorithmic_bytes // 2 + 16383) // 16384 * 16384
+        bufs = [torch.empty(half, dtype=torch.uint8, device=dev).fill_(0x3c) for _ in range(4)]
+        probe_out = torch.empty(half // 4096, dtype=torch.float32, device=dev)
+
+        def step_probe(i):
+            sv.spec_verify_debug_stream_probe(bufs[(2 * i) % 4], bufs[(2 * i + 1) % 4], probe_out, stream=stream.cuda_stream)
+
+        for i in range(8):
+            step_probe(i)
+        _, probe_ms = timed(max(args.steps // 4, 8), step_probe)
+        floor = {"device_ms": probe_ms, "bytes": 2 * half, "GBps": 2 * half / (probe_ms * 1e-3) / 1e9,
+                 "frac_of_peak": 2 * half / (probe_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "what": "spec_verify_debug_stream_probe: same launch shape and first-sweep arithmetic, no verification"}
+        del bufs, probe_out
+
     for i in range(args.warmup):
         step(i)
     wall, dev_ms = timed(args.steps, step)
@@ -212,7 +231,8 @@ def main():
                      "kernel": "whole call: fused_verify_kernel, the call's only kernel on the default path "
                                "(four staged kernels with --path staged)" if args.input == "logits" else
                                "whole call: probs_weights_kernel, probs_residual_kernel, probs_finalize_kernel",
-                     "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms, **extra},
+                     "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms, **extra,
+                     "floor_of_launch_shape": floor},
     }
     if not args.no_cpu_baseline and args.input == "logits":
         out["cpu_baseline"] = cpu_baseline(cfg, sets[0])

@@ -129,6 +129,14 @@ sv_status_t spec_sample_tokens(const void *logits, int64_t rows, int32_t V, sv_d
  * scaled against.  SV_ERR_INVALID_ARG for null, misaligned or ragged arguments.            */
 sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* Measurement hook: the floor of this launch shape.  Reads `bytes_each` bytes (a multiple of 16384) from each of the two
+ * 16-byte aligned device buffers `a` and `b` with the access pattern of the verification kernel - one 256-thread
+ * workgroup per 2 x 16 KB, eight 16-byte loads per lane issued up front, five waves per SIMD - and runs the first
+ * sweep's arithmetic on them as bf16 (maximum, exp2, sum), with no traffic between workgroups; one float per wave goes
+ * to `out` (bytes_each / 4096 floats).  What this kernel needs for a call's bytes is what no kernel of this shape that
+ * also verifies can beat.  SV_ERR_INVALID_ARG for null, misaligned or ragged arguments.    */
+sv_status_t spec_verify_debug_stream_probe(const void *a, const void *b, size_t bytes_each, float *out, void *stream);
+
 /*
  * Block verification (Alg. 2).
  *   target_logits  [B, gamma+1, V]  dtype, V contiguous, rows dense (stride V)

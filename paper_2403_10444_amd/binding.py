@@ -33,6 +33,7 @@ EXPORTED = (
     "spec_verify_workspace_check",
     "spec_verify_debug_config",
     "spec_verify_debug_copy",
+    "spec_verify_debug_stream_probe",
     "spec_sample_tokens",
     "spec_verify_block",
     "spec_verify_token",
@@ -94,6 +95,8 @@ def load() -> ctypes.CDLL:
             lib.spec_verify_debug_profile.argtypes = [ctypes.c_void_p]
         lib.spec_verify_debug_copy.restype = ctypes.c_int
         lib.spec_verify_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        lib.spec_verify_debug_stream_probe.restype = ctypes.c_int
+        lib.spec_verify_debug_stream_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         lib.spec_sample_tokens.restype = ctypes.c_int
         lib.spec_sample_tokens.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_float,
                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -149,6 +152,19 @@ def spec_verify_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) ->
     if stream is None:
         stream = torch.cuda.current_stream(src.device).cuda_stream
     code = load().spec_verify_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream)
+    if code != SV_OK:
+        raise SpecVerifyError(code, status_string(code))
+
+
+def spec_verify_debug_stream_probe(a: torch.Tensor, b: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """The library's streaming probe (the floor of the verification kernel's launch shape) over two equally large
+    device buffers; `out` takes one float per 4096 bytes of `a`."""
+    nbytes = a.numel() * a.element_size()
+    if b.numel() * b.element_size() != nbytes or out.numel() * 4096 < nbytes or out.dtype != torch.float32:
+        raise ValueError("a and b must have the same size in bytes and out one float32 per 4096 bytes of a")
+    if stream is None:
+        stream = torch.cuda.current_stream(a.device).cuda_stream
+    code = load().spec_verify_debug_stream_probe(a.data_ptr(), b.data_ptr(), nbytes, out.data_ptr(), stream)
     if code != SV_OK:
         raise SpecVerifyError(code, status_string(code))
 

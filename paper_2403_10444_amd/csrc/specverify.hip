@@ -371,6 +371,45 @@ sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, voi
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
+// What a one-pass kernel of the fused kernel's launch shape can reach: one 256-thread workgroup per 2 x 16 KB (a wave
+// reads 4 KB of each of two buffers with eight 16-byte loads per lane, all issued up front), the first sweep's
+// arithmetic on bf16 (unpack, maximum, exp2, sum), five waves per SIMD, no traffic between workgroups.
+namespace { __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5)))
+void stream_probe_kernel(const uint4 *a, const uint4 *b, float *out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint4 *pa = a + (size_t)blockIdx.x * 1024 + wave * 256 + lane;
+    const uint4 *pb = b + (size_t)blockIdx.x * 1024 + wave * 256 + lane;
+    uint4 va[4], vb[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) va[j] = pa[j * 64];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) vb[j] = pb[j * 64];
+    float res = 0.f;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const uint4 *v = r ? vb : va;
+        float x[32];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) unpack_vec<bf16_t>(v[j], x + j * 8);
+        float shift;
+        const u64 word = first_sweep_row(x, 1.8f, shift);
+        res += stat_sum(word) + shift;
+    }
+    if (lane == 0) out[(size_t)blockIdx.x * 4 + wave] = res;
+} }
+
+sv_status_t spec_verify_debug_stream_probe(const void *a, const void *b, size_t bytes_each, float *out, void *stream)
+{
+    if (!a || !b || !out || bytes_each == 0 || bytes_each % 16384 != 0) return SV_ERR_INVALID_ARG;
+    if (((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15u) != 0) return SV_ERR_INVALID_ARG;
+    const size_t blocks = bytes_each / 16384;
+    if (blocks > 0x7fffffffull) return SV_ERR_UNSUPPORTED;
+    stream_probe_kernel<<<(unsigned)blocks, 256, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const uint4 *>(a), static_cast<const uint4 *>(b), out);
+    return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
 sv_status_t spec_sample_tokens(const void *logits, int64_t rows, int32_t V, sv_dtype_t dtype, float temperature,
                                const float *uniforms, int32_t *tokens, void *stream_v)
 {
