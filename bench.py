@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--sigma-draft", type=float, default=None,
                     help="draft noise of the workload (configuration 4 is swept over 0.5, 1.5, 3.0; 0.5 = high acceptance)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed region: no floor probe, no second leg with every residual mass formed (for "
+                         "profiler runs, whose per-kernel averages should hold the timed launches only)")
     ap.add_argument("--path", default="default", choices=["default", "staged", "fused", "fused-small", "fused-large"],
                     help="kernel path (testing hook of the library)")
     ap.add_argument("--spin-limit", type=int, default=-1,
@@ -152,7 +155,7 @@ def main():
     # the floor of the kernel's launch shape for this call's bytes, in this same run: the library's streaming probe
     # (first sweep only, no traffic between workgroups) over buffers of the call's size, rotated like the inputs
     floor = None
-    if args.input == "logits" and cfg.dtype == "bf16":
+    if args.input == "logits" and cfg.dtype == "bf16" and not args.no_extras:
         half = (cfg.algorithmic_bytes // 2 + 16383) // 16384 * 16384
         bufs = [torch.empty(half, dtype=torch.uint8, device=dev).fill_(0x3c) for _ in range(4)]
         probe_out = torch.empty(half // 4096, dtype=torch.float32, device=dev)
@@ -179,7 +182,7 @@ def main():
     # same kernel is also timed with every S_i formed (the debug block asks for them), and the share of what was left
     # out on this workload is reported beside it.
     extra = {}
-    if args.input == "logits":
+    if args.input == "logits" and not args.no_extras:
         dbg = torch.empty((cfg.B, cfg.gamma + 1, 3), dtype=torch.float32, device=dev)
 
         def step_all(i):

@@ -34,7 +34,15 @@
  * finite logit and a drafted token has a finite DRAFT logit (its target logit may be -inf: its
  * ratio is then 0 and it is never accepted).  That, tokens in [0, V) and uniforms in [0, 1) are
  * the caller's contract and are not checked on the device.
- * Two calls may run concurrently only with disjoint workspaces.
+ *
+ * Calls that share a workspace must not overlap (two calls may run concurrently only with disjoint workspaces); the
+ * testing hook spec_verify_debug_config and the one-time look at the device below are the only process-wide state.
+ * Graph capture: a call is kernel launches only, but the FIRST call of each kernel variant (logit type, alignment,
+ * row width class) asks the runtime once how many of its workgroups the device holds at a time; make one call of the
+ * shape outside the capture first.
+ * If the verification kernel ever gives up one of its (bounded) waits - which needs a device that does not start
+ * workgroups in index order, or another kernel that takes its compute units away for seconds - the sequences concerned
+ * get accept_len = next_token = -1 instead of a result, and spec_verify_workspace_check reports SV_ERR_INTERNAL.
  */
 #ifndef SPECVERIFY_H
 #define SPECVERIFY_H
@@ -66,10 +74,11 @@ size_t spec_verify_workspace_bytes(int32_t B, int32_t gamma, int32_t V);
 
 /* Prepares a workspace for calls of exactly the shape (B, gamma, V): enqueues one small
  * kernel on `stream` that clears the control words the verification kernel synchronises
- * its workgroups with.  Required once after allocation (and again before using the same
- * memory for another shape); every verification call leaves the control words ready for
- * the next one (the workspace's contents between calls are the library's business: do not
- * clear or copy parts of it).  Calls that share a workspace must not overlap; calls on
+ * its workgroups with (they exist twice; a sequence's calls use the two copies alternately and
+ * each call clears the copy it does not use).  Required once after allocation (and again before
+ * using the same memory for another shape, or after a call that reported -1); every
+ * verification call leaves the workspace ready for the next one (its contents between calls
+ * are the library's business: do not clear or copy parts of it).  Calls that share a workspace must not overlap; calls on
  * different streams need workspaces of their own.
  * A verification call on a workspace that was not initialised for its shape
  * touches nothing else and writes -1 to every accept_len and next_token.                  */
@@ -78,8 +87,8 @@ sv_status_t spec_verify_workspace_init(void *workspace, size_t workspace_bytes,
 
 /* Synchronises `stream` and reads the workspace's status words back to the host: SV_OK,
  * SV_ERR_INVALID_ARG if the workspace is not initialised for this shape, SV_ERR_INTERNAL
- * if a workgroup gave up a bounded wait during an earlier call (the results of that call
- * are then invalid; re-initialise the workspace).  Meant for tests and debugging: it is
+ * if a workgroup gave up a bounded wait during an earlier call (that call wrote -1 for the
+ * sequences concerned; re-initialise the workspace).  Meant for tests and debugging: it is
  * the one entry point that blocks.                                                        */
 sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_t gamma, int32_t V,
                                         void *stream);
@@ -90,10 +99,11 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
  * workgroups resident; other shapes are then refused), 3 / 4 = the fused kernel with its
  * small / large units (32 / 64 logits of a row per lane; large ones exist for bf16 rows on
  * the 16-byte path only, other calls use the small ones; the library's own choice depends on
- * the shape; both also switch on, whatever the size of the call, the leaving-out of residual
- * masses that cannot matter, which the library otherwise uses for calls larger than one
- * resident set of workgroups); `spin_limit` bounds every wait inside the fused kernel in polls (negative:
- * default).                                                                               */
+ * the shape; both also switch on, whatever the size of the call, what the library otherwise
+ * does only in calls larger than one resident set of workgroups: residual masses that cannot
+ * matter are left out, the last target row is read only where every token can be accepted, and
+ * w_i travels from position to position as one published word); `spin_limit` bounds every wait
+ * inside the fused kernel in polls (negative: default).                                   */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);
 
 #ifdef SPECVERIFY_PROFILE_BUILD

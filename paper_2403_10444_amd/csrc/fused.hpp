@@ -135,6 +135,10 @@ __device__ __forceinline__ Words words_of(const FusedParams &P, unsigned copy)
     return W;
 }
 
+// The same number, but one the compiler knows nothing about: what is computed from it is computed where it is used and
+// not at the top of the kernel (where it would only be spilled until then).
+__device__ __forceinline__ unsigned launder(unsigned v) { asm volatile("" : "+s"(v)); return v; }
+
 // A load through the scalar data path for values that do not change while the kernel runs and whose address is the
 // same for the whole wave (inputs; the call count of a sequence, which changes only after its last reader).  It
 // does not queue behind the wave's sixteen-byte loads.
@@ -933,8 +937,9 @@ void fused_verify_kernel(const FusedParams P)
         if (clears) { clear_row_words(P, P.words, U.b, slot); clear_row_words(P, words_of(P, 1), U.b, slot); }
         return;
     }
-    // the copy of the words this call uses for the sequence (see the head of this file)
-    const Words W = words_of(P, par);
+    // (the copy of the words this call uses for the sequence - see the head of this file - is `par`; the addresses in it
+    // are formed block by block where they are used: the kernel is short of scalar registers)
+#define SV_WORDS words_of(P, launder(par))
 
     __shared__ u64 wave_words[2][kWaves];
     __shared__ double row_values[8];
@@ -948,17 +953,18 @@ void fused_verify_kernel(const FusedParams P)
     const int n_prev = U.i;                                   // ratios that w_i is made of
     const bool chain = P.prune != 0;
 #define SV_RATIO_WORD (W.ratio + seq_d + (lane < n_prev ? lane : 0))
-    const u64 *const lw_word = W.lw + seq_d + (n_prev > 0 ? n_prev - 1 : 0);
+#define SV_LW_WORD (W.lw + seq_d + (n_prev > 0 ? n_prev - 1 : 0))
 
     if (U.last_row) {
         // ---- the last target row: needed only if every token is accepted (then Y ~ p_gamma, Alg. 1 / 2 / 4).  In
         // calls large enough for it to pay, its workgroups first look at w_gamma: where eta_gamma >= w_gamma (Alg. 1:
         // where some test fails) the row is not read at all, and its words say "no mass here".
         if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
+        const Words W = SV_WORDS;
         if (P.skip_last) {
             if (wave == 0) {
                 const float eta_g = load_uniform(P.uniforms + seq_u + gb - 1);
-                const u64 wt = wait_word(lw_word, P.spin_limit, gave_up);
+                const u64 wt = wait_word(SV_LW_WORD, P.spin_limit, gave_up);
                 const bool wanted = can_become_tau(P.algo, gb, unpack_ratio(wt), eta_g);
                 if (lane == 0) row_flag = gave_up ? 2 : wanted ? 0 : 1;
                 if (gave_up) report_gave_up(P);
@@ -987,8 +993,9 @@ void fused_verify_kernel(const FusedParams P)
     float eta_i = 0.f, eta_next = 0.f;                       // the uniforms of test i (this position's) and test i + 1
     int tok = 0;                                             // the drafted token X_{i+1}, for the leader
     if (wave == 0) {
+        const Words W = SV_WORDS;
         eta_i = load_uniform(P.uniforms + seq_u + (n_prev > 0 ? n_prev - 1 : 0));
-        if (chain) { if (n_prev > 0) wt = ld_u64(lw_word); }
+        if (chain) { if (n_prev > 0) wt = ld_u64(SV_LW_WORD); }
         else wt = ld_u64(SV_RATIO_WORD);
     }
     if (wave == 0) {
@@ -1002,7 +1009,7 @@ void fused_verify_kernel(const FusedParams P)
     float shiftA, shiftB;
     unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
     const u64 stA = first_sweep_row(xa, k, shiftA);
-    if (lane == 0) st_u64(W.pstat + drow * nu + U.c, stA);
+    if (lane == 0) st_u64(SV_WORDS.pstat + drow * nu + U.c, stA);
     // the two logits of the draft token, asked for only now so that the streams above did not queue behind them
     float ya_f = 0.f, yb_f = 0.f;
     if (leader) { ya_f = logit_as_float(rowA + tok); yb_f = logit_as_float(rowB + tok); }
@@ -1016,10 +1023,11 @@ void fused_verify_kernel(const FusedParams P)
     double log2w = 0.0;
     if (wave == 0) {
         SV_STAMP(1);
+        const Words W = SV_WORDS;
         publish_group_words(wave_words, W.pgrp + drow * nwg + wg_x, W.qgrp + drow * nwg + wg_x);
         bool wanted = true;
         if (early) {
-            wt = wait_word(lw_word, wt, true, P.spin_limit, gave_up);
+            wt = wait_word(SV_LW_WORD, wt, true, P.spin_limit, gave_up);
             log2w = unpack_ratio(read_lane_u64(wt, 0));
             wanted = gave_up || can_become_tau(P.algo, U.i, log2w, eta_i);
         }
@@ -1038,11 +1046,12 @@ void fused_verify_kernel(const FusedParams P)
     double lw_next = 0.0;            // the leader's log2 w_{i+1}
     if (wave == 0) {
         // ---- L_p, L_q: the words of all workgroups of the row
+        const Words W = SV_WORDS;
         float Mp, Mq;
         double Lp, Lq;
         const bool need_w = n_prev > 0 && !early;            // w_i still to come: the chain's word, or the ratios
         const bool need_lane = need_w && (chain || lane < n_prev);
-        const u64 *const w_word = chain ? lw_word : SV_RATIO_WORD;
+        const u64 *const w_word = chain ? SV_LW_WORD : SV_RATIO_WORD;
         if (nwg <= kWave / 2) {
             // one poll covers the row: the target row's words in lanes 0.., the draft row's in lanes 32.., what w_i is
             // made of (if still missing) beside them; the two halves of the wave are then combined side by side
@@ -1142,9 +1151,10 @@ void fused_verify_kernel(const FusedParams P)
             }
         }
         acc = wave_sum(acc);
-        if (lane == 0) st_u32(W.spart + drow * nu + U.c, poisoned ? kPoison32 : pack_partial(acc));
+        if (lane == 0) st_u32(SV_WORDS.spart + drow * nu + U.c, poisoned ? kPoison32 : pack_partial(acc));
         SV_STAMP(4);
         if (!leader) return;
+        const Words W = SV_WORDS;
         // ---- the row's leader sums the row's partial sums and, if this position can become tau, draws the token that
         // follows in that case - while the later positions are still streaming: whoever finishes the sequence then
         // only picks both up
@@ -1159,6 +1169,7 @@ void fused_verify_kernel(const FusedParams P)
     if (!finisher) return;
     // ---- the leader of a sequence's last row pair finishes the sequence
     SV_STAMP(5);
+    const Words W = SV_WORDS;
     const double Lp = row_values[0], Lq = row_values[1];
     const float u = load_uniform(P.uniforms + seq_u + gb);
     // what the tests need of the earlier positions, asked for at once: their ratios and (calls larger than one resident
@@ -1207,6 +1218,8 @@ void fused_verify_kernel(const FusedParams P)
     }
     SV_STAMP(6);
 #undef SV_RATIO_WORD
+#undef SV_LW_WORD
+#undef SV_WORDS
 }
 
 // Clears the control words of a workspace and marks it initialised.
