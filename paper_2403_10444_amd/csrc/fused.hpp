@@ -1050,8 +1050,10 @@ void fused_verify_kernel(const FusedParams P)
         float Mp, Mq;
         double Lp, Lq;
         const bool need_w = n_prev > 0 && !early;            // w_i still to come: the chain's word, or the ratios
-        const bool need_lane = need_w && (chain || lane < n_prev);
-        const u64 *const w_word = chain ? SV_LW_WORD : SV_RATIO_WORD;
+        // (the chain's word is polled beside the row's words; the ratios of the earlier positions only after this row's
+        // own ratio is out - it does not depend on them, and the later positions wait for it)
+        const bool need_lane = need_w && chain;
+        const u64 *const w_word = SV_LW_WORD;
         if (nwg <= kWave / 2) {
             // one poll covers the row: the target row's words in lanes 0.., the draft row's in lanes 32.., what w_i is
             // made of (if still missing) beside them; the two halves of the wave are then combined side by side
@@ -1081,10 +1083,8 @@ void fused_verify_kernel(const FusedParams P)
             load_row_words<NW>(W.qgrp + drow * nwg, nwg, qw);
             Lp = row_normaliser<NW>(W.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
             Lq = row_normaliser<NW>(W.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
-            if (need_w) wt = wait_word(w_word, wt, need_lane, P.spin_limit, gave_up);
+            if (need_lane) wt = wait_word(w_word, wt, true, P.spin_limit, gave_up);
         }
-        if (need_w) log2w = chain ? unpack_ratio(read_lane_u64(wt, 0)) : read_lane_double(weights_from_ratios(P.algo, wt, n_prev), n_prev - 1);
-        candidate = can_become_tau(P.algo, U.i, log2w, eta_i);
         if (leader) {
             // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for every later position and for whoever finishes
             // the sequence.  The sweeps scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To
@@ -1099,12 +1099,18 @@ void fused_verify_kernel(const FusedParams P)
             // Alg. 1's test of X_{i+1}, judged here once for everybody: eta_{i+1} < min(r_{i+1}, 1)
             const bool passes = P.algo == kToken && (double)eta_next < exp2_precise(fmin(lr, 0.0));
             own_word = pack_ratio(lr, passes);
-            lw_next = unpack_ratio(pack_ratio(next_weight(P.algo, log2w, unpack_ratio(own_word), passes), false));
             if (gave_up) report_gave_up(P);
-            if (lane == 0) {
-                st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
-                if (chain) st_u64(W.lw + drow, gave_up ? kPoison64 : pack_ratio(lw_next, false));
-            }
+            if (lane == 0) st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
+        }
+        if (need_w) {
+            if (!chain) wt = wait_word(SV_RATIO_WORD, wt, lane < n_prev, P.spin_limit, gave_up);
+            log2w = chain ? unpack_ratio(read_lane_u64(wt, 0)) : read_lane_double(weights_from_ratios(P.algo, wt, n_prev), n_prev - 1);
+        }
+        candidate = can_become_tau(P.algo, U.i, log2w, eta_i);
+        if (leader && chain) {
+            lw_next = unpack_ratio(pack_ratio(next_weight(P.algo, log2w, unpack_ratio(own_word), ratio_passes(own_word)), false));
+            if (gave_up) report_gave_up(P);
+            if (lane == 0) st_u64(W.lw + drow, gave_up ? kPoison64 : pack_ratio(lw_next, false));
         }
         if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
         if (P.algo == kGreedy) log2w = fmin(log2w, 100.0);          // keeps w p finite in float
