@@ -10,7 +10,6 @@
 #include <math.h>
 #include <atomic>
 #include <mutex>
-#include <stdlib.h>
 
 #include "../../include/specverify.h"
 #include "common.hpp"
@@ -84,22 +83,15 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
 
 template <typename T> constexpr int dtype_bytes() { return ElemTraits<T>::kVec == 4 ? 4 : 2; }
 
-// Waits (of 64 clocks) per row between the load requests of the first resident set's rows; SPECVERIFY_PACE overrides
-// the factor for tuning.
+// Waits (of 64 clocks) per row between the load requests of the first resident set's rows: three quarters of the time
+// one row pair's bytes take at about 6 TB/s and 2.1 GHz (measured at B = 64, gamma = 8, V = 128256: 0.75 is the best of
+// 0 .. 1.5 in steps of a quarter; 0 costs 1.2 us of 58, 1.25 and more cost more than they gain).
 float pace_units(double row_pair_bytes)
 {
-    static const double factor = [] { const char *e = getenv("SPECVERIFY_PACE"); return e ? atof(e) : 0.75; }();
-    return (float)(factor * row_pair_bytes / 6.0e12 * 2.1e9 / 64.0);
+    return (float)(0.75 * row_pair_bytes / 6.0e12 * 2.1e9 / 64.0);
 }
 
 // Workgroups of a kernel that the current device keeps resident at once (cached per kernel).
-// (tuning: SPECVERIFY_LDS bytes of dynamic LDS per workgroup, which lowers the number of resident workgroups)
-size_t tuning_lds_bytes()
-{
-    static const size_t bytes = [] { const char *e = getenv("SPECVERIFY_LDS"); return e ? (size_t)atol(e) : (size_t)0; }();
-    return bytes;
-}
-
 template <typename K>
 int resident_workgroups(K kernel, std::atomic<int> &cache)
 {
@@ -107,7 +99,7 @@ int resident_workgroups(K kernel, std::atomic<int> &cache)
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, tuning_lds_bytes()) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess) return 0;
     cache.store(cus * per_cu);
     return cus * per_cu;
 }
@@ -213,10 +205,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     const dim3 grid((unsigned)wpr, (unsigned)P.group_seqs, (unsigned)(n_groups * (gamma + 1)));
     // (the testing hook's forced unit sizes also force the pruning, so that small test shapes exercise it)
     P.prune = g_lane.load() != 0 || (size_t)wpr * P.group_seqs * n_groups * (gamma + 1) > (size_t)capacity ? 1 : 0;
-    {
-        static const int mode = [] { const char *e = getenv("SPECVERIFY_SKIP_LAST"); return e ? atoi(e) : 2; }();
-        P.skip_last = P.prune && (mode == 2 || (mode == 1 && n_groups == 1)) ? 1 : 0;
-    }
+    P.skip_last = P.prune;
     P.spin_limit = g_spin_limit.load();
     P.resident = capacity;
     // pacing of the first resident set (only where there is a second one): one row pair's bytes at about 6 TB/s, in
@@ -238,7 +227,7 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
 #ifdef SV_PROFILE
     P.prof = g_prof.load();
 #endif
-    kernel<<<grid, kThreads, tuning_lds_bytes(), stream>>>(P);
+    kernel<<<grid, kThreads, 0, stream>>>(P);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
