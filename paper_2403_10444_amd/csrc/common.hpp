@@ -71,6 +71,20 @@ __device__ __forceinline__ float logit_as_float(const T *p)
     if constexpr (ElemTraits<T>::kVec == 4) return *reinterpret_cast<const float *>(p);
     else return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(p)[0] << 16);
 }
+// The same in two steps, for a caller that must not wait for the load where it asks: the logit's bits as loaded ...
+template <typename T>
+__device__ __forceinline__ uint32_t logit_bits(const T *p)
+{
+    if constexpr (ElemTraits<T>::kVec == 4) return *reinterpret_cast<const uint32_t *>(p);
+    else return (uint32_t)reinterpret_cast<const uint16_t *>(p)[0];
+}
+// ... and the float they stand for
+template <typename T>
+__device__ __forceinline__ float logit_bits_as_float(uint32_t bits)
+{
+    if constexpr (ElemTraits<T>::kVec == 4) return __uint_as_float(bits);
+    else return __uint_as_float(bits << 16);
+}
 template <typename T>
 __device__ __forceinline__ double logit_as_double(const T *p) { return (double)logit_as_float(p); }
 

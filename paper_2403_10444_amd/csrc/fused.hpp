@@ -148,13 +148,16 @@ template <typename X> __device__ __forceinline__ X load_uniform(const X *p)
 }
 
 // ---- agent-scope accessors for words that other waves (on any XCD) write or read
-__device__ __forceinline__ int ld_i32(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ unsigned ld_u32(const unsigned *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void st_u32(unsigned *p, unsigned v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// The words live in device memory.  The accesses say so: a pointer that went through arithmetic on bytes may otherwise
+// count as generic, and a generic load is waited for wherever LDS or scalar loads are (and the other way round).
+#define SV_GLOBAL(type, p) ((__attribute__((address_space(1))) type *)(p))
+__device__ __forceinline__ int ld_i32(const int *p) { return __hip_atomic_load(SV_GLOBAL(const int, p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ unsigned ld_u32(const unsigned *p) { return __hip_atomic_load(SV_GLOBAL(const unsigned, p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_u32(unsigned *p, unsigned v) { __hip_atomic_store(SV_GLOBAL(unsigned, p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ unsigned pack_partial(float v) { return __float_as_uint(v) | 1u; }
 __device__ __forceinline__ float unpack_partial(unsigned w) { return __uint_as_float(w & ~1u); }
-__device__ __forceinline__ u64 ld_u64(const u64 *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void st_u64(u64 *p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ u64 ld_u64(const u64 *p) { return __hip_atomic_load(SV_GLOBAL(const u64, p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_u64(u64 *p, u64 v) { __hip_atomic_store(SV_GLOBAL(u64, p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ u64 pack_stat(float shift, float sum)
 {
     return ((u64)__float_as_uint(sum) << 32) | (u64)__float_as_uint(shift);
@@ -599,8 +602,10 @@ __device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float 
 // workgroup's record `stamps`; the default build has none of it.
 #ifdef SV_PROFILE
 #define SV_STAMP(slot) do { if (stamps && threadIdx.x == 0) stamps[slot] = wall_clock64(); } while (0)
+#define SV_NOTE(slot, value) do { if (stamps && threadIdx.x == 0) stamps[slot] = (value); } while (0)
 #else
 #define SV_STAMP(slot) do { } while (0)
+#define SV_NOTE(slot, value) do { } while (0)
 #endif
 
 // ------------------------------------------------------------------ the draw of a token
@@ -770,17 +775,15 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &
 // block); returns tau.  y_out is the token that the leader of row pair tau has drawn from its residual, or -1 when tau
 // is the last row pair or beyond (then the caller draws); lw_own is log2 w of the last row pair.
 __device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words &W, int b, int gamma, u64 ratio_word, double lw, float S_own,
-                                               int &y_out, double &lw_own, bool &gave_up, long long *stamps)
+                                               u64 res, float eta, int &y_out, double &lw_own, bool &gave_up, long long *stamps)
 {
     const int lane = threadIdx.x & 63;
     // G, the call's (largest) draft length, is the stride of every array
     const int G = P.gamma;
     const size_t base = (size_t)b * (G + 1);
-    // one word per earlier position: S_j and the token its leader drew.  Asked for before anything else; what is not
-    // there yet is polled once it is known which positions publish one
+    // one word per earlier position: S_j and the token its leader drew (`res`: what the caller's first look found there;
+    // what is not there yet is polled once it is known which positions publish one).  `eta`: lane l holds eta_{l+1}
     const u64 *res_word = W.rowres + (size_t)b * G + (lane < gamma - 1 ? lane : 0);
-    u64 res = gamma > 1 ? ld_u64(res_word) : 0;
-    const float eta = P.uniforms[base + (lane < gamma ? lane : gamma - 1)];          // lane l: eta_{l+1}
     SV_STAMP(7);
     const double lr = unpack_ratio(ratio_word);
     // lane l tests position j = l + 1
@@ -1009,11 +1012,15 @@ void fused_verify_kernel(const FusedParams P)
     float shiftA, shiftB;
     unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
     const u64 stA = first_sweep_row(xa, k, shiftA);
-    if (lane == 0) st_u64(SV_WORDS.pstat + drow * nu + U.c, stA);
-    // the two logits of the draft token, asked for only now so that the streams above did not queue behind them
-    float ya_f = 0.f, yb_f = 0.f;
-    if (leader) { ya_f = logit_as_float(rowA + tok); yb_f = logit_as_float(rowB + tok); }
+    // (the draft row's logits are taken out of their load registers before anything else is sent to memory: the
+    // hardware counts outstanding loads and stores in one counter, in order, and a wait for these loads placed after
+    // a store would be a wait for that store's acknowledgement too)
     unpack_slice<T, ALIGNED, LANE>(rowB, unit_first, V, rawB, xb);
+    if (lane == 0) st_u64(SV_WORDS.pstat + drow * nu + U.c, stA);
+    // the two logits of the draft token, asked for only now so that the streams above did not queue behind them, and
+    // left as loaded until they are needed: the row's words will have come in by then, and these with them
+    uint32_t ya_bits = 0, yb_bits = 0;
+    if (leader) { ya_bits = logit_bits(rowA + tok); yb_bits = logit_bits(rowB + tok); }
     const u64 stB = first_sweep_row(xb, k, shiftB);
     // the wave's two words meet the other waves' in LDS; the first wave publishes the workgroup's two words and, in
     // calls larger than one resident set, decides whether this row's residual mass can matter: a row that is not needed
@@ -1027,7 +1034,9 @@ void fused_verify_kernel(const FusedParams P)
         publish_group_words(wave_words, W.pgrp + drow * nwg + wg_x, W.qgrp + drow * nwg + wg_x);
         bool wanted = true;
         if (early) {
+            SV_NOTE(14, read_lane_u64(wt, 0) != 0 ? 1 : 2);
             wt = wait_word(SV_LW_WORD, wt, true, P.spin_limit, gave_up);
+            SV_STAMP(13);
             log2w = unpack_ratio(read_lane_u64(wt, 0));
             wanted = gave_up || can_become_tau(P.algo, U.i, log2w, eta_i);
         }
@@ -1091,8 +1100,8 @@ void fused_verify_kernel(const FusedParams P)
             // first order that moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken
             // as the row maximum); only this ratio, whose logs reach hundreds, is sensitive to it.
             // (the three floats become doubles here and not a moment earlier: registers are scarce until the second sweep)
-            asm volatile("" : "+v"(ya_f), "+v"(yb_f), "+s"(eta_next));
-            const double ya = (double)ya_f, yb = (double)yb_f;
+            asm volatile("" : "+v"(ya_bits), "+v"(yb_bits), "+s"(eta_next));
+            const double ya = (double)logit_bits_as_float<T>(ya_bits), yb = (double)logit_bits_as_float<T>(yb_bits);
             const double lp = ya * P.kd - (Lp + P.k_eps * (double)Mp);
             const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
             const double lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
@@ -1183,6 +1192,9 @@ void fused_verify_kernel(const FusedParams P)
     const u64 *const r_word = W.ratio + seq_d + (lane < gb - 1 ? lane : 0);
     const u64 *const l_word = W.lw + seq_d + (lane > 0 && lane < gb ? lane - 1 : 0);        // lane j: the word of log2 w_j
     u64 rw_all = gb > 1 ? ld_u64(r_word) : 0, lw_all = chain && gb > 1 ? ld_u64(l_word) : 0;
+    // (and, in the same round trip, the earlier positions' results and the sequence's uniforms: lane l gets eta_{l+1})
+    const u64 res_first = gb > 1 ? ld_u64(W.rowres + seq_d + (lane < gb - 1 ? lane : 0)) : 0;
+    const float eta_all = P.uniforms[seq_u + (lane < gb ? lane : gb - 1)];
     // its own row's mass (the draw, if tau turns out to be this position, comes after the tests)
     if (needed) draw_from_row<T, ALIGNED, LANE>(P, W, W.pstat + drow * nu, U.b, U.i, 0, false, 0.0, 0.0, u, S_own, gave_up);
     // the last target row's words, asked for early: they are waited for before the sequence's call count moves on
@@ -1203,7 +1215,7 @@ void fused_verify_kernel(const FusedParams P)
     }
     int y = -1;
     double lw_own;
-    const int tau = finish_sequence(P, W, U.b, gb, rw_all, lw_seen, (float)S_own, y, lw_own, gave_up, stamps);
+    const int tau = finish_sequence(P, W, U.b, gb, rw_all, lw_seen, (float)S_own, res_first, eta_all, y, lw_own, gave_up, stamps);
     if (y < 0) {
         // tau is the last row pair (its residual: this wave has the row's constants) or every token was
         // accepted (Y comes from the last target row itself)
