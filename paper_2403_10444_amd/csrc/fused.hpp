@@ -22,15 +22,16 @@
 //      workgroups of the row, which give L_p and L_q.  The first wave of the row's last workgroup is the
 //      row's leader and always stays: it publishes the row's ratio log2 r_{i+1},
 //   4. forms its share of S_i from the registers and publishes it; the row's leader then sums the row's
-//      shares, draws the token that follows if this position becomes tau (draw_from_row) and publishes
-//      both in one word.
+//      shares and judges the position's own accept test (Alg. 2 / 4: eta_i < h_i = S_i / (S_i + 1 - w_i)); where it
+//      passes - and at position 0, which is tau when no test passes - it draws the token that follows if this
+//      position becomes tau (draw_from_row) and publishes both in one word (lead_row).
 // Workgroups start position-major inside groups of sequences (all row pairs of position 0, then
 // position 1, ..., then the last target rows), so what an earlier position publishes is there
 // before a later one asks for it, and a workgroup only ever waits for the workgroups of
 // its own row, which start next to it.  The leader of a sequence's last row pair finishes the
-// sequence: it reads one word per earlier position (S_i and the token drawn there), runs the accept
-// tests (finish_sequence) and picks up the token drawn for position tau (or draws it, if tau is its own
-// position or every token was accepted).  The last target row is needed only when every token is accepted
+// sequence: it reads one word per earlier position (did its test pass, and the token drawn there), judges the last
+// test (eta_gamma < w_gamma) and writes tau and the token drawn for position tau (its own, or one from the last target
+// row if every token was accepted).  The last target row is needed only when every token is accepted
 // (Y ~ p_gamma): its workgroups wait for the ratios, and where eta_gamma >= w_gamma they load nothing.
 //
 // Everything that crosses workgroups is a self-announcing word: zero until written, non-zero once written
@@ -82,8 +83,9 @@ struct Words {
     u64 *lw;              // [B, gamma]               calls larger than one resident set: log2 w_{i+1} as double bits, lowest bit set
                           //                          (Alg. 1: 0 while every test up to i + 1 has passed, kLog2RatioFloor afterwards); by
                           //                          the leader of row pair i
-    u64 *rowres;          // [B, gamma]               low half: S_i as float bits; high half: the token drawn from row pair i's
-                          //                          residual + 2, or 1 if none was drawn; by the leader of row pair i
+    u64 *rowres;          // [B, gamma]               what position i contributes to tau and Y (pack_rowres): whether its accept test
+                          //                          passes (Alg. 2 / 4: eta_i < h_i; Alg. 1: the test of X_{i+1}) and the token drawn from
+                          //                          row pair i's residual where tau can still be i; by the leader of row pair i
     u64 *pstat;           // [B, gamma, nu]           (largest scaled logit, sum) per wave chunk of a row pair's target row
     u64 *plast;           // [B, nu]                  the same of the sequence's last target row (row draft_lens[b])
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
@@ -168,8 +170,10 @@ __device__ __forceinline__ float stat_sum(u64 v) { return __uint_as_float((unsig
 __device__ __forceinline__ u64 pack_ratio(double log2r, bool passes) { return ((u64)__double_as_longlong(log2r) & ~3ull) | 1ull | (passes ? 2ull : 0ull); }
 __device__ __forceinline__ double unpack_ratio(u64 v) { return __longlong_as_double((long long)(v & ~3ull)); }
 __device__ __forceinline__ bool ratio_passes(u64 v) { return (v & 2ull) != 0; }
-__device__ __forceinline__ u64 pack_rowres(float S, int token) { return ((u64)(unsigned)(token + 2) << 32) | (u64)__float_as_uint(S); }
-__device__ __forceinline__ float rowres_S(u64 v) { return __uint_as_float((unsigned)(v & 0xffffffffull)); }
+// (low half: whether the leader's own accept test passes; high half: the token it drew + 2, 1 if it drew none - so the
+// word is never zero)
+__device__ __forceinline__ u64 pack_rowres(bool passes, int token) { return ((u64)(unsigned)(token + 2) << 32) | (passes ? 1ull : 0ull); }
+__device__ __forceinline__ bool rowres_passes(u64 v) { return (v & 1ull) != 0; }
 __device__ __forceinline__ int rowres_token(u64 v) { return (int)(unsigned)(v >> 32) - 2; }
 // What a wave publishes instead of a value once one of its waits has run out (or it has read this word itself):
 // all ones, which no value packs to (as a float, a double or a pair of floats it would be a NaN).
@@ -608,6 +612,25 @@ __device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float 
 #define SV_NOTE(slot, value) do { } while (0)
 #endif
 
+// ------------------------------------------------------------------ the accept test of one position
+// Alg. 2 / Alg. 4, position j >= 1 (j < the draft length): eta_j < h_j with h_j = S_j / (S_j + 1 - w_j), 1 where
+// w_j >= 1.  Greedy (Alg. 4) divides by the rejected mass sum_x max(q - w p, 0) instead, which is the same number: it
+// equals S - sum_x (w p - q) = S + 1 - w because both rows sum to one (w unclipped; at w >= 1 the ratio is >= 1 and
+// every eta in [0, 1) passes).  `log2w`: log2 w_j (greedy: capped so that w stays finite).
+struct AcceptTest {
+    double log2w;
+    float eta;
+    bool allowed;         // false: the position cannot become tau whatever S_j is (can_become_tau): the test counts as failed
+    bool passes;          // out
+    double w, h;          // out, for the debug block
+    __device__ __forceinline__ void evaluate(double S)
+    {
+        w = exp2_precise(log2w);
+        h = log2w >= 0.0 ? 1.0 : S / (S + one_minus_exp2(fmin(log2w, 0.0)));
+        passes = allowed && (double)eta < h;
+    }
+};
+
 // ------------------------------------------------------------------ the draw of a token
 // Row `row` of sequence b (one wave).  First the sum of the weights: mode 0, the residual max(w p - q, 0) of row pair
 // `row`, by the partial sums per wave chunk that the pair's units publish (polled here until all are there); mode 1,
@@ -615,10 +638,11 @@ __device__ __forceinline__ u64 first_sweep_row(float (&x)[LANE], float k, float 
 // `want_draw`, the inverse-CDF draw in index order, first token whose running sum exceeds u * total: the wave chunk
 // that holds it by a scan over the chunks' sums, then the token by the weights of that one chunk, formed again from
 // the logits with alpha_p = L_p - log2 w and alpha_q = L_q.  A residual without any mass is drawn from p_row
-// instead.  Returns the token, or -1 if none was asked for.
+// instead.  `test`, if `has_test`: the position's accept test, evaluated on the sum as soon as it is there; nothing is
+// drawn where it fails.  Returns the token, or -1 if none was asked for.
 template <typename T, bool ALIGNED, int LANE>
 __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &W, const u64 *st, int b, int row, int mode, bool want_draw,
-                                             double alpha_p, double alpha_q, float u, double &total_out, bool &gave_up)
+                                             bool has_test, AcceptTest &test, double alpha_p, double alpha_q, float u, double &total_out, bool &gave_up)
 {
     constexpr int kVec = ElemTraits<T>::kVec;
     constexpr int kNV = LANE / kVec;
@@ -671,7 +695,10 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &
             }
             if (pass_no == 0) {
                 total = carry; t = (double)u * total;
-                if (attempt == 0) total_out = total;
+                if (attempt == 0) {
+                    total_out = total;
+                    if (has_test) { test.evaluate(total); want_draw = want_draw && test.passes; }
+                }
                 if (!want_draw) return -1;
             }
         }
@@ -768,79 +795,6 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &
 }
 
 // ------------------------------------------------------------------ whole sequences
-// Accept tests of one sequence (one wave: the leader of the sequence's last row pair, position gamma - 1, where `gamma`
-// is this sequence's draft length).  `ratio_word`: lane j < gamma holds the word of log2 r_{j+1} (the last one is this
-// wave's own); `lw`: lane j < gamma holds log2 w_{j+1} as the positions' workgroups saw it; S_own: the residual mass of
-// the last row pair, if it was formed.  Writes tau (and the debug
-// block); returns tau.  y_out is the token that the leader of row pair tau has drawn from its residual, or -1 when tau
-// is the last row pair or beyond (then the caller draws); lw_own is log2 w of the last row pair.
-__device__ __forceinline__ int finish_sequence(const FusedParams &P, const Words &W, int b, int gamma, u64 ratio_word, double lw, float S_own,
-                                               u64 res, float eta, int &y_out, double &lw_own, bool &gave_up, long long *stamps)
-{
-    const int lane = threadIdx.x & 63;
-    // G, the call's (largest) draft length, is the stride of every array
-    const int G = P.gamma;
-    const size_t base = (size_t)b * (G + 1);
-    // one word per earlier position: S_j and the token its leader drew (`res`: what the caller's first look found there;
-    // what is not there yet is polled once it is known which positions publish one).  `eta`: lane l holds eta_{l+1}
-    const u64 *res_word = W.rowres + (size_t)b * G + (lane < gamma - 1 ? lane : 0);
-    SV_STAMP(7);
-    const double lr = unpack_ratio(ratio_word);
-    // lane l tests position j = l + 1
-    const int j = lane + 1;
-    double lw_j = lw;                                    // log2 w_j as the rule sees it (greedy: unclipped and uncapped)
-    const u64 may = __ballot(j < gamma && can_become_tau(P.algo, j, lw_j, eta));
-    const u64 have = __ballot(j < gamma && residual_needed(P, j, lw_j, eta));
-    if (P.algo == kGreedy) lw_j = fmin(lw_j, 100.0);
-    if (P.algo == kToken) lw_j = 0.0;
-    const double w_j = exp2_precise(lw_j);
-    const double one_minus_w = one_minus_exp2(fmin(lw_j, 0.0));
-    const double h_token = exp2_precise(fmin(lr, 0.0)); // min(r_j, 1), for the debug block
-    SV_STAMP(8);
-
-    // ---- S_i of position i into lane i: position 0 and every position of `have` publish theirs
-    const bool published = lane < gamma - 1 && (lane == 0 || ((have >> (lane - 1)) & 1));
-    res = wait_word(res_word, res, published, P.spin_limit, gave_up);
-    float my_S = published ? rowres_S(res) : 0.f;
-    if (lane == gamma - 1) my_S = S_own;
-    SV_STAMP(9);
-
-    // ---- accept tests eta_j < h_j
-    const double S_row = (double)__shfl_down(my_S, 1, kWave);
-    bool pass = false;
-    if (j <= gamma) {
-        const double S = j < gamma ? S_row : w_j;        // q_gamma == 0: S_gamma = w_gamma
-        double h;
-        if (P.algo == kToken) h = h_token;
-        else if (j == gamma) h = fmin(w_j, 1.0);                                           // h_gamma = w_gamma
-        // block: S / (S + 1 - w).  Greedy (Alg. 4) divides by the rejected mass sum_x max(q - w p, 0) instead, which
-        // is the same number: it equals S - sum_x (w p - q) = S + 1 - w because both rows sum to one (w unclipped;
-        // at w >= 1 the ratio is >= 1 and every eta in [0, 1) passes)
-        else h = lw_j >= 0.0 ? 1.0 : S / (S + one_minus_w);
-        // (Alg. 1: as the row's leader judged it, with this same expression; the later positions' workgroups went by that)
-        pass = P.algo == kToken ? ratio_passes(ratio_word) : (double)eta < h && (j == gamma || ((have & may) >> (j - 1)) & 1);
-        if (P.debug_out) {
-            float *d = P.debug_out + (base + j) * 3;
-            d[0] = (float)w_j; d[1] = (float)S; d[2] = (float)h;
-        }
-    }
-    if (lane == 0 && P.debug_out) {
-        float *d = P.debug_out + base * 3;
-        d[0] = 1.f; d[1] = my_S; d[2] = 1.f;
-    }
-    const u64 passed = __ballot(pass);
-    int tau;
-    if (P.algo == kToken) tau = passed == ~0ull ? 64 : __ffsll((long long)~passed) - 1;    // leading run of passes
-    else tau = passed ? 64 - __clzll((long long)passed) : 0;                               // last passing sub-block
-    if (lane == 0) P.accept_len[b] = tau;
-    SV_STAMP(10);
-    // the token drawn for position tau: its leader drew one, because a position whose test passes can become tau
-    y_out = tau <= gamma - 2 ? rowres_token(read_lane_u64(res, tau)) : -1;
-    // log2 w of the last row pair, for its residual (token verification: its residual is p - q)
-    lw_own = gamma > 1 && P.algo != kToken ? read_lane_double(lw_j, gamma - 2) : 0.0;
-    return tau;
-}
-
 // Clears the words of row slot `slot` of sequence b in one copy (one wave, all lanes, whole rows at a time: full
 // cache lines).  Slot gamma holds the words of the sequence's last target row and nothing else.
 __device__ __forceinline__ void clear_row_words(const FusedParams &P, const Words &W, int b, int slot)
@@ -865,6 +819,142 @@ __device__ __forceinline__ void report_gave_up(const FusedParams &P)
 }
 
 // ------------------------------------------------------------------ the kernel
+// The kernel's arguments once more, read from the kernel argument segment where a rarely taken part of the kernel
+// begins: what that part needs of them then lives in registers from there on, and not from the top of the kernel
+// through its hot part (where it would only be parked in lanes of a vector register and fetched back).
+__device__ __forceinline__ FusedParams reread_params()
+{
+    typedef __attribute__((address_space(4))) const unsigned char ArgByte;
+    ArgByte *kp = (ArgByte *)__builtin_amdgcn_kernarg_segment_ptr();      // (FusedParams is the only argument)
+    asm volatile("" : "+s"(kp));
+    FusedParams Q;
+#define SV_ARG(f) Q.f = *reinterpret_cast<__attribute__((address_space(4))) const decltype(Q.f) *>(kp + offsetof(FusedParams, f))
+    SV_ARG(target); SV_ARG(draft); SV_ARG(tokens); SV_ARG(draft_lens); SV_ARG(uniforms); SV_ARG(B); SV_ARG(gamma); SV_ARG(V);
+    SV_ARG(tstride); SV_ARG(dstride); SV_ARG(k); SV_ARG(kd); SV_ARG(k_eps); SV_ARG(algo); SV_ARG(nu); SV_ARG(group_seqs);
+    SV_ARG(inv_slots); SV_ARG(inv_wpr); SV_ARG(prune); SV_ARG(skip_last); SV_ARG(spin_limit); SV_ARG(resident); SV_ARG(pace);
+    SV_ARG(magic); SV_ARG(header); SV_ARG(gen); SV_ARG(copy_bytes); SV_ARG(accept_len); SV_ARG(next_token); SV_ARG(debug_out);
+    SV_ARG(words.ratio); SV_ARG(words.lw); SV_ARG(words.rowres); SV_ARG(words.pstat); SV_ARG(words.plast);
+    SV_ARG(words.pgrp); SV_ARG(words.qgrp); SV_ARG(words.spart);
+#ifdef SV_PROFILE
+    SV_ARG(prof);
+#endif
+#undef SV_ARG
+    return Q;
+}
+
+// ------------------------------------------------------------------ the leader of a row pair
+// One wave, the first of the last workgroup of row pair i of sequence b, once the row's ratio is out (and, where the
+// row's residual mass is formed, the wave's own share of it): what position i contributes to tau and Y.  Alg. 2 / 4:
+// the position's own accept test, eta_i < h_i, needs S_i, the sum of the row's partial sums; where it passes (and at
+// position 0, which is tau when no test passes) the leader draws the token that follows if this position becomes tau.
+// Alg. 1: the test of X_{i+1} was judged with the ratio; the position is tau where every test up to it has passed and
+// that one fails.  All of it happens while the later positions are still streaming: the leader of the sequence's last
+// row pair (`finisher`; gb is the sequence's draft length) then only picks up one word per position, judges the last
+// test, eta_gamma < w_gamma, writes tau and Y and hands the sequence's words over to the next call.
+// (A row whose residual mass is not formed has nothing to wait for here: its test fails.)
+// `values`: the row's L_p, L_q and log2 w_i as the wave left them in LDS; `res`: the finisher's first look at the
+// earlier positions' words (lane l: position l; 0 where the word was not there yet).
+template <typename T, bool ALIGNED, int LANE>
+__device__ __forceinline__ void lead_row(int b, int i_own, int gb, unsigned par, bool needed, bool candidate, bool finisher, u64 own_word,
+                                         double lw_next, u64 res, float eta_i, float eta_next, bool gave_up, const double *values, long long *stamps)
+{
+    const FusedParams P = reread_params();
+    const int lane = threadIdx.x & 63;
+    const int nu = P.nu;
+    const size_t seq_d = (size_t)b * P.gamma, seq_u = (size_t)b * (P.gamma + 1), drow = seq_d + i_own;
+    SV_STAMP(5);
+    const Words W = words_of(P, par);
+    const double Lp = values[0], Lq = values[1], log2w_row = values[2];
+    const float u = load_uniform(P.uniforms + seq_u + gb);
+    const bool token_algo = P.algo == kToken;
+    const bool next_passes = ratio_passes(own_word);             // Alg. 1: the test of X_{i+1}
+    // the finisher's first loads: the earlier positions' words (lane l: position l) and the last target row's words
+    const u64 *const res_word = W.rowres + seq_d + (lane < gb - 1 ? lane : 0);
+    const int e_lane = lane < nu ? lane : nu - 1;
+    const u64 *const last = W.plast + (size_t)b * nu;
+    u64 last_first = 0;
+    if (finisher) last_first = ld_u64(last + e_lane);
+    // the test of the last position, eta_gamma < h_gamma = w_gamma (Alg. 2 / 4), which the finisher judges first: where
+    // it passes, tau = gamma and nothing of this row's residual is needed
+    double w_last = 1.0;
+    bool last_passes = next_passes;                              // Alg. 1: the test of X_gamma
+    if (finisher && !token_algo) {
+        w_last = exp2_precise(P.algo == kGreedy ? fmin(lw_next, 100.0) : lw_next);
+        last_passes = (double)eta_next < fmin(w_last, 1.0);
+    }
+    AcceptTest test;
+    test.log2w = log2w_row; test.eta = eta_i; test.allowed = candidate; test.passes = false; test.w = 1.0; test.h = 1.0;
+    const bool has_test = !token_algo && i_own > 0;
+    // where the draw is wanted if the position's own test lets it through
+    bool want = token_algo ? candidate && !next_passes : true;
+    if (finisher && !token_algo && last_passes) want = false;
+    double S_own = 0.0;
+    int drawn = -1;
+    if (needed && (want || has_test || P.debug_out))
+        drawn = draw_from_row<T, ALIGNED, LANE>(P, W, W.pstat + drow * nu, b, i_own, 0, want, has_test, test,
+                                                Lp - log2w_row, Lq, u, S_own, gave_up);
+    const bool own_passes = token_algo ? next_passes : has_test && test.passes;
+    if (P.debug_out && lane == 0) {
+        // row i of the block: (w_i, S_i, h_i); Alg. 1 has no w, and its h_i = min(r_i, 1) comes from the ratio that
+        // the leader of the position before published
+        float *d = P.debug_out + (seq_u + i_own) * 3;
+        double h_i = test.h;
+        if (token_algo && i_own > 0) h_i = exp2_precise(fmin(unpack_ratio(wait_word(W.ratio + drow - 1, P.spin_limit, gave_up)), 0.0));
+        d[0] = i_own > 0 && !token_algo ? (float)test.w : 1.f; d[1] = (float)S_own; d[2] = i_own > 0 ? (float)h_i : 1.f;
+    }
+    if (!finisher) {
+        if (gave_up) report_gave_up(P);
+        if (lane == 0) st_u64(W.rowres + drow, gave_up ? kPoison64 : pack_rowres(own_passes, drawn));
+        SV_STAMP(15);
+        return;
+    }
+
+    // ---- the leader of a sequence's last row pair finishes the sequence: one word per earlier position
+    res = wait_word(res_word, res, lane < gb - 1, P.spin_limit, gave_up);
+    const u64 flags = __ballot(lane < gb - 1 && rowres_passes(res));                 // bit l: position l's word says "passes"
+    int tau;
+    if (token_algo) {
+        // bit l: the test of X_{l+1}; tau is the length of the leading run of passes
+        const u64 tests = flags | ((u64)(last_passes ? 1 : 0) << (gb - 1));
+        tau = __ffsll((long long)~tests) - 1;
+        if (tau > gb) tau = gb;
+    } else {
+        // bit l: the test of position l (none at position 0); tau is the last position whose test passes, else 0
+        const u64 tests = (flags & ~1ull) | ((u64)(own_passes ? 1 : 0) << (gb - 1)) | ((u64)(last_passes ? 1 : 0) << gb);
+        tau = tests ? 63 - __clzll((long long)tests) : 0;
+    }
+    if (lane == 0) P.accept_len[b] = tau;
+    if (P.debug_out && lane == 0) {
+        float *d = P.debug_out + (seq_u + gb) * 3;       // S_gamma = w_gamma: q_gamma == 0
+        d[0] = (float)w_last; d[1] = (float)w_last;
+        d[2] = token_algo ? (float)exp2_precise(fmin(unpack_ratio(own_word), 0.0)) : (float)fmin(w_last, 1.0);
+    }
+    SV_STAMP(10);
+    int y;
+    if (tau == gb) {
+        // every token was accepted: Y comes from the last target row itself
+        double total;
+        y = draw_from_row<T, ALIGNED, LANE>(P, W, last, b, gb, 1, true, false, test, 0.0, 0.0, u, total, gave_up);
+    } else if (tau == gb - 1) {
+        y = drawn;
+    } else {
+        y = rowres_token(read_lane_u64(res, tau));
+    }
+    SV_STAMP(12);
+    // every workgroup of the sequence has read the call count once the last target row's words are there (the row
+    // pairs' workgroups published words that this wave, or a leader it heard from, has waited for)
+    wait_word(last + e_lane, last_first, lane < nu, P.spin_limit, gave_up);
+    for (int e = lane + kWave; e < nu; e += kWave) wait_word(last + e, P.spin_limit, gave_up);
+    if (gave_up) report_gave_up(P);
+    if (lane == 0) {
+        // a wait that ran out anywhere on the way here leaves nothing to trust
+        if (gave_up) { P.accept_len[b] = -1; y = -1; }
+        P.next_token[b] = y;
+        __hip_atomic_store(P.gen + b, (int)(par ^ 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    SV_STAMP(6);
+}
+
 template <typename T, bool ALIGNED, int NW, int LANE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(LANE == kLaneLarge ? 3 : ElemTraits<T>::kVec == 8 ? SV_WAVES_SMALL : 4)))
 void fused_verify_kernel(const FusedParams P)
@@ -976,6 +1066,7 @@ void fused_verify_kernel(const FusedParams P)
             const int flag = row_flag;
             if (flag != 0) {
                 if (lane == 0) st_u64(W.plast + (size_t)U.b * nu + U.c, flag == 2 ? kPoison64 : pack_stat(-INFINITY, 0.f));
+                SV_STAMP(11);
                 return;
             }
         }
@@ -1053,9 +1144,13 @@ void fused_verify_kernel(const FusedParams P)
     bool candidate = true;           // whether this position can become tau: then its leader draws the token that would follow
     u64 own_word = 0;                // the leader's word of log2 r_{i+1}
     double lw_next = 0.0;            // the leader's log2 w_{i+1}
+    u64 res_first = 0;               // the finisher's first look at the earlier positions' words (lane l: position l)
     if (wave == 0) {
         // ---- L_p, L_q: the words of all workgroups of the row
         const Words W = SV_WORDS;
+        // (the earlier positions have had a row's lifetime to publish what they contribute: asked for now, their words
+        // come in with the row's, and the finisher does not wait for them at the end)
+        if (finisher && gb > 1) res_first = ld_u64(W.rowres + seq_d + (lane < gb - 1 ? lane : 0));
         float Mp, Mq;
         double Lp, Lq;
         const bool need_w = n_prev > 0 && !early;            // w_i still to come: the chain's word, or the ratios
@@ -1094,6 +1189,7 @@ void fused_verify_kernel(const FusedParams P)
             Lq = row_normaliser<NW>(W.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
             if (need_lane) wt = wait_word(w_word, wt, true, P.spin_limit, gave_up);
         }
+        SV_STAMP(7);
         if (leader) {
             // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for every later position and for whoever finishes
             // the sequence.  The sweeps scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To
@@ -1111,34 +1207,38 @@ void fused_verify_kernel(const FusedParams P)
             if (gave_up) report_gave_up(P);
             if (lane == 0) st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
         }
+        SV_STAMP(8);
         if (need_w) {
             if (!chain) wt = wait_word(SV_RATIO_WORD, wt, lane < n_prev, P.spin_limit, gave_up);
             log2w = chain ? unpack_ratio(read_lane_u64(wt, 0)) : read_lane_double(weights_from_ratios(P.algo, wt, n_prev), n_prev - 1);
         }
+        SV_STAMP(9);
         candidate = can_become_tau(P.algo, U.i, log2w, eta_i);
-        if (leader && chain) {
+        if (leader && (chain || finisher)) {
+            // (rounded as the word holds it: everybody goes by the same number)
             lw_next = unpack_ratio(pack_ratio(next_weight(P.algo, log2w, unpack_ratio(own_word), ratio_passes(own_word)), false));
             if (gave_up) report_gave_up(P);
-            if (lane == 0) st_u64(W.lw + drow, gave_up ? kPoison64 : pack_ratio(lw_next, false));
+            if (chain && lane == 0) st_u64(W.lw + drow, gave_up ? kPoison64 : pack_ratio(lw_next, false));
         }
         if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
         if (P.algo == kGreedy) log2w = fmin(log2w, 100.0);          // keeps w p finite in float
         // the second sweep's row constants: w p(x) = 2^(y_p - A) with A = L_p - log2 w, q(x) = 2^(y_q - L_q).  Their
         // integer parts meet the units' integer shifts in the exponent; the fractions are formed once, here, in double
-        const double A = Lp - log2w, Ai = rint(A), Qi = rint(Lq);
-        const double fq = exp2_precise(Qi - Lq), frho = exp2_precise((Ai - A) - (Qi - Lq));
+        // (only where there is a second sweep: the leader of a row without one is on its way to the row's word)
+        if (needed) {
+            const double A = Lp - log2w, Ai = rint(A), Qi = rint(Lq);
+            const double fq = exp2_precise(Qi - Lq), frho = exp2_precise((Ai - A) - (Qi - Lq));
+            if (lane == 0) { row_values[3] = Ai; row_values[4] = Qi; row_values[5] = fq; row_values[6] = frho; row_values[7] = 1.0 / frho; }
+        }
         if (lane == 0) {
             row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w;
-            row_values[3] = Ai; row_values[4] = Qi; row_values[5] = fq; row_values[6] = frho; row_values[7] = 1.0 / frho;
             row_flag = gave_up ? 2 : 1;
         }
         if (gave_up) report_gave_up(P);
         SV_STAMP(2);
     }
-    double S_own = 0.0;              // the leader's: S_i, summed over the row's partial sums
     if (needed) {
         __syncthreads();
-        const double Lp = row_values[0], Lq = row_values[1], log2w_row = row_values[2];
         const bool poisoned = row_flag == 2 || gave_up;
         SV_STAMP(3);
 
@@ -1168,73 +1268,9 @@ void fused_verify_kernel(const FusedParams P)
         acc = wave_sum(acc);
         if (lane == 0) st_u32(SV_WORDS.spart + drow * nu + U.c, poisoned ? kPoison32 : pack_partial(acc));
         SV_STAMP(4);
-        if (!leader) return;
-        const Words W = SV_WORDS;
-        // ---- the row's leader sums the row's partial sums and, if this position can become tau, draws the token that
-        // follows in that case - while the later positions are still streaming: whoever finishes the sequence then
-        // only picks both up
-        if (!finisher) {
-            const float u = load_uniform(P.uniforms + seq_u + gb);
-            const int drawn = draw_from_row<T, ALIGNED, LANE>(P, W, W.pstat + drow * nu, U.b, U.i, 0, candidate, Lp - log2w_row, Lq, u, S_own, gave_up);
-            if (gave_up) report_gave_up(P);
-            if (lane == 0) st_u64(W.rowres + drow, gave_up ? kPoison64 : pack_rowres((float)S_own, drawn));
-            return;
-        }
     }
-    if (!finisher) return;
-    // ---- the leader of a sequence's last row pair finishes the sequence
-    SV_STAMP(5);
-    const Words W = SV_WORDS;
-    const double Lp = row_values[0], Lq = row_values[1];
-    const float u = load_uniform(P.uniforms + seq_u + gb);
-    // what the tests need of the earlier positions, asked for at once: their ratios and (calls larger than one resident
-    // set) the weights their workgroups went by; in smaller calls those came from these same ratios
-    const u64 *const r_word = W.ratio + seq_d + (lane < gb - 1 ? lane : 0);
-    const u64 *const l_word = W.lw + seq_d + (lane > 0 && lane < gb ? lane - 1 : 0);        // lane j: the word of log2 w_j
-    u64 rw_all = gb > 1 ? ld_u64(r_word) : 0, lw_all = chain && gb > 1 ? ld_u64(l_word) : 0;
-    // (and, in the same round trip, the earlier positions' results and the sequence's uniforms: lane l gets eta_{l+1})
-    const u64 res_first = gb > 1 ? ld_u64(W.rowres + seq_d + (lane < gb - 1 ? lane : 0)) : 0;
-    const float eta_all = P.uniforms[seq_u + (lane < gb ? lane : gb - 1)];
-    // its own row's mass (the draw, if tau turns out to be this position, comes after the tests)
-    if (needed) draw_from_row<T, ALIGNED, LANE>(P, W, W.pstat + drow * nu, U.b, U.i, 0, false, 0.0, 0.0, u, S_own, gave_up);
-    // the last target row's words, asked for early: they are waited for before the sequence's call count moves on
-    const int e_lane = lane < nu ? lane : nu - 1;
-    const u64 *last = W.plast + (size_t)U.b * nu;
-    const u64 last_first = ld_u64(last + e_lane);
-    rw_all = wait_word(r_word, rw_all, lane < gb - 1, P.spin_limit, gave_up);
-    if (lane == gb - 1) rw_all = own_word;
-    // lane j: log2 w_{j+1} as position j + 1's workgroups saw it (lane gb - 1: this wave's own w_{gb})
-    double lw_seen;
-    if (chain) {
-        lw_all = wait_word(l_word, lw_all, lane > 0 && lane < gb, P.spin_limit, gave_up);
-        const double lw_j = lane > 0 && lane < gb ? unpack_ratio(lw_all) : 0.0;           // lane j: log2 w_j
-        lw_seen = __shfl_down(lw_j, 1, kWave);
-        if (lane == gb - 1) lw_seen = lw_next;
-    } else {
-        lw_seen = weights_from_ratios(P.algo, rw_all, gb);
-    }
-    int y = -1;
-    double lw_own;
-    const int tau = finish_sequence(P, W, U.b, gb, rw_all, lw_seen, (float)S_own, res_first, eta_all, y, lw_own, gave_up, stamps);
-    if (y < 0) {
-        // tau is the last row pair (its residual: this wave has the row's constants) or every token was
-        // accepted (Y comes from the last target row itself)
-        double total;
-        y = draw_from_row<T, ALIGNED, LANE>(P, W, tau == gb ? last : W.pstat + drow * nu, U.b, tau, tau == gb ? 1 : 0, true, Lp - lw_own, Lq, u, total, gave_up);
-    }
-    SV_STAMP(12);
-    // every workgroup of the sequence has read the call count once the last target row's words are there (the row
-    // pairs' workgroups published words that this wave, or a leader it heard from, has waited for)
-    wait_word(last + e_lane, last_first, lane < nu, P.spin_limit, gave_up);
-    for (int e = lane + kWave; e < nu; e += kWave) wait_word(last + e, P.spin_limit, gave_up);
-    if (gave_up) report_gave_up(P);
-    if (lane == 0) {
-        // a wait that ran out anywhere on the way here leaves nothing to trust
-        if (gave_up) { P.accept_len[U.b] = -1; y = -1; }
-        P.next_token[U.b] = y;
-        __hip_atomic_store(P.gen + U.b, (int)(par ^ 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    SV_STAMP(6);
+    if (!leader) return;
+    lead_row<T, ALIGNED, LANE>(U.b, U.i, gb, par, needed, candidate, finisher, own_word, lw_next, res_first, eta_i, eta_next, gave_up, row_values, stamps);
 #undef SV_RATIO_WORD
 #undef SV_LW_WORD
 #undef SV_WORDS
