@@ -160,15 +160,26 @@ def main():
         bufs = [torch.empty(half, dtype=torch.uint8, device=dev).fill_(0x3c) for _ in range(4)]
         probe_out = torch.empty(half // 4096, dtype=torch.float32, device=dev)
 
+        waits = (0, 0)
+
         def step_probe(i):
-            sv.spec_verify_debug_stream_probe(bufs[(2 * i) % 4], bufs[(2 * i + 1) % 4], probe_out, stream=stream.cuda_stream)
+            sv.spec_verify_debug_stream_probe(bufs[(2 * i) % 4], bufs[(2 * i + 1) % 4], probe_out, waits[0], waits[1],
+                                              stream=stream.cuda_stream)
 
         for i in range(8):
             step_probe(i)
         _, probe_ms = timed(max(args.steps // 4, 8), step_probe)
+        # the same with the waits a verifying workgroup has, as the per-workgroup timestamps of the tuning build show
+        # them at configuration 3 (about 1.5 us between a workgroup's first sweep and its look at log2 w_i; about
+        # 4.4 us for the quarter of the rows whose residual mass is formed), in units of 512 clocks
+        waits = (6, 18)
+        for i in range(8):
+            step_probe(i)
+        _, waits_ms = timed(max(args.steps // 4, 8), step_probe)
         floor = {"device_ms": probe_ms, "bytes": 2 * half, "GBps": 2 * half / (probe_ms * 1e-3) / 1e9,
                  "frac_of_peak": 2 * half / (probe_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                 "what": "spec_verify_debug_stream_probe: same launch shape and first-sweep arithmetic, no verification"}
+                 "what": "spec_verify_debug_stream_probe: same launch shape and first-sweep arithmetic, no verification",
+                 "device_ms_with_modelled_waits": waits_ms, "modelled_waits_x512_clocks": list(waits)}
         del bufs, probe_out
 
     for i in range(args.warmup):

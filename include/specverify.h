@@ -144,8 +144,13 @@ sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, voi
  * workgroup per 2 x 16 KB, eight 16-byte loads per lane issued up front, five waves per SIMD - and runs the first
  * sweep's arithmetic on them as bf16 (maximum, exp2, sum), with no traffic between workgroups; one float per wave goes
  * to `out` (bytes_each / 4096 floats).  What this kernel needs for a call's bytes is what no kernel of this shape that
- * also verifies can beat.  SV_ERR_INVALID_ARG for null, misaligned or ragged arguments.    */
-sv_status_t spec_verify_debug_stream_probe(const void *a, const void *b, size_t bytes_each, float *out, void *stream);
+ * also verifies can beat.  `short_waits`, `long_waits` (0 .. 64, units of 512 clocks): how long a workgroup keeps its
+ * registers after its sweep before it ends - `long_waits` for one in four groups of 16 neighbouring workgroups,
+ * `short_waits` for the others - which models the waits of a kernel that verifies (the look at the weight of the
+ * position; the wait for the row and the second sweep) without any of its traffic; 0, 0 is the floor itself.
+ * SV_ERR_INVALID_ARG for null, misaligned, ragged or out-of-range arguments.    */
+sv_status_t spec_verify_debug_stream_probe(const void *a, const void *b, size_t bytes_each, float *out,
+                                           int32_t short_waits, int32_t long_waits, void *stream);
 
 /*
  * Block verification (Alg. 2).

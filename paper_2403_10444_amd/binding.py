@@ -96,7 +96,8 @@ def load() -> ctypes.CDLL:
         lib.spec_verify_debug_copy.restype = ctypes.c_int
         lib.spec_verify_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         lib.spec_verify_debug_stream_probe.restype = ctypes.c_int
-        lib.spec_verify_debug_stream_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        lib.spec_verify_debug_stream_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                                       ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         lib.spec_sample_tokens.restype = ctypes.c_int
         lib.spec_sample_tokens.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_float,
                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -156,15 +157,18 @@ def spec_verify_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) ->
         raise SpecVerifyError(code, status_string(code))
 
 
-def spec_verify_debug_stream_probe(a: torch.Tensor, b: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+def spec_verify_debug_stream_probe(a: torch.Tensor, b: torch.Tensor, out: torch.Tensor, short_waits: int = 0,
+                                   long_waits: int = 0, stream=None) -> None:
     """The library's streaming probe (the floor of the verification kernel's launch shape) over two equally large
-    device buffers; `out` takes one float per 4096 bytes of `a`."""
+    device buffers; `out` takes one float per 4096 bytes of `a`.  `short_waits`, `long_waits` (units of 512 clocks):
+    the modelled waits of a verifying kernel, see the header; 0, 0 is the floor."""
     nbytes = a.numel() * a.element_size()
     if b.numel() * b.element_size() != nbytes or out.numel() * 4096 < nbytes or out.dtype != torch.float32:
         raise ValueError("a and b must have the same size in bytes and out one float32 per 4096 bytes of a")
     if stream is None:
         stream = torch.cuda.current_stream(a.device).cuda_stream
-    code = load().spec_verify_debug_stream_probe(a.data_ptr(), b.data_ptr(), nbytes, out.data_ptr(), stream)
+    code = load().spec_verify_debug_stream_probe(a.data_ptr(), b.data_ptr(), nbytes, out.data_ptr(),
+                                                 int(short_waits), int(long_waits), stream)
     if code != SV_OK:
         raise SpecVerifyError(code, status_string(code))
 

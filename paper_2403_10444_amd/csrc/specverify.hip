@@ -364,7 +364,7 @@ sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, voi
 // reads 4 KB of each of two buffers with eight 16-byte loads per lane, all issued up front), the first sweep's
 // arithmetic on bf16 (unpack, maximum, exp2, sum), five waves per SIMD, no traffic between workgroups.
 namespace { __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5)))
-void stream_probe_kernel(const uint4 *a, const uint4 *b, float *out)
+void stream_probe_kernel(const uint4 *a, const uint4 *b, float *out, int short_waits, int long_waits)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint4 *pa = a + (size_t)blockIdx.x * 1024 + wave * 256 + lane;
@@ -385,17 +385,27 @@ void stream_probe_kernel(const uint4 *a, const uint4 *b, float *out)
         const u64 word = first_sweep_row(x, 1.8f, shift);
         res += stat_sum(word) + shift;
     }
+    // the waits of a verifying kernel, modelled: a workgroup keeps its registers for a while after its sweep (the look
+    // at log2 w_i; for one in four "rows" of 16 neighbouring workgroups the wait for the row and the second sweep)
+    const int waits = ((blockIdx.x >> 4) & 3) == 0 ? long_waits : short_waits;
+    if (waits > 0) {
+        __syncthreads();
+        for (int i = 0; i < waits; ++i) __builtin_amdgcn_s_sleep(8);        // 512 clocks each
+        __syncthreads();
+    }
     if (lane == 0) out[(size_t)blockIdx.x * 4 + wave] = res;
 } }
 
-sv_status_t spec_verify_debug_stream_probe(const void *a, const void *b, size_t bytes_each, float *out, void *stream)
+sv_status_t spec_verify_debug_stream_probe(const void *a, const void *b, size_t bytes_each, float *out,
+                                           int32_t short_waits, int32_t long_waits, void *stream)
 {
     if (!a || !b || !out || bytes_each == 0 || bytes_each % 16384 != 0) return SV_ERR_INVALID_ARG;
+    if (short_waits < 0 || long_waits < 0 || short_waits > 64 || long_waits > 64) return SV_ERR_INVALID_ARG;
     if (((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15u) != 0) return SV_ERR_INVALID_ARG;
     const size_t blocks = bytes_each / 16384;
     if (blocks > 0x7fffffffull) return SV_ERR_UNSUPPORTED;
     stream_probe_kernel<<<(unsigned)blocks, 256, 0, static_cast<hipStream_t>(stream)>>>(
-        static_cast<const uint4 *>(a), static_cast<const uint4 *>(b), out);
+        static_cast<const uint4 *>(a), static_cast<const uint4 *>(b), out, short_waits, long_waits);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 

@@ -108,6 +108,22 @@ def test_copy_probe_validates_its_arguments():
     assert lib.spec_verify_debug_copy(0x1008, 0x2000, 256, None) == binding.SV_ERR_INVALID_ARG    # misaligned
 
 
+def test_stream_probe_validates_its_arguments():
+    lib = sv.load()
+
+    def call(a=0x10000, b=0x20000, nbytes=16384, out=0x30000, short=0, long=0):
+        return lib.spec_verify_debug_stream_probe(a, b, nbytes, out, short, long, None)
+
+    assert call(a=None) == binding.SV_ERR_INVALID_ARG
+    assert call(b=None) == binding.SV_ERR_INVALID_ARG
+    assert call(out=None) == binding.SV_ERR_INVALID_ARG
+    assert call(nbytes=0) == binding.SV_ERR_INVALID_ARG
+    assert call(nbytes=16384 + 16) == binding.SV_ERR_INVALID_ARG       # whole workgroups only
+    assert call(a=0x10008) == binding.SV_ERR_INVALID_ARG               # misaligned
+    assert call(short=-1) == binding.SV_ERR_INVALID_ARG
+    assert call(long=65) == binding.SV_ERR_INVALID_ARG
+
+
 def test_sample_tokens_validates_its_arguments():
     lib = sv.load()
     ok = dict(logits=0x1000, rows=4, V=10, dtype=0, T=1.0, uniforms=0x1000, tokens=0x1000)

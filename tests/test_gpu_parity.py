@@ -446,3 +446,19 @@ def test_a_wait_that_runs_out_is_reported_not_hung(path):
     parity.compare(parity.run_gpu("block", inp, cfg.temperature, workspace=ws),
                    parity.run_oracle("block", inp, cfg.temperature))
     assert sv.spec_verify_workspace_check(ws, cfg.B, cfg.gamma, cfg.V) == 0
+
+
+def test_stream_probe_runs_with_and_without_modelled_waits():
+    """The measurement hook behind bench.py's floor: it reads its two buffers whole (every wave's float is the sweep's
+    result for constant logits) whatever waits are modelled."""
+    nbytes = 5 * 16384
+    a = torch.full((nbytes,), 0x3c, dtype=torch.uint8, device="cuda")
+    b = torch.full((nbytes,), 0x3c, dtype=torch.uint8, device="cuda")
+    outs = []
+    for waits in ((0, 0), (2, 5)):
+        out = torch.full((nbytes // 4096,), float("nan"), dtype=torch.float32, device="cuda")
+        sv.spec_verify_debug_stream_probe(a, b, out, waits[0], waits[1])
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all())
+        outs.append(out.cpu())
+    assert bool((outs[0] == outs[1]).all()) and bool((outs[0] == outs[0][0]).all())
