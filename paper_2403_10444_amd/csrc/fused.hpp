@@ -1124,6 +1124,7 @@ void fused_verify_kernel(const FusedParams P)
         const Words W = SV_WORDS;
         // (where the look at the start came too early for the chain's word, the second look goes out in front of the
         // workgroup's own words: one round trip for both, not one after the other)
+        if (early) SV_NOTE(14, read_lane_u64(wt, 0) != 0 ? 1 : 2);
         if (early && read_lane_u64(wt, 0) == 0) wt = ld_u64(SV_LW_WORD);
         publish_group_words(wave_words, W.pgrp + drow * nwg + wg_x, W.qgrp + drow * nwg + wg_x);
         bool wanted = true;
