@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="distinct input sets rotated through")
     ap.add_argument("--sigma-draft", type=float, default=None,
                     help="draft noise of the workload (configuration 4 is swept over 0.5, 1.5, 3.0; 0.5 = high acceptance)")
+    ap.add_argument("--graph", type=int, default=0, metavar="N",
+                    help="launch the timed calls as replays of a HIP graph of N calls (0: one launch per call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed region: no floor probe, no second leg with every residual mass formed (for "
@@ -112,14 +114,15 @@ def main():
             s["target_logits"] = torch.softmax(s["target_logits"].float() / cfg.temperature, -1).to(dt)
             s["draft_logits"] = torch.softmax(s["draft_logits"].float() / cfg.temperature, -1).to(dt)
 
-    def step(i):
+    def step(i, on=None):
         s = sets[i % len(sets)]
+        on = stream.cuda_stream if on is None else on
         if args.input == "probs":
             sv.spec_verify_probs(args.algo, s["target_logits"], s["draft_logits"], s["draft_tokens"], s["uniforms"],
-                                 workspace=ws, accept_len=tau, next_token=y, stream=stream.cuda_stream)
+                                 workspace=ws, accept_len=tau, next_token=y, stream=on)
             return
         fn(s["target_logits"], s["draft_logits"], s["draft_tokens"], s["uniforms"], cfg.temperature,
-           workspace=ws, accept_len=tau, next_token=y, stream=stream.cuda_stream)
+           workspace=ws, accept_len=tau, next_token=y, stream=on)
 
     if args.copy_probe > 0:
         src = torch.full((COPY_PROBE_BYTES,), 1, dtype=torch.uint8, device=dev)
@@ -184,7 +187,24 @@ def main():
 
     for i in range(args.warmup):
         step(i)
-    wall, dev_ms = timed(args.steps, step)
+    # On request the timed calls are replays of a HIP graph of `graph_calls` calls (the calls allocate nothing and record
+    # no memset); steps = calls.
+    graph_calls = max(args.graph, 0)
+    steps_done = args.steps
+    if graph_calls:
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            on = torch.cuda.current_stream(dev).cuda_stream
+            for i in range(graph_calls):
+                step(i, on)
+        replays = max(1, (args.steps + graph_calls - 1) // graph_calls)
+        steps_done = replays * graph_calls
+        graph.replay()
+        wall, dev_ms = timed(replays, lambda i: graph.replay())
+        dev_ms /= graph_calls
+    else:
+        wall, dev_ms = timed(args.steps, step)
     healthy("timed region")
     mean_tau = float(tau.float().mean().item())
 
@@ -225,24 +245,27 @@ def main():
                  "pruned_row_pairs": sum(left_out) / len(left_out),
                  "last_target_rows_not_read": sum(last_skipped) / len(last_skipped)}
 
-    ms_per_step = wall / args.steps * 1e3
-    calls_per_s = args.steps / wall
+    ms_per_step = wall / steps_done * 1e3
+    calls_per_s = steps_done / wall
     achieved = cfg.algorithmic_bytes / (dev_ms * 1e-3) / 1e9
     out = {
         "metric": "verify calls/sec", "value": calls_per_s, "unit": "calls/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": steps_done, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "algo": args.algo, "B": cfg.B, "gamma": cfg.gamma, "V": cfg.V,
                    "logit_dtype": cfg.dtype, "temperature": cfg.temperature, "input_sets": len(sets), "path": args.path,
-                   "input": args.input},
+                   "input": args.input,
+                   "launch": f"replays of a HIP graph of {graph_calls} calls" if graph_calls else "one launch per call"},
         "seq_verifications_per_s": calls_per_s * cfg.B,
         "mean_accept_len": mean_tau,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(cfg.name, args.algo)
                      if args.path == "default" and args.input == "logits" else None,
-                     "kernel": "whole call: fused_verify_kernel, the call's only kernel on the default path "
+                     "kernel": "whole call: tiny_verify_kernel (one workgroup per sequence), the call's only kernel"
+                               if args.input == "logits" and args.path == "default" and (2 * cfg.gamma + 1) * cfg.V <= 14336 else
+                               "whole call: fused_verify_kernel, the call's only kernel on the default path "
                                "(four staged kernels with --path staged)" if args.input == "logits" else
                                "whole call: probs_weights_kernel, probs_residual_kernel, probs_finalize_kernel",
                      "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms, **extra,

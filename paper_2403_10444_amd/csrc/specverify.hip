@@ -17,6 +17,7 @@
 #include "probs.hpp"
 #include "sample.hpp"
 #include "staged.hpp"
+#include "tiny.hpp"
 
 namespace {
 
@@ -24,7 +25,7 @@ using namespace sv;
 
 constexpr int kDefaultSpinLimit = 1 << 20;
 
-std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused; 3 / 4: fused with small / large units (testing hook)
+std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused, 5 one workgroup per sequence (testing hook; 3 / 4: fused with small / large units)
 std::atomic<int> g_spin_limit{kDefaultSpinLimit};
 std::atomic<int> g_lane{0};                        // 0 auto, 32 or 64: logits per lane of the fused kernel's units (testing hook)
 #ifdef SV_PROFILE
@@ -159,6 +160,30 @@ sv_status_t launch_probs(int algo, const void *target_v, const void *draft_v, co
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
+// Whether a sequence's 2 gamma + 1 rows fit the LDS of one workgroup.
+bool tiny_ok(int gamma, int V) { return (size_t)(2 * gamma + 1) * (size_t)V <= (size_t)kTinyMaxFloats; }
+
+template <typename T>
+sv_status_t launch_tiny(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
+                        size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd,
+                        char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out, hipStream_t stream)
+{
+    if (!tiny_ok(gamma, V)) return SV_ERR_UNSUPPORTED;
+    FusedParams P = {};
+    P.target = target; P.draft = draft; P.tokens = tokens; P.draft_lens = draft_lens; P.uniforms = uniforms;
+    P.B = B; P.gamma = gamma; P.V = V; P.tstride = tstride; P.dstride = dstride;
+    P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
+    P.magic = workspace_magic(B, gamma, V);
+    P.inv_wpr = V > 1 ? (unsigned)(0x100000000ull / (unsigned)V) + 1u : 0u;
+    P.header = reinterpret_cast<int *>(ws);
+    P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
+#ifdef SV_PROFILE
+    P.prof = g_prof.load();
+#endif
+    tiny_verify_kernel<T><<<(unsigned)B, kTinyThreads, 0, stream>>>(P);
+    return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
 template <typename T, bool ALIGNED>
 sv_status_t launch_fused(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
                          size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
@@ -268,6 +293,12 @@ sv_status_t verify_entry(int algo, bool probs, const void *target, const void *d
     }
     const int path = g_path.load();
     if (path == 2 && !L.fused_ok) return SV_ERR_UNSUPPORTED;
+    // sequences small enough for one workgroup each need nothing between workgroups
+    if (path == 5 || (path == 0 && tiny_ok(gamma, V))) {
+        return dtype == SV_DTYPE_F32
+            ? launch_tiny<float>(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, ws, accept_len, next_token, debug_out, stream)
+            : launch_tiny<bf16_t>(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, ws, accept_len, next_token, debug_out, stream);
+    }
 
 #define SV_ARGS algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, L, ws, \
                 accept_len, next_token, debug_out, stream
@@ -338,7 +369,7 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
 
 void spec_verify_debug_config(int32_t path, int32_t spin_limit)
 {
-    g_path.store(path >= 0 && path <= 2 ? path : path == 3 || path == 4 ? 2 : 0);
+    g_path.store((path >= 0 && path <= 2) || path == 5 ? path : path == 3 || path == 4 ? 2 : 0);
     g_lane.store(path == 3 ? kLaneSmall : path == 4 ? kLaneLarge : 0);
     g_spin_limit.store(spin_limit >= 0 ? spin_limit : kDefaultSpinLimit);
 }
