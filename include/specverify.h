@@ -93,8 +93,10 @@ sv_status_t spec_verify_workspace_init(void *workspace, size_t workspace_bytes,
 sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_t gamma, int32_t V,
                                         void *stream);
 
-/* Testing hook, process-wide: `path` 0 = the library's choice (the fused kernel where it
- * takes the shape, else the staged kernels), 1 = the four-launch staged kernels, 2 = the
+/* Testing hook, process-wide: `path` 0 = the library's choice (sequences whose 2 gamma + 1 rows fit
+ * into LDS together, (2 gamma + 1) V <= 14336: the kernel of one workgroup per sequence; else the
+ * fused kernel where it takes the shape, else the staged kernels), 5 = that one-workgroup-per-
+ * sequence kernel (larger sequences are then refused), 1 = the four-launch staged kernels, 2 = the
  * single-launch fused kernel (takes V <= 128 * 8192 and a device that keeps four rows'
  * workgroups resident; other shapes are then refused), 3 / 4 = the fused kernel with its
  * small / large units (32 / 64 logits of a row per lane; large ones exist for bf16 rows on
