@@ -1040,8 +1040,9 @@ void fused_verify_kernel(const FusedParams P)
     bool gave_up = false;
 
     // Two ways to w_i.  Calls larger than one resident set ("chain"): the leader of row pair i - 1 publishes log2 w_i
-    // itself, one word that the workgroups of position i read - position i starts a resident set after position i - 1, the
-    // word is there long before it is asked for.  Smaller calls, where all positions run at once: the first wave of a
+    // itself, one word that the workgroups of position i read at their start - position i starts up to a resident set
+    // after position i - 1 (where a position is less than that, the word is often not there yet, and a second look goes
+    // out with the workgroup's own words).  Smaller calls, where all positions run at once: the first wave of a
     // workgroup reads the ratios of all earlier positions (lane j: the word of log2 r_{j+1}) and forms w_i from them.
     const int n_prev = U.i;                                   // ratios that w_i is made of
     const bool chain = P.prune != 0;
