@@ -21,6 +21,9 @@ MARGIN = 1e-6
 # counts per configuration are written out at the end of a test session (see record()).
 S_RTOL = 1e-5
 S_FLOOR = 6e-7
+# ... and their share is bounded: of a comparison's rows (where there are at least 200) at most this fraction may lie
+# outside 1e-5 relative (measured over the five configurations: at most 2.4 % on the fused kernel, 3.0 % on the staged one)
+S_OUTSIDE_MAX = 0.05
 
 # reports of this session's comparisons, for the per-configuration summaries
 RECORDS = []
@@ -111,6 +114,8 @@ def compare(gpu, ref, rows=None, label="", greedy=False):
     assert report["unexcused"] == 0, f"unexcused (tau, Y) mismatches: {report}"
     assert np.all((g_tau >= 0) & (g_tau <= r_dbg.shape[1] - 1)), report
     assert np.all(s_err <= s_tol), f"residual mass out of tolerance: {report}"
+    assert report["S_rows"] < 200 or report["S_rows_outside_1e-5_rel"] <= S_OUTSIDE_MAX * report["S_rows"], \
+        f"too many residual masses outside 1e-5 relative: {report}"
     assert report["max_w_rel_err"] <= 2e-5, report
     assert report["max_h_err_over_tol"] <= 1.0, report
     return report
