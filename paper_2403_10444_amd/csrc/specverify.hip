@@ -84,14 +84,6 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
 
 template <typename T> constexpr int dtype_bytes() { return ElemTraits<T>::kVec == 4 ? 4 : 2; }
 
-// Waits (of 64 clocks) per row between the load requests of the first resident set's rows: three quarters of the time
-// one row pair's bytes take at about 6 TB/s and 2.1 GHz (measured at B = 64, gamma = 8, V = 128256: 0.75 is the best of
-// 0 .. 1.5 in steps of a quarter; 0 costs 1.2 us of 58, 1.25 and more cost more than they gain).
-float pace_units(double row_pair_bytes)
-{
-    return (float)(0.75 * row_pair_bytes / 6.0e12 * 2.1e9 / 64.0);
-}
-
 // Workgroups of a kernel that the current device keeps resident at once (cached per kernel).
 template <typename K>
 int resident_workgroups(K kernel, std::atomic<int> &cache)
@@ -232,10 +224,6 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     P.prune = g_lane.load() != 0 || (size_t)wpr * P.group_seqs * n_groups * (gamma + 1) > (size_t)capacity ? 1 : 0;
     P.skip_last = P.prune;
     P.spin_limit = g_spin_limit.load();
-    P.resident = capacity;
-    // pacing of the first resident set (only where there is a second one): one row pair's bytes at about 6 TB/s, in
-    // units of 64 clocks at about 2.1 GHz, less the rate at which the workgroups start anyway
-    P.pace = P.prune ? pace_units((double)V * (dtype_bytes<T>() * 2)) : 0.f;
     P.magic = workspace_magic(B, gamma, V);
     P.header = reinterpret_cast<int *>(ws);
     P.gen = reinterpret_cast<int *>(ws + L.off_gen);
@@ -402,9 +390,9 @@ void stream_probe_kernel(const uint4 *a, const uint4 *b, float *out, int short_w
     const uint4 *pb = b + (size_t)blockIdx.x * 1024 + wave * 256 + lane;
     uint4 va[4], vb[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) va[j] = pa[j * 64];
+    for (int j = 0; j < 4; ++j) va[j] = load_streamed(pa + j * 64);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) vb[j] = pb[j * 64];
+    for (int j = 0; j < 4; ++j) vb[j] = load_streamed(pb + j * 64);
     float res = 0.f;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
