@@ -515,15 +515,6 @@ template <typename T, int LANE> struct RawSlice<T, true, LANE> {
 };
 template <typename T, int LANE> struct RawSlice<T, false, LANE> { };      // the element-wise path loads when it unpacks
 
-// Sixteen bytes of a row that is read once: a non-temporal load, which leaves the caches to what is used again (the words
-// that cross workgroups, the kernel's arguments): 55.9 -> 54.5 us at B = 64, gamma = 8, V = 128256.
-__device__ __forceinline__ uint4 load_streamed(const void *p)
-{
-    typedef unsigned v4u __attribute__((ext_vector_type(4)));
-    const v4u t = __builtin_nontemporal_load(static_cast<const v4u *>(p));
-    return make_uint4(t.x, t.y, t.z, t.w);
-}
-
 // Vector v of a lane starts at element first + v * 64 * kVec of the row, so one load instruction of
 // the wave covers 1 KB of contiguous memory.
 template <typename T, bool ALIGNED, int LANE>
