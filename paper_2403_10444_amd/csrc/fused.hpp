@@ -915,11 +915,12 @@ __device__ __forceinline__ void lead_row(int b, int i_own, int gb, unsigned par,
         // bit l: the test of X_{l+1}; tau is the length of the leading run of passes
         const u64 tests = flags | ((u64)(last_passes ? 1 : 0) << (gb - 1));
         tau = __ffsll((long long)~tests) - 1;
-        if (tau > gb) tau = gb;
+        if (tau < 0 || tau > gb) tau = gb;                       // (a draft of 64 tokens, all accepted: no zero bit)
     } else {
         // bit l: the test of position l (none at position 0); tau is the last position whose test passes, else 0
-        const u64 tests = (flags & ~1ull) | ((u64)(own_passes ? 1 : 0) << (gb - 1)) | ((u64)(last_passes ? 1 : 0) << gb);
-        tau = tests ? 63 - __clzll((long long)tests) : 0;
+        // (the last position's test apart: with a draft of 64 tokens it has no bit in the word)
+        const u64 tests = (flags & ~1ull) | ((u64)(own_passes ? 1 : 0) << (gb - 1));
+        tau = last_passes ? gb : tests ? 63 - __clzll((long long)tests) : 0;
     }
     if (lane == 0) P.accept_len[b] = tau;
     if (P.debug_out && lane == 0) {

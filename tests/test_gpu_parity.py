@@ -137,8 +137,9 @@ def test_unaligned_base_pointers(algo, path):
 
 
 @pytest.mark.parametrize("algo", ["block", "token", "greedy"])
-def test_identical_models_accept_everything(algo):
-    cfg = _custom(16, 5, 20000, "bf16", sigma_t=4.0)
+@pytest.mark.parametrize("gamma", [5, 64])          # (64: the longest draft - every bit of the word of test results is used)
+def test_identical_models_accept_everything(algo, gamma, path):
+    cfg = _custom(16 if gamma == 5 else 3, gamma, 20000 if gamma == 5 else 9000, "bf16", sigma_t=4.0)
     inp = workloads.generate(cfg, seed=5, device=DEV)
     inp["draft_logits"] = inp["target_logits"][:, :cfg.gamma].contiguous()
     gpu = parity.run_gpu(algo, inp, 0.7)
