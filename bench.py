@@ -75,7 +75,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed region: no floor probe, no second leg with every residual mass formed (for "
                          "profiler runs, whose per-kernel averages should hold the timed launches only)")
-    ap.add_argument("--path", default="default", choices=["default", "staged", "fused", "fused-small", "fused-large"],
+    ap.add_argument("--path", default="default", choices=["default", "staged", "fused", "fused-small", "fused-large", "tiny", "resident"],
                     help="kernel path (testing hook of the library)")
     ap.add_argument("--spin-limit", type=int, default=-1,
                     help="bound of the fused kernel's waits in polls (testing hook; 0 makes results invalid)")
@@ -90,10 +90,11 @@ def main():
 
     import torch
     import paper_2403_10444_amd as sv
+    from paper_2403_10444_amd import binding
     import workloads
 
     sv.load()
-    sv.spec_verify_debug_config({"default": 0, "staged": 1, "fused": 2, "fused-small": 3, "fused-large": 4}[args.path], args.spin_limit)
+    sv.spec_verify_debug_config({"default": 0, "staged": 1, "fused": 2, "fused-small": 3, "fused-large": 4, "tiny": 5, "resident": 7}[args.path], args.spin_limit)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -207,6 +208,14 @@ def main():
         wall, dev_ms = timed(args.steps, step)
     healthy("timed region")
     mean_tau = float(tau.float().mean().item())
+    # which kernels the timed calls were (the library chooses by the shape of the call)
+    kernel_text = {
+        binding.SV_KERNEL_STAGED: "whole call: the four staged kernels (row_stats, prefix_weights, residual, finalize)",
+        binding.SV_KERNEL_FUSED: "whole call: fused_verify_kernel, the call's only kernel",
+        binding.SV_KERNEL_TINY: "whole call: tiny_verify_kernel (one workgroup per sequence), the call's only kernel",
+        binding.SV_KERNEL_RESIDENT: "whole call: resident_verify_kernel (calls of few resident sets), the call's only kernel",
+        binding.SV_KERNEL_PROBS: "whole call: probs_weights_kernel, probs_residual_kernel, probs_finalize_kernel",
+    }[sv.spec_verify_debug_last_kernel()]
 
     # What the measured time depends on besides the bytes: the kernels leave out residual masses that cannot matter
     # (positions whose test fails whatever S_i is) and do not read a last target row that cannot be drawn from.  So the
@@ -263,11 +272,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(cfg.name, args.algo)
                      if args.path == "default" and args.input == "logits" else None,
-                     "kernel": "whole call: tiny_verify_kernel (one workgroup per sequence), the call's only kernel"
-                               if args.input == "logits" and args.path == "default" and (2 * cfg.gamma + 1) * cfg.V <= 14336 else
-                               "whole call: fused_verify_kernel, the call's only kernel on the default path "
-                               "(four staged kernels with --path staged)" if args.input == "logits" else
-                               "whole call: probs_weights_kernel, probs_residual_kernel, probs_finalize_kernel",
+                     "kernel": kernel_text,
                      "algorithmic_bytes_per_launch": cfg.algorithmic_bytes, "device_ms_per_launch": dev_ms, **extra,
                      "floor_of_launch_shape": floor},
     }

@@ -93,10 +93,13 @@ sv_status_t spec_verify_workspace_init(void *workspace, size_t workspace_bytes,
 sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_t gamma, int32_t V,
                                         void *stream);
 
-/* Testing hook, process-wide: `path` 0 = the library's choice (sequences whose 2 gamma + 1 rows fit
- * into LDS together, (2 gamma + 1) V <= 14336: the kernel of one workgroup per sequence; else the
- * fused kernel where it takes the shape, else the staged kernels), 5 = that one-workgroup-per-
- * sequence kernel (larger sequences are then refused), 1 = the four-launch staged kernels, 2 = the
+/* Testing hook, process-wide: `path` 0 = the library's choice by the shape of the call: sequences whose
+ * 2 gamma + 1 rows fit into LDS together, (2 gamma + 1) V <= 14336: the kernel of one workgroup per
+ * sequence; else, calls of at most three times the workgroups that the device keeps resident and rows
+ * of at most 32 * 8192 logits: the kernel for calls of few resident sets; else the fused kernel where it
+ * takes the shape, else the staged kernels.  5 = the one-workgroup-per-sequence kernel, 7 = the
+ * kernel for calls of few resident sets (calls beyond their limits are then refused), 1 = the
+ * four-launch staged kernels, 2 = the
  * single-launch fused kernel (takes V <= 128 * 8192 and a device that keeps four rows'
  * workgroups resident; other shapes are then refused), 3 / 4 = the fused kernel with its
  * small / large units (32 / 64 logits of a row per lane; large ones exist for bf16 rows on
@@ -105,8 +108,18 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
  * does only in calls larger than one resident set of workgroups: residual masses that cannot
  * matter are left out, the last target row is read only where every token can be accepted, and
  * w_i travels from position to position as one published word); `spin_limit` bounds every wait
- * inside the fused kernel in polls (negative: default).                                   */
+ * inside the kernels that wait for each other's words, in polls (negative: default).        */
 void spec_verify_debug_config(int32_t path, int32_t spin_limit);
+
+/* Testing hook: which kernels the last verification call of this process launched (0 before the first).  */
+enum {
+    SV_KERNEL_STAGED = 1,     /* the four staged kernels                                   */
+    SV_KERNEL_FUSED = 2,      /* the single-launch fused kernel                            */
+    SV_KERNEL_TINY = 5,       /* one workgroup per sequence                                */
+    SV_KERNEL_RESIDENT = 7,   /* the kernel for calls of few resident sets                 */
+    SV_KERNEL_PROBS = 8       /* the three kernels that take probabilities                 */
+};
+int32_t spec_verify_debug_last_kernel(void);
 
 #ifdef SPECVERIFY_PROFILE_BUILD
 /* Tuning builds of the library only (compiled with -DSV_PROFILE; the product library exports no such symbol and

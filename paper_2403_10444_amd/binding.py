@@ -32,6 +32,7 @@ EXPORTED = (
     "spec_verify_workspace_init",
     "spec_verify_workspace_check",
     "spec_verify_debug_config",
+    "spec_verify_debug_last_kernel",
     "spec_verify_debug_copy",
     "spec_verify_debug_stream_probe",
     "spec_sample_tokens",
@@ -88,6 +89,8 @@ def load() -> ctypes.CDLL:
         lib.spec_verify_workspace_check.restype = ctypes.c_int
         lib.spec_verify_workspace_check.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                                     ctypes.c_int32, ctypes.c_void_p]
+        lib.spec_verify_debug_last_kernel.restype = ctypes.c_int32
+        lib.spec_verify_debug_last_kernel.argtypes = []
         lib.spec_verify_debug_config.restype = None
         lib.spec_verify_debug_config.argtypes = [ctypes.c_int32, ctypes.c_int32]
         if hasattr(lib, "spec_verify_debug_profile"):          # tuning builds only
@@ -133,6 +136,14 @@ def spec_verify_workspace_check(workspace: torch.Tensor, B: int, gamma: int, V: 
 
 def spec_verify_debug_config(path: int = 0, spin_limit: int = -1) -> None:
     load().spec_verify_debug_config(int(path), int(spin_limit))
+
+
+SV_KERNEL_STAGED, SV_KERNEL_FUSED, SV_KERNEL_TINY, SV_KERNEL_RESIDENT, SV_KERNEL_PROBS = 1, 2, 5, 7, 8
+
+
+def spec_verify_debug_last_kernel() -> int:
+    """Which kernels the last verification call of this process launched (SV_KERNEL_*; 0 before the first)."""
+    return int(load().spec_verify_debug_last_kernel())
 
 
 def spec_verify_debug_profile(buffer) -> None:

@@ -18,6 +18,7 @@
 #include "sample.hpp"
 #include "staged.hpp"
 #include "tiny.hpp"
+#include "resident.hpp"
 
 namespace {
 
@@ -25,8 +26,9 @@ using namespace sv;
 
 constexpr int kDefaultSpinLimit = 1 << 20;
 
-std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused, 5 one workgroup per sequence (testing hook; 3 / 4: fused with small / large units)
+std::atomic<int> g_path{0};                       // 0 auto, 1 staged, 2 fused, 5 one workgroup per sequence, 7 the kernel for calls of one resident set (testing hook; 3 / 4: fused with small / large units)
 std::atomic<int> g_spin_limit{kDefaultSpinLimit};
+std::atomic<int> g_last_kernel{0};                  // the kernels of the last verification call that was launched (SV_KERNEL_*)
 std::atomic<int> g_lane{0};                        // 0 auto, 32 or 64: logits per lane of the fused kernel's units (testing hook)
 #ifdef SV_PROFILE
 std::atomic<long long *> g_prof{nullptr};          // device buffer for per-workgroup timestamps (tuning builds only)
@@ -176,6 +178,56 @@ sv_status_t launch_tiny(int algo, const void *target, const void *draft, const i
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
+// The arguments that the kernels working through the control words share: the inputs, the outputs, the words.
+FusedParams word_params(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
+                        size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
+                        char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out)
+{
+    FusedParams P = {};
+    P.target = target; P.draft = draft; P.tokens = tokens; P.draft_lens = draft_lens; P.uniforms = uniforms;
+    P.tstride = tstride; P.dstride = dstride;
+    P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
+    P.nu = L.nu;
+    P.spin_limit = g_spin_limit.load();
+    P.magic = workspace_magic(B, gamma, V);
+    P.header = reinterpret_cast<int *>(ws);
+    P.gen = reinterpret_cast<int *>(ws + L.off_gen);
+    P.words.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
+    P.words.lw = reinterpret_cast<u64 *>(ws + L.off_lw);
+    P.words.rowres = reinterpret_cast<u64 *>(ws + L.off_rowres);
+    P.words.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
+    P.words.plast = reinterpret_cast<u64 *>(ws + L.off_plast);
+    P.words.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
+    P.words.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
+    P.words.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
+    P.copy_bytes = L.copy_bytes;
+    P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
+#ifdef SV_PROFILE
+    P.prof = g_prof.load();
+#endif
+    return P;
+}
+
+// The kernel for calls of few resident sets; SV_ERR_UNSUPPORTED for the calls it does not take (more workgroups than
+// kResidentSets times what the device keeps resident, rows of more than kResidentMaxGroups workgroups).
+template <typename T, bool ALIGNED>
+sv_status_t launch_resident(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
+                            size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
+                            char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out, hipStream_t stream)
+{
+    const int nwg = L.nu / kWaves;
+    if (nwg > kResidentMaxGroups || B > 65535) return SV_ERR_UNSUPPORTED;
+    static std::atomic<int> cap;
+    void (*kernel)(const FusedParams) = resident_verify_kernel<T, ALIGNED>;
+    const int capacity = resident_workgroups(kernel, cap);
+    if (capacity < 1) return SV_ERR_HIP;
+    if ((long long)nwg * B * (gamma + 1) > (long long)kResidentSets * capacity) return SV_ERR_UNSUPPORTED;
+    const FusedParams P = word_params(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, L,
+                                      ws, accept_len, next_token, debug_out);
+    kernel<<<dim3((unsigned)nwg, (unsigned)B, (unsigned)(gamma + 1)), kThreads, 0, stream>>>(P);
+    return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
 template <typename T, bool ALIGNED>
 sv_status_t launch_fused(int algo, const void *target, const void *draft, const int32_t *tokens, const int32_t *draft_lens,
                          size_t tstride, size_t dstride, const float *uniforms, int B, int gamma, int V, float k, double kd, const Layout &L,
@@ -206,10 +258,8 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     const int wpr = nwg;
     // a row's workgroups wait for each other and must fit on the device together, with room to spare
     if (capacity < 4 * wpr) return capacity < 1 ? SV_ERR_HIP : SV_ERR_UNSUPPORTED;
-    FusedParams P;
-    P.target = target; P.draft = draft; P.tokens = tokens; P.draft_lens = draft_lens; P.uniforms = uniforms;
-    P.tstride = tstride; P.dstride = dstride;
-    P.B = B; P.gamma = gamma; P.V = V; P.k = k; P.kd = kd; P.k_eps = kd / (double)k - 1.0; P.algo = algo;
+    FusedParams P = word_params(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, L,
+                                ws, accept_len, next_token, debug_out);
     P.nu = nu;
     P.inv_slots = (unsigned)(0x100000000ull / (unsigned)(gamma + 1)) + 1u;
     P.inv_wpr = (unsigned)(0x100000000ull / (unsigned)(nu / kWaves)) + 1u;
@@ -223,23 +273,6 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
     // (the testing hook's forced unit sizes also force the pruning, so that small test shapes exercise it)
     P.prune = g_lane.load() != 0 || (size_t)wpr * P.group_seqs * n_groups * (gamma + 1) > (size_t)capacity ? 1 : 0;
     P.skip_last = P.prune;
-    P.spin_limit = g_spin_limit.load();
-    P.magic = workspace_magic(B, gamma, V);
-    P.header = reinterpret_cast<int *>(ws);
-    P.gen = reinterpret_cast<int *>(ws + L.off_gen);
-    P.words.ratio = reinterpret_cast<u64 *>(ws + L.off_ratio);
-    P.words.lw = reinterpret_cast<u64 *>(ws + L.off_lw);
-    P.words.rowres = reinterpret_cast<u64 *>(ws + L.off_rowres);
-    P.words.pstat = reinterpret_cast<u64 *>(ws + L.off_pstat);
-    P.words.plast = reinterpret_cast<u64 *>(ws + L.off_plast);
-    P.words.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
-    P.words.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
-    P.words.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
-    P.copy_bytes = L.copy_bytes;
-    P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
-#ifdef SV_PROFILE
-    P.prof = g_prof.load();
-#endif
     kernel<<<grid, kThreads, 0, stream>>>(P);
     return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
@@ -275,6 +308,7 @@ sv_status_t verify_entry(int algo, bool probs, const void *target, const void *d
     if (probs) {
 #define SV_PROBS(TT, AL) launch_probs<TT, AL>(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, \
                                               L, ws, accept_len, next_token, debug_out, stream)
+        g_last_kernel.store(SV_KERNEL_PROBS);
         return dtype == SV_DTYPE_F32 ? (aligned ? SV_PROBS(float, true) : SV_PROBS(float, false))
                                      : (aligned ? SV_PROBS(bf16_t, true) : SV_PROBS(bf16_t, false));
 #undef SV_PROBS
@@ -283,6 +317,7 @@ sv_status_t verify_entry(int algo, bool probs, const void *target, const void *d
     if (path == 2 && !L.fused_ok) return SV_ERR_UNSUPPORTED;
     // sequences small enough for one workgroup each need nothing between workgroups
     if (path == 5 || (path == 0 && tiny_ok(gamma, V))) {
+        g_last_kernel.store(SV_KERNEL_TINY);
         return dtype == SV_DTYPE_F32
             ? launch_tiny<float>(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, ws, accept_len, next_token, debug_out, stream)
             : launch_tiny<bf16_t>(algo, target, draft, tokens, draft_lens, tstride, dstride, uniforms, B, gamma, V, k, kd, ws, accept_len, next_token, debug_out, stream);
@@ -293,15 +328,25 @@ sv_status_t verify_entry(int algo, bool probs, const void *target, const void *d
 #define SV_DISPATCH(FN)                                                                   \
     (dtype == SV_DTYPE_F32 ? (aligned ? FN<float, true>(SV_ARGS) : FN<float, false>(SV_ARGS)) \
                            : (aligned ? FN<bf16_t, true>(SV_ARGS) : FN<bf16_t, false>(SV_ARGS)))
+    // calls of few resident sets: the kernel without a row leader's second look at the logits
+    if ((path == 7 || path == 0) && L.fused_ok) {
+        const sv_status_t st = SV_DISPATCH(launch_resident);
+        if (st == SV_OK) g_last_kernel.store(SV_KERNEL_RESIDENT);
+        if (st != SV_ERR_UNSUPPORTED || path == 7) return st;
+    } else if (path == 7) {
+        return SV_ERR_UNSUPPORTED;
+    }
     // the fused kernel (every logit read once) is the default; the staged kernels (every logit read twice)
     // take the shapes it does not: rows of more than kMaxUnitsPerRow wave chunks, or rows too wide to fit
     // four times into the device's resident set
     if (path != 1 && L.fused_ok) {
         const sv_status_t st = SV_DISPATCH(launch_fused);
+        if (st == SV_OK) g_last_kernel.store(SV_KERNEL_FUSED);
         if (st != SV_ERR_UNSUPPORTED || path == 2) return st;
     } else if (path == 2) {
         return SV_ERR_UNSUPPORTED;
     }
+    g_last_kernel.store(SV_KERNEL_STAGED);
     return SV_DISPATCH(launch_staged);
 #undef SV_DISPATCH
 #undef SV_ARGS
@@ -355,9 +400,11 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
     return words[kHdrError] == 0 ? SV_OK : SV_ERR_INTERNAL;
 }
 
+int32_t spec_verify_debug_last_kernel(void) { return g_last_kernel.load(); }
+
 void spec_verify_debug_config(int32_t path, int32_t spin_limit)
 {
-    g_path.store((path >= 0 && path <= 2) || path == 5 ? path : path == 3 || path == 4 ? 2 : 0);
+    g_path.store((path >= 0 && path <= 2) || path == 5 || path == 7 ? path : path == 3 || path == 4 ? 2 : 0);
     g_lane.store(path == 3 ? kLaneSmall : path == 4 ? kLaneLarge : 0);
     g_spin_limit.store(spin_limit >= 0 ? spin_limit : kDefaultSpinLimit);
 }

@@ -16,8 +16,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-# "default": the library's own choice of kernels (the fused kernel with the unit size it picks for the shape, and what
-# cannot matter left out only in calls larger than one resident set); the others force a path through the testing hook
+# "default": the library's own choice of kernels by the shape of the call (one workgroup per sequence, the kernel for calls
+# of few resident sets, the fused kernel with the unit size it picks); the others force a path through the testing hook
 PATHS = {"default": 0, "staged": 1, "fused": 3, "fused-large": 4}
 
 
@@ -83,6 +83,8 @@ def test_cfg3_full_batch(algo, path):
         rep = parity.compare(parity.run_gpu(algo, inp, cfg.temperature),
                              parity.run_oracle(algo, inp, cfg.temperature), label=f"cfg3/seed{seed}/{algo}/{path}")
         _say(rep)
+    # (the headline shape is the fused kernel's by the library's own choice too)
+    assert sv.spec_verify_debug_last_kernel() == (1 if path == "staged" else 2)
 
 
 # ------------------------------------------------------------------ shapes and edge cases

@@ -65,8 +65,10 @@ def test_the_librarys_own_choice_for_small_sequences_is_this_kernel(algo):
     a = parity.run_gpu(algo, inp, cfg.temperature)
     sv.spec_verify_debug_config(0, -1)
     b = parity.run_gpu(algo, inp, cfg.temperature)
+    assert sv.spec_verify_debug_last_kernel() == binding.SV_KERNEL_TINY
     sv.spec_verify_debug_config(3, -1)
     c = parity.run_gpu(algo, inp, cfg.temperature)
+    assert sv.spec_verify_debug_last_kernel() == binding.SV_KERNEL_FUSED
     for key in ("accept_len", "next_token", "dbg"):
         assert np.array_equal(a[key], b[key], equal_nan=True), key
     ref = parity.run_oracle(algo, inp, cfg.temperature)
