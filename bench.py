@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--sets", type=int, default=4, help="distinct input sets rotated through")
     ap.add_argument("--sigma-draft", type=float, default=None,
                     help="draft noise of the workload (configuration 4 is swept over 0.5, 1.5, 3.0; 0.5 = high acceptance)")
+    ap.add_argument("--batch", type=int, default=None, metavar="B",
+                    help="the configuration's shape with another number of sequences (how the time per call grows "
+                         "with the call's size; the headline is the configuration as it stands)")
     ap.add_argument("--graph", type=int, default=0, metavar="N",
                     help="launch the timed calls as replays of a HIP graph of N calls (0: one launch per call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -101,6 +104,8 @@ def main():
     cfg = workloads.CONFIGS[args.config]
     if args.sigma_draft is not None:
         cfg = workloads.with_overrides(cfg, sigma_draft=args.sigma_draft, name=f"{cfg.name}_sigma{args.sigma_draft}")
+    if args.batch is not None:
+        cfg = workloads.with_overrides(cfg, B=args.batch, name=f"{cfg.name}_with_B{args.batch}")
     fn = {"block": sv.spec_verify_block, "token": sv.spec_verify_token, "greedy": sv.spec_verify_greedy}[args.algo]
 
     sets = [workloads.generate(cfg, seed=9000 + s, device=dev) for s in range(args.sets)]

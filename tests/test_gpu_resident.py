@@ -47,6 +47,10 @@ SHAPES = [
     (2, 1, 262100, "bf16"),
     (100, 1, 1024, "bf16"),     # many sequences of one workgroup per row
     (12, 6, 30000, "bf16"),
+    # more workgroups than run at once: what cannot matter is left out, last target rows are read only where needed
+    (40, 8, 32000, "bf16"),
+    (12, 8, 128256, "bf16"),
+    (90, 3, 20001, "f32"),
 ]
 
 
@@ -123,9 +127,9 @@ def test_calls_beyond_its_limits_are_refused_when_forced_and_go_to_the_large_ker
 
 
 @pytest.mark.parametrize("algo", ["block", "token", "greedy"])
-@pytest.mark.parametrize("gamma", [5, 64])
-def test_identical_models_accept_everything(algo, gamma):
-    cfg = _custom(6, gamma, 9000, "bf16", sigma_t=4.0)
+@pytest.mark.parametrize("B,gamma", [(6, 5), (6, 64), (60, 8)])           # (60 x 9 x 3 workgroups: more than run at once)
+def test_identical_models_accept_everything(algo, B, gamma):
+    cfg = _custom(B, gamma, 9000 if B == 6 else 20000, "bf16", sigma_t=4.0)
     inp = workloads.generate(cfg, seed=5, device=DEV)
     inp["draft_logits"] = inp["target_logits"][:, :cfg.gamma].contiguous()
     gpu = parity.run_gpu(algo, inp, 0.7)
@@ -168,7 +172,7 @@ def test_masked_logits_top_k(algo, kt, kd):
 
 
 @pytest.mark.parametrize("algo", ["block", "token", "greedy"])
-@pytest.mark.parametrize("B,gamma,V,dtype", [(24, 8, 8400, "bf16"), (9, 5, 12917, "f32"), (40, 16, 3000, "bf16")])
+@pytest.mark.parametrize("B,gamma,V,dtype", [(24, 8, 8400, "bf16"), (9, 5, 12917, "f32"), (40, 16, 3000, "bf16"), (50, 8, 30000, "bf16")])
 def test_ragged_draft_lengths(algo, B, gamma, V, dtype):
     """Sequence b must come out exactly as a call with gamma = draft_lens[b] on its leading rows does; the rows beyond
     a sequence's length are poisoned with NaN to show that they are never read."""
