@@ -15,7 +15,7 @@
 //                             re-read that one chunk)
 #pragma once
 
-#include "common.hpp"
+#include "fused.hpp"
 
 namespace sv {
 
@@ -185,17 +185,14 @@ __device__ __forceinline__ float prob_thread_weights(const T *prow, const T *qro
     return mine;
 }
 
-// Inclusive sum over the lanes of a wave, in lane order.
-__device__ __forceinline__ double wave_inclusive_scan_double(double v)
+// Sums and inclusive sums over the lanes of a wave in double, through DPP (fixed orders).
+__device__ __forceinline__ double wave_total_double(double v)
 {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const double up = __shfl_up(v, off, 64);
-        if (lane >= off) v += up;
-    }
-    return v;
+    double first, second;
+    halves_sum_f64(v, first, second);
+    return first + second;
 }
+__device__ __forceinline__ double wave_inclusive_scan_double(double v) { return wave_scan(v); }
 
 template <typename T, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
@@ -211,32 +208,52 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
     double *S = smd, *R = smd + (gamma + 1);
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int gb = clamped_draft_len(draft_lens, b, gamma);
-    const ProbWeight *wb = weights + (size_t)b * (gamma + 1);
     const float2 *pb = part + (size_t)b * (gamma + 1) * nchunks;
     const float *eta = uniforms + (size_t)b * (gamma + 1);
-    // the chunk sums stay in LDS for the draw when they fit (the host sizes the dynamic LDS to match)
-    const bool keep = (gamma + 1) * nchunks <= kProbsKeepMax;
+    // the chunk sums stay in LDS for the draw when they fit (the host sizes the dynamic LDS to match: one float per
+    // sum, a second one per chunk for Alg. 4's rejected mass)
+    const bool keep = (gamma + 1) * nchunks * (algo == kGreedy ? 2 : 1) <= kProbsKeepMax;
     float *kept = reinterpret_cast<float *>(smd + 2 * (gamma + 1));
+    float *kept_rej = kept + (gamma + 1) * nchunks;
+    __shared__ ProbWeight wbs[SV_MAX_GAMMA + 1];                 // the sequence's constants, read once
 
-    // what the accept tests need besides the sums is asked for now, so that it arrives together with them
-    ProbWeight pw = {};
+    // Everything that comes from memory is asked for at once - the sequence's constants, the uniforms, every chunk sum
+    // of its positions (those of rows whose sums were not formed are stale and never used) - so that the kernel has
+    // one trip to memory here and one for the chunk that holds the token.
     float eta_i = 0.f, u = 0.f;
     if (wave == 0) {
-        if (lane + 1 <= gb) { pw = wb[lane + 1]; eta_i = eta[lane]; }
+        if (lane + 1 <= gb) eta_i = eta[lane];
         u = eta[gb];
     }
+    if (tid <= gb) wbs[tid] = weights[(size_t)b * (gamma + 1) + tid];
+    if (keep) {
+        const int n_words = (gb + 1) * nchunks;
+        for (int w = tid; w < n_words; w += kThreads) {
+            const float2 v = pb[w];
+            kept[w] = v.x;
+            if (algo == kGreedy) kept_rej[w] = v.y;
+        }
+    }
+    __syncthreads();
+    const ProbWeight *wb = wbs;
+    ProbWeight pw = {};
+    if (wave == 0 && lane + 1 <= gb) pw = wb[lane + 1];
 
     // S_i = sum over the chunks: wave (i mod 4) takes position i, lanes stride over the chunks
     for (int i = wave; i <= gb; i += kWaves) {
         double acc = 0.0, rej = 0.0;
         // (rows whose sums were not formed: S stays 0, their tests are decided without it and they cannot become tau)
         if (wb[i].needed) for (int c = lane; c < nchunks; c += 64) {
-            const float2 v = pb[(size_t)i * nchunks + c];
-            if (keep) kept[i * nchunks + c] = v.x;
-            acc += (double)v.x; rej += (double)v.y;
+            if (keep) {
+                acc += (double)kept[i * nchunks + c];
+                if (algo == kGreedy) rej += (double)kept_rej[i * nchunks + c];
+            } else {
+                const float2 v = pb[(size_t)i * nchunks + c];
+                acc += (double)v.x; rej += (double)v.y;
+            }
         }
-        acc = wave_sum_double(acc);
-        rej = wave_sum_double(rej);
+        acc = wave_total_double(acc);
+        if (algo == kGreedy) rej = wave_total_double(rej);
         if (lane == 0) { S[i] = acc; R[i] = rej; }
     }
     __syncthreads();
@@ -322,9 +339,9 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
             if (hit) {
                 const int first = __ffsll((long long)hit) - 1;
                 chunk = c0 + first;
-                t_in = t - __shfl(inc - v, first, 64);
+                t_in = t - read_lane_double(inc - v, first);
             }
-            carry = __shfl(inc, 63, 64);
+            carry = read_lane_double(inc, 63);
         }
         if (lane == 0) {
             s_chunk = chunk < 0 ? last_nonzero : chunk;      // rounding pushed t past the end: the last chunk with weight

@@ -147,7 +147,8 @@ sv_status_t launch_probs(int algo, const void *target_v, const void *draft_v, co
     else
         probs_residual_kernel<T, ALIGNED, false><<<blocks, kThreads, 0, stream>>>(
             target, draft, tstride, dstride, draft_lens, gamma, V, L.nchunks, part, weights);
-    const size_t keep = (size_t)(gamma + 1) * L.nchunks <= (size_t)kProbsKeepMax ? (size_t)(gamma + 1) * L.nchunks * sizeof(float) : 0;
+    const size_t kept_floats = (size_t)(gamma + 1) * L.nchunks * (algo == kGreedy ? 2 : 1);      // chunk sums (Alg. 4: and rejected masses)
+    const size_t keep = kept_floats <= (size_t)kProbsKeepMax ? kept_floats * sizeof(float) : 0;
     probs_finalize_kernel<T, ALIGNED><<<B, kThreads, 2 * (gamma + 1) * sizeof(double) + keep, stream>>>(
         target, draft, tstride, dstride, uniforms, draft_lens, gamma, V, L.nchunks, algo, part, weights,
         accept_len, next_token, debug_out);
