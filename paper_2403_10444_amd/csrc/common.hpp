@@ -297,11 +297,17 @@ __device__ int walk_range(const T *prow, const T *qrow, int V, int start, int ns
         }
         float exc, total;
         const float inc = block_inclusive_scan(mine, lds, exc, total);
-        if (tid == 0) ints[0] = kThreads;
+        // the first thread whose running sum exceeds t: per wave by a ballot, then the first wave that has one
+        // (one atomic operation per thread on one LDS word took microseconds here); `lds` is free after the scan
+        const unsigned long long hits = __ballot(inc > t);
+        int *wave_first = reinterpret_cast<int *>(lds);
         __syncthreads();
-        if (inc > t) atomicMin(&ints[0], tid);          // first thread whose running sum exceeds t
+        if ((tid & 63) == 0) wave_first[tid >> 6] = hits ? (tid | (__ffsll((long long)hits) - 1)) : kThreads;
         __syncthreads();
-        const int first = ints[0];
+        int first = kThreads;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) first = wave_first[w] < first ? wave_first[w] : first;
+        __syncthreads();
         if (first < kThreads) {
             if (tid == first) {
                 float run = exc;

@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
 {
     extern __shared__ double smd[];                     // [gamma+1] S_i, [gamma+1] rejected mass, then the kept partial sums
     __shared__ double wave_tot[kWaves];
-    __shared__ int s_tau, s_chunk, s_mode, s_winner, s_cand;
+    __shared__ int s_tau, s_chunk, s_mode, s_winner, wave_cand[kWaves];
     __shared__ double s_t, s_total;
     double *S = smd, *R = smd + (gamma + 1);
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
             scan_chunk(c, false, mine, below, total);
             row_total += total;
         }
-        if (tid == 0) { s_total = (double)u * row_total; s_winner = -1; s_cand = -1; }
+        if (tid == 0) { s_total = (double)u * row_total; s_winner = -1; }
     } else if (wave == 0) {
         // pick the chunk of row tau that holds t = u * (total weight): 64 chunk sums at a time, scanned in order
         const double total = mode == 1 ? S[gb] : S[tau];
@@ -347,7 +347,6 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
             s_chunk = chunk < 0 ? last_nonzero : chunk;      // rounding pushed t past the end: the last chunk with weight
             s_t = t_in;
             s_winner = -1;
-            s_cand = -1;
         }
     }
     __syncthreads();
@@ -367,9 +366,15 @@ __global__ __launch_bounds__(kThreads) void probs_finalize_kernel(
         for (int e = 0; e < kPerThread; ++e)
             if (wgt[e] > 0.f) last_positive = start + e;
         if (mode != 2 || t_in < total || c + 1 >= nchunks) {
-            if (mine > 0.f && below <= t_in) atomicMax(&s_cand, tid);
+            // the last thread with weight whose preceding sum does not exceed t: per wave by a ballot, then the last
+            // wave that has one (hundreds of atomic operations on one LDS word took microseconds here)
+            const unsigned long long cands = __ballot(mine > 0.f && below <= t_in);
+            if (lane == 0) wave_cand[wave] = cands ? wave * kWave + 63 - __clzll((long long)cands) : -1;
             __syncthreads();
-            if (tid == s_cand) {
+            int cand = -1;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) cand = wave_cand[w] > cand ? wave_cand[w] : cand;
+            if (tid == cand) {
                 double run = below;
                 int y = -1, lastpos = 0;
 #pragma unroll
