@@ -126,7 +126,10 @@ int32_t spec_verify_debug_last_kernel(void);
  * its kernels hold no such stores).  Process-wide: when `device_buffer` is not NULL the fused kernel stores up to
  * sixteen 64-bit timestamps (100 MHz ticks) per workgroup into it, taken by the workgroup's first wave: 0 start,
  * 1 partial normalisers announced, 2 the row's normalisers and w_i known, 3 second sweep begins, 4 second sweep
- * done; for the workgroup that finishes a sequence also 5 begin, 7..12 its phases, 6 done.  Record r of the buffer
+ * done; for the workgroup that finishes a sequence also 5 begin, 7..12 its phases, 6 done (the kernel for calls of
+ * few resident sets: 0 start, 1 first sweep done, 7 the row's words in, 8 ratio out, 9 w_i known, 2 row constants,
+ * 4 second sweep done, 5 the row's shares in, 10 place of the token found, 15 position's word out, 6 tau and Y
+ * written).  Record r of the buffer
  * belongs to workgroup x of row slot i (gamma: the last target row) of sequence b, r = (b * (gamma + 1) + i) *
  * ceil(V / 8192) + x: the buffer holds B * (gamma + 1) * ceil(V / 8192) records of 128 bytes and is zeroed by the
  * caller.                                                                                  */
