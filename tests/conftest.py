@@ -11,15 +11,15 @@ def pytest_configure(config):
 
 
 def pytest_sessionfinish(session, exitstatus):
-    """After a session with GPU parity comparisons: one summary per configuration under gpurun_out/ (what was
-    compared, what mismatched, how many residual masses lie outside 1e-5 relative)."""
+    """After a session with GPU parity comparisons: one summary per configuration in the session's output folder (what
+    was compared, what mismatched, how many residual masses lie outside 1e-5 relative)."""
     try:
         from tests import parity
     except Exception:
         return
     if not parity.RECORDS:
         return
-    out_dir = os.path.join(ROOT, "gpurun_out")
+    out_dir = os.path.join(ROOT, os.environ.get("SPECVERIFY_TEST_OUTPUT", "gpurun_out"))
     os.makedirs(out_dir, exist_ok=True)
     groups = {}
     for rep in parity.RECORDS:
