@@ -39,10 +39,13 @@
 // get their lowest mantissa bit set).  Words are written and read with agent-scope atomic accesses, which
 // go through to device memory instead of living in one XCD's L2; no agent-scope fence is needed (on this
 // part such a fence writes back / invalidates a whole L2 and cost more than the rest of the kernel).
-// The words exist twice.  A sequence's calls use the two copies alternately (the parity of gen[b], which the
-// wave that finishes the sequence flips as its last act), and every row's leader clears, in the copy that the
-// call does NOT use, the words of its row - so nobody ever clears a word that somebody may still read, and
-// nothing is cleared on the path that ends the kernel.
+// The words exist twice.  A sequence's calls use the two copies alternately (the parity of gen[b]), and every row's
+// leader clears, in the copy that the call does NOT use, the words of its row - so nobody ever clears a word that
+// somebody may still read, and nothing is cleared on the path that ends the kernel.  gen[b] is flipped once every
+// workgroup of the sequence has read it: the workgroups of the last target row, which start last, each leave a word
+// when they have, and the last of them flips gen[b] as soon as it has those words and one that the sequence's last row
+// pair could only publish after every row pair's workgroups had published theirs (and so had read gen[b]).  Nothing
+// at the end of a sequence waits for it.
 //
 // Progress: the hardware starts workgroups in index order (round-robin over the XCDs, in order
 // within each).  A unit waits only for units of its own row (at most kMaxUnitsPerRow / 4
@@ -90,6 +93,7 @@ struct Words {
     u64 *plast;           // [B, nu]                  the same of the sequence's last target row (row draft_lens[b])
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
+    u64 *lseen;           // [B, nu / 4]              non-zero once the workgroup of the last target row has read gen[b]
 };
 
 struct FusedParams {
@@ -131,7 +135,7 @@ __device__ __forceinline__ Words words_of(const FusedParams &P, unsigned copy)
     const size_t off = copy ? P.copy_bytes : 0;
     Words W;
     W.ratio = shifted(P.words.ratio, off); W.lw = shifted(P.words.lw, off); W.rowres = shifted(P.words.rowres, off); W.pstat = shifted(P.words.pstat, off); W.plast = shifted(P.words.plast, off);
-    W.pgrp = shifted(P.words.pgrp, off); W.qgrp = shifted(P.words.qgrp, off); W.spart = shifted(P.words.spart, off);
+    W.pgrp = shifted(P.words.pgrp, off); W.qgrp = shifted(P.words.qgrp, off); W.spart = shifted(P.words.spart, off); W.lseen = shifted(P.words.lseen, off);
     return W;
 }
 
@@ -801,6 +805,7 @@ __device__ __forceinline__ void clear_row_words(const FusedParams &P, const Word
     const int G = P.gamma, nu = P.nu, nwg = nu / kWaves;
     if (slot == G) {
         for (int e = lane; e < nu; e += kWave) st_u64(W.plast + (size_t)b * nu + e, 0);
+        for (int e = lane; e < nwg; e += kWave) st_u64(W.lseen + (size_t)b * nwg + e, 0);
         return;
     }
     const size_t drow = (size_t)b * G + slot;
@@ -832,7 +837,7 @@ __device__ __forceinline__ FusedParams reread_params()
     SV_ARG(inv_slots); SV_ARG(inv_wpr); SV_ARG(prune); SV_ARG(skip_last); SV_ARG(spin_limit);
     SV_ARG(magic); SV_ARG(header); SV_ARG(gen); SV_ARG(copy_bytes); SV_ARG(accept_len); SV_ARG(next_token); SV_ARG(debug_out);
     SV_ARG(words.ratio); SV_ARG(words.lw); SV_ARG(words.rowres); SV_ARG(words.pstat); SV_ARG(words.plast);
-    SV_ARG(words.pgrp); SV_ARG(words.qgrp); SV_ARG(words.spart);
+    SV_ARG(words.pgrp); SV_ARG(words.qgrp); SV_ARG(words.spart); SV_ARG(words.lseen);
 #ifdef SV_PROFILE
     SV_ARG(prof);
 #endif
@@ -866,12 +871,9 @@ __device__ __forceinline__ void lead_row(int b, int i_own, int gb, unsigned par,
     const float u = load_uniform(P.uniforms + seq_u + gb);
     const bool token_algo = P.algo == kToken;
     const bool next_passes = ratio_passes(own_word);             // Alg. 1: the test of X_{i+1}
-    // the finisher's first loads: the earlier positions' words (lane l: position l) and the last target row's words
+    // the finisher's first loads: the earlier positions' words (lane l: position l)
     const u64 *const res_word = W.rowres + seq_d + (lane < gb - 1 ? lane : 0);
-    const int e_lane = lane < nu ? lane : nu - 1;
     const u64 *const last = W.plast + (size_t)b * nu;
-    u64 last_first = 0;
-    if (finisher) last_first = ld_u64(last + e_lane);
     // the test of the last position, eta_gamma < h_gamma = w_gamma (Alg. 2 / 4), which the finisher judges first: where
     // it passes, tau = gamma and nothing of this row's residual is needed
     double w_last = 1.0;
@@ -940,16 +942,11 @@ __device__ __forceinline__ void lead_row(int b, int i_own, int gb, unsigned par,
         y = rowres_token(read_lane_u64(res, tau));
     }
     SV_STAMP(12);
-    // every workgroup of the sequence has read the call count once the last target row's words are there (the row
-    // pairs' workgroups published words that this wave, or a leader it heard from, has waited for)
-    wait_word(last + e_lane, last_first, lane < nu, P.spin_limit, gave_up);
-    for (int e = lane + kWave; e < nu; e += kWave) wait_word(last + e, P.spin_limit, gave_up);
     if (gave_up) report_gave_up(P);
     if (lane == 0) {
         // a wait that ran out anywhere on the way here leaves nothing to trust
         if (gave_up) { P.accept_len[b] = -1; y = -1; }
         P.next_token[b] = y;
-        __hip_atomic_store(P.gen + b, (int)(par ^ 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     SV_STAMP(6);
 }
@@ -1040,13 +1037,29 @@ void fused_verify_kernel(const FusedParams P)
     if (U.last_row) {
         // ---- the last target row: needed only if every token is accepted (then Y ~ p_gamma, Alg. 1 / 2 / 4).  In
         // calls large enough for it to pay, its workgroups first look at w_gamma: where eta_gamma >= w_gamma (Alg. 1:
-        // where some test fails) the row is not read at all, and its words say "no mass here".
+        // where some test fails) the row is not read at all, and nothing is said about it: nobody will ask.
         if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
         const Words W = SV_WORDS;
+        // The row's workgroups are the sequence's last to start.  Each says so once it has read gen[b] (the word hangs on
+        // the value read); the last of them hands the sequence's words over to the next call - it flips gen[b] - as soon
+        // as it has its siblings' words and proof that every row pair's workgroups have read gen[b] too: a word that the
+        // sequence's last row pair publishes only after all of them have published theirs.
+        u64 seen = 0;
+        if (wave == 0) {
+            if (lane == 0 && !clears) st_u64(W.lseen + (size_t)U.b * nwg + wg_x, 1ull + (launder(par) >> 1));
+            if (clears) seen = ld_u64(W.lseen + (size_t)U.b * nwg + (lane < nwg - 1 ? lane : 0));
+        }
+        auto hand_over = [&]() {
+            // (first wave of the row's last workgroup)
+            wait_word(W.lseen + (size_t)U.b * nwg + (lane < nwg - 1 ? lane : 0), seen, lane < nwg - 1, P.spin_limit, gave_up);
+            for (int e = lane + kWave; e < nwg - 1; e += kWave) wait_word(W.lseen + (size_t)U.b * nwg + e, P.spin_limit, gave_up);
+            if (lane == 0) __hip_atomic_store(P.gen + U.b, (int)(par ^ 1u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
         if (P.skip_last) {
             if (wave == 0) {
                 const float eta_g = load_uniform(P.uniforms + seq_u + gb - 1);
                 const u64 wt = wait_word(SV_LW_WORD, P.spin_limit, gave_up);
+                if (clears) hand_over();                     // (the word of log2 w_gamma is such a proof)
                 const bool wanted = can_become_tau(P.algo, gb, unpack_ratio(wt), eta_g);
                 if (lane == 0) row_flag = gave_up ? 2 : wanted ? 0 : 1;
                 if (gave_up) report_gave_up(P);
@@ -1054,7 +1067,8 @@ void fused_verify_kernel(const FusedParams P)
             __syncthreads();
             const int flag = row_flag;
             if (flag != 0) {
-                if (lane == 0) st_u64(W.plast + (size_t)U.b * nu + U.c, flag == 2 ? kPoison64 : pack_stat(-INFINITY, 0.f));
+                // (nobody asks for the words of a row that cannot be drawn from; a wait that ran out is passed on)
+                if (flag == 2 && lane == 0) st_u64(W.plast + (size_t)U.b * nu + U.c, kPoison64);
                 SV_STAMP(11);
                 return;
             }
@@ -1064,6 +1078,12 @@ void fused_verify_kernel(const FusedParams P)
         unpack_slice<T, ALIGNED, LANE>(rowA, unit_first, V, rawA, xa);
         const u64 stA = first_sweep_row(xa, k, shiftA);
         if (lane == 0) st_u64(W.plast + (size_t)U.b * nu + U.c, stA);
+        if (!P.skip_last && clears) {
+            // (calls whose last target rows ask nobody: the proof is the ratio of every position)
+            wait_word(W.ratio + seq_d + (lane < gb ? lane : 0), 0, lane < gb, P.spin_limit, gave_up);
+            if (gave_up) report_gave_up(P);
+            hand_over();
+        }
         return;
     }
 

@@ -42,7 +42,7 @@ struct Layout {
     size_t fused_grid;            // workgroups of the fused kernel
     size_t control_words;         // header, call counts and both copies of the words that cross waves: in ints, at offset 0
     size_t off_gen, copy_bytes;   // the call counts; bytes from one copy of the words to the other
-    size_t off_ratio, off_lw, off_rowres, off_pstat, off_plast, off_pgrp, off_qgrp, off_spart;     // copy 0
+    size_t off_ratio, off_lw, off_rowres, off_pstat, off_plast, off_pgrp, off_qgrp, off_spart, off_lseen;     // copy 0
     // staged path
     int nchunks;                  // chunks of kChunk logits per row
     size_t rows_total;
@@ -72,6 +72,8 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_qgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
     L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
+    off = align_up(off, 8);
+    L.off_lseen = off;  off += (size_t)B * (L.nu / kWaves) * sizeof(u64);
     L.copy_bytes = align_up(off - copy0, 256);
     off = copy0 + 2 * L.copy_bytes;
     L.control_words = off / sizeof(int);
@@ -201,6 +203,7 @@ FusedParams word_params(int algo, const void *target, const void *draft, const i
     P.words.pgrp = reinterpret_cast<u64 *>(ws + L.off_pgrp);
     P.words.qgrp = reinterpret_cast<u64 *>(ws + L.off_qgrp);
     P.words.spart = reinterpret_cast<unsigned *>(ws + L.off_spart);
+    P.words.lseen = reinterpret_cast<u64 *>(ws + L.off_lseen);
     P.copy_bytes = L.copy_bytes;
     P.accept_len = accept_len; P.next_token = next_token; P.debug_out = debug_out;
 #ifdef SV_PROFILE
