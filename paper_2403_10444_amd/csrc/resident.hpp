@@ -22,9 +22,9 @@ constexpr int kResidentMaxGroups = 32;        // workgroups per row: one poll of
 // Up to how many times the workgroups that the device keeps resident the library takes this kernel by itself.  Its
 // workgroups hold their registers until the row's S_i is there, which costs nothing while everything runs at once and
 // more and more as workgroups queue for the compute units; the large kernel pays a fixed price for its chain of row
-// leaders instead.  Measured with gamma = 8, V = 128256 (bf16), this kernel / the large one: B = 8 (1.1 sets) 15.1 / 15.7 us,
-// B = 9 18.3 / 25.2, B = 16 (2.3 sets) 22.5 / 27.7, B = 20 27.0 / 28.8, B = 24 (3.4 sets) 30.8 / 30.4, B = 32 39.8 / 34.7,
-// B = 64 (9 sets) 75.2 / 57.1.
+// leaders instead.  Measured with gamma = 8, V = 128256 (bf16, 1280 workgroups resident), this kernel / the large one:
+// B = 8 (0.9 sets) 15.3 / 16.3 us, B = 9 16.3 / 25.4, B = 16 (1.8 sets) 23.1 / 28.8, B = 24 (2.7 sets) 29.6 / 31.9,
+// B = 28 (3.2 sets) 33.6 / 33.8, B = 32 36.7 / 34.8, B = 64 (7.2 sets) 67.7 / 55.3.
 constexpr int kResidentSets = 3;
 
 // (largest scaled logit, sum) of four words, one per lane of a quad: every lane of the quad gets the combination
@@ -38,6 +38,14 @@ __device__ __forceinline__ u64 quad_word(u64 w)
     z += dpp_shift_double<0xB1>(z);
     z += dpp_shift_double<0x4E>(z);
     return pack_stat(M, (float)z);
+}
+
+// A wave-uniform float as a double, converted where it is used: left to itself the compiler converts the uniforms at
+// the top of the kernel and keeps the doubles in vector registers through both sweeps.
+__device__ __forceinline__ double late_double(float v)
+{
+    asm volatile("" : "+s"(v));
+    return (double)v;
 }
 
 // Where t falls among the entries z of the lanes (inclusive running sums `inc`; lanes beyond the entries hold 0):
@@ -139,8 +147,10 @@ __device__ __forceinline__ int draw_in_unit(F weight, double t, float *sums)
 
 // Grid (x, y, z) = (workgroup of the row, sequence, slot): slot i is row pair i, slot gamma the sequence's last target
 // row; x runs fastest in the start order, so a row's workgroups start together and a position's before the next one's.
+// (bf16 rows: held to the registers of five waves per SIMD, as the large kernel is - in calls of more than one resident
+// set a fifth of the workgroups more run at a time: B = 20 of the shape above 28.3 -> 25.5 us)
 template <typename T, bool ALIGNED>
-__global__ __launch_bounds__(kThreads)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ElemTraits<T>::kVec == 8 ? SV_WAVES_SMALL : 4)))
 void resident_verify_kernel(const FusedParams P)
 {
     constexpr int LANE = kLaneSmall, kUnitLogits = kWave * LANE, kVec = ElemTraits<T>::kVec;
@@ -195,6 +205,11 @@ void resident_verify_kernel(const FusedParams P)
     __shared__ int row_flag[4];
     __shared__ float draw_sums[kWaves][kWave * (LANE / kVec)];      // per wave: its unit's weights summed per (vector, lane)
     __shared__ float wave_scale[kWaves];
+    // what the first wave keeps across the second sweep lives here meanwhile (its registers are the whole workgroup's):
+    // the row's words as its lanes hold them, the words of log2 r_{i+1} and log2 r_i, log2 w_i, the row's largest
+    // scaled target logit, whether the position can become tau
+    __shared__ u64 kept_grp[kWave], kept_words[4];
+    __shared__ float kept_Mp;
     __shared__ int draw_entry;
     bool gave_up = false;
 
@@ -243,7 +258,7 @@ void resident_verify_kernel(const FusedParams P)
                 const double z = m > -INFINITY ? ldexp((double)stat_sum(pw), (int)(shift_of(m) - shift_of(M))) : 0.0;
                 const double inc = wave_scan(z);
                 double t_in;
-                const int e = locate_entry(z, inc, (double)u * read_lane_double(inc, kWave - 1), t_in);
+                const int e = locate_entry(z, inc, late_double(u) * read_lane_double(inc, kWave - 1), t_in);
                 if (e == c && !gave_up) {
                     // ... and in which of the workgroup's four units
                     const u64 ww = wave_words[0][lane & 3];
@@ -328,12 +343,12 @@ void resident_verify_kernel(const FusedParams P)
     __syncthreads();
     SV_STAMP(1);
 
-    u64 grp = 0;                    // first wave: the row's words (lanes 0..: the target row's, lanes 32..: the draft row's)
-    float Mp = 0.f;
-    double log2w = 0.0;
-    u64 own_word = 0, prev_word = 0;
-    bool candidate = true;
     if (wave == 0) {
+        u64 grp = 0;                // the row's words (lanes 0..: the target row's, lanes 32..: the draft row's)
+        float Mp = 0.f;
+        double log2w = 0.0;
+        u64 own_word = 0, prev_word = 0;
+        bool candidate = true;
         publish_group_words(wave_words, W.pgrp + drow * nwg + c, W.qgrp + drow * nwg + c);
         // ---- L_p, L_q from the words of all workgroups of the row
         const int e = lane & 31;
@@ -381,6 +396,14 @@ void resident_verify_kernel(const FusedParams P)
             st_u64(W.rowres + drow, pack_rowres(token_algo && ratio_passes(own_word), -1));
         }
         if (gave_up) report_gave_up(P);
+        if (needed) {
+            kept_grp[lane] = grp;
+            if (lane == 0) {
+                kept_words[0] = own_word; kept_words[1] = prev_word; kept_words[2] = (u64)__double_as_longlong(log2w);
+                kept_words[3] = candidate ? 1 : 0;
+                kept_Mp = Mp;
+            }
+        }
         if (lane == 0) row_flag[0] = needed ? 1 : 0;
         SV_STAMP(2);
     }
@@ -420,6 +443,9 @@ void resident_verify_kernel(const FusedParams P)
         const float mine = (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
         const unsigned own_part = gave_up ? kPoison32 : pack_partial(mine);
         if (lane == 0) st_u32(W.spart + drow * nu + c, own_part);
+        const u64 own_word = kept_words[0], prev_word = kept_words[1];
+        const double log2w = __longlong_as_double((long long)kept_words[2]);
+        const bool candidate = kept_words[3] != 0;
         // (while the shares travel: what the accept test needs of w_i)
         const bool has_test = !token_algo && i > 0;
         const double one_minus_w = has_test ? one_minus_exp2(fmin(log2w, 0.0)) : 0.0;
@@ -431,7 +457,7 @@ void resident_verify_kernel(const FusedParams P)
         // ---- the position's accept test (Alg. 2 / 4); Alg. 1: the test of X_{i+1} came with the ratio
         // (Alg. 2 / 4, position i >= 1: eta_i < h_i = S_i / (S_i + 1 - w_i), 1 where w_i >= 1 - see AcceptTest; judged
         // without the division)
-        const bool test_passes = has_test && candidate && (log2w >= 0.0 || (double)eta_i * (S_i + one_minus_w) < S_i);
+        const bool test_passes = has_test && candidate && (log2w >= 0.0 || late_double(eta_i) * (S_i + one_minus_w) < S_i);
         const bool next_passes = ratio_passes(own_word);
         const bool own_passes = token_algo ? next_passes : test_passes;
         // the token that follows if this position becomes tau is drawn where it can
@@ -446,13 +472,15 @@ void resident_verify_kernel(const FusedParams P)
         if (want) {
             // where u * S_i falls; a residual without any mass is drawn from p_i instead (weights: the exponentials)
             const bool from_p = !(S_i > 0.0);
+            const float Mp = kept_Mp;
+            const u64 grp = kept_grp[lane];
             if (from_p) {
                 const float m = lane < nwg ? stat_shift(grp) : -INFINITY;
                 z = m > -INFINITY ? ldexp((double)stat_sum(grp), (int)(shift_of(m) - shift_of(Mp))) : 0.0;
                 inc = wave_scan(z);
             }
             double t_in;
-            const int e = locate_entry(z, inc, (double)u * read_lane_double(inc, kWave - 1), t_in);
+            const int e = locate_entry(z, inc, late_double(u) * read_lane_double(inc, kWave - 1), t_in);
             if (e == c) {
                 // ... in which of the workgroup's four units, and what is left of t in that unit's own units
                 double t_w;
