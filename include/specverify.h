@@ -159,7 +159,8 @@ sv_status_t spec_verify_debug_copy(void *dst, const void *src, size_t bytes, voi
 
 /* Measurement hook: the floor of this launch shape.  Reads `bytes_each` bytes (a multiple of 16384) from each of the two
  * 16-byte aligned device buffers `a` and `b` with the access pattern of the verification kernel - one 256-thread
- * workgroup per 2 x 16 KB, eight 16-byte loads per lane issued up front, five waves per SIMD - and runs the first
+ * workgroup per 2 x 16 KB, eight 16-byte loads per lane issued up front, five workgroups per compute unit (held to
+ * that by the LDS the launch asks for: the probe's registers alone would allow eight) - and runs the first
  * sweep's arithmetic on them as bf16 (maximum, exp2, sum), with no traffic between workgroups; one float per wave goes
  * to `out` (bytes_each / 4096 floats).  What this kernel needs for a call's bytes is what no kernel of this shape that
  * also verifies can beat.  `short_waits`, `long_waits` (0 .. 64, units of 512 clocks): how long a workgroup keeps its
