@@ -187,7 +187,7 @@ def main():
         _, waits_ms = timed(max(args.steps // 4, 8), step_probe)
         floor = {"device_ms": probe_ms, "bytes": 2 * half, "GBps": 2 * half / (probe_ms * 1e-3) / 1e9,
                  "frac_of_peak": 2 * half / (probe_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                 "what": "spec_verify_debug_stream_probe: same launch shape and first-sweep arithmetic, no verification",
+                 "what": "spec_verify_debug_stream_probe: same launch shape, workgroups per compute unit and first-sweep arithmetic, no verification",
                  "device_ms_with_modelled_waits": waits_ms, "modelled_waits_x512_clocks": list(waits)}
         del bufs, probe_out
 
