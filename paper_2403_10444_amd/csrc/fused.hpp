@@ -68,6 +68,10 @@ constexpr int kWave = 64;
 // kWave * LANE contiguous logits of one row; fatter units mean fewer workgroups per row to wait for and the
 // fixed registers of a wave spread over more logits (bf16 rows only: 161 VGPRs, 3 waves per SIMD).
 constexpr int kLaneSmall = 32, kLaneLarge = 64;
+// Whether the units of a row pair leave out the per-wave word of their target row (see draw_from_target_row): the kernel
+// of the smaller units does; the one of the larger units sits at its register limit with the words published, and the
+// few instructions of the other way cost it three spilled exponentials in its sweeps.
+template <int LANE> constexpr bool kLazyRowWords = LANE == kLaneSmall;
 constexpr int kMaxUnitsPerRow = 512;     // wave chunks per row the fused kernel takes (V <= 1 Mi logits): 8 words per lane
 
 // Word 0 of an initialised workspace: a constant mixed with the shape it was initialised for.
@@ -89,7 +93,8 @@ struct Words {
     u64 *rowres;          // [B, gamma]               what position i contributes to tau and Y (pack_rowres): whether its accept test
                           //                          passes (Alg. 2 / 4: eta_i < h_i; Alg. 1: the test of X_{i+1}) and the token drawn from
                           //                          row pair i's residual where tau can still be i; by the leader of row pair i
-    u64 *pstat;           // [B, gamma, nu]           (largest scaled logit, sum) per wave chunk of a row pair's target row
+    u64 *pstat;           // [B, gamma, nu]           (largest scaled logit, sum) per wave chunk of a row pair's target row: filled in
+                          //                          only by a wave that has to draw from that row itself (draw_from_target_row)
     u64 *plast;           // [B, nu]                  the same of the sequence's last target row (row draft_lens[b])
     u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
@@ -174,6 +179,8 @@ __device__ __forceinline__ double unpack_ratio(u64 v) { return __longlong_as_dou
 __device__ __forceinline__ bool ratio_passes(u64 v) { return (v & 2ull) != 0; }
 // (low half: whether the leader's own accept test passes; high half: the token it drew + 2, 1 if it drew none - so the
 // word is never zero)
+// (a token of kRowDrawDeferred: the position's residual has no mass; if it becomes tau, Y is drawn from its target row)
+constexpr int kRowDrawDeferred = -3;
 __device__ __forceinline__ u64 pack_rowres(bool passes, int token) { return ((u64)(unsigned)(token + 2) << 32) | (passes ? 1ull : 0ull); }
 __device__ __forceinline__ bool rowres_passes(u64 v) { return (v & 1ull) != 0; }
 __device__ __forceinline__ int rowres_token(u64 v) { return (int)(unsigned)(v >> 32) - 2; }
@@ -705,8 +712,11 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &
             }
         }
         if (slot < 0) {
-            if (mode == 0 && !(total > 0.0)) {                         // no residual mass: draw from p_row
-                mode = 1;
+            // no residual mass: Y would be drawn from p_row itself, which takes a sweep over the whole row by this one
+            // wave (draw_from_target_row) - left to whoever finishes the sequence, and only if this position is tau
+            if (mode == 0 && !(total > 0.0)) {
+                if constexpr (kLazyRowWords<LANE>) return kRowDrawDeferred;
+                mode = 1;                                               // (larger units: the row's words are there)
                 Mrow = row_max_shift(st, nu, P.spin_limit, gave_up);
                 continue;
             }
@@ -794,6 +804,34 @@ __device__ __forceinline__ int draw_from_row(const FusedParams &P, const Words &
         y = last_positive < 0 ? 0 : last_positive;
     }
     return y;
+}
+
+// Y from p_row for a row pair's target row whose residual has no mass (Alg. 1 / 2 / 4 draw from the residual; where
+// rounding leaves none of it, from the row itself: in exact arithmetic such a position cannot become tau).  The units of
+// a row pair publish no word of their own per wave chunk - nobody reads them on any other path - so the wave that needs
+// them forms them here, chunk by chunk with the units' own arithmetic, into the row's words `pstat` (which only it
+// uses), and then draws as from a last target row.  A whole row through one wave: tens of microseconds, on a path that
+// consistent inputs do not take.
+template <typename T, bool ALIGNED, int LANE>
+__device__ __forceinline__ int draw_from_target_row(const FusedParams &P, const Words &W, int b, int row, float u, bool &gave_up)
+{
+    constexpr int kUnitLogits = kWave * LANE;
+    const int lane = threadIdx.x & 63;
+    const int nu = P.nu;
+    u64 *st = W.pstat + ((size_t)b * P.gamma + row) * nu;
+    const T *prow = static_cast<const T *>(P.target) + ((size_t)b * (P.gamma + 1) + row) * P.tstride;
+    for (int c = 0; c < nu; ++c) {
+        RawSlice<T, ALIGNED, LANE> raw;
+        float x[LANE], shift;
+        issue_loads<T, ALIGNED, LANE>(prow, c * kUnitLogits, P.V, raw);
+        unpack_slice<T, ALIGNED, LANE>(prow, c * kUnitLogits, P.V, raw, x);
+        const u64 word = first_sweep_row(x, P.k, shift);
+        if (lane == 0) st_u64(st + c, word);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the words are in memory before they are read back
+    AcceptTest none = {};
+    double total;
+    return draw_from_row<T, ALIGNED, LANE>(P, W, st, b, row, 1, true, false, none, 0.0, 0.0, u, total, gave_up);
 }
 
 // ------------------------------------------------------------------ whole sequences
@@ -940,6 +978,9 @@ __device__ __forceinline__ void lead_row(int b, int i_own, int gb, unsigned par,
         y = drawn;
     } else {
         y = rowres_token(read_lane_u64(res, tau));
+    }
+    if constexpr (kLazyRowWords<LANE>) {
+        if (y == kRowDrawDeferred) y = draw_from_target_row<T, ALIGNED, LANE>(P, W, b, tau, u, gave_up);
     }
     SV_STAMP(12);
     if (gave_up) report_gave_up(P);
@@ -1116,7 +1157,12 @@ void fused_verify_kernel(const FusedParams P)
     // hardware counts outstanding loads and stores in one counter, in order, and a wait for these loads placed after
     // a store would be a wait for that store's acknowledgement too)
     unpack_slice<T, ALIGNED, LANE>(rowB, unit_first, V, rawB, xb);
-    if (lane == 0) st_u64(SV_WORDS.pstat + drow * nu + U.c, stA);
+    // (smaller units: the target row's word of this wave, stA, goes to the workgroup's word only - per wave chunk nobody
+    // needs it but a draw from the row itself, which forms it again where it happens: 36 864 stores less per call at
+    // B = 64, gamma = 8, V = 128256, 52.2 -> 51.1 us)
+    if constexpr (!kLazyRowWords<LANE>) {
+        if (lane == 0) st_u64(SV_WORDS.pstat + drow * nu + U.c, stA);
+    }
     // the two logits of the draft token, asked for only now so that the streams above did not queue behind them, and
     // left as loaded until they are needed: the row's words will have come in by then, and these with them
     uint32_t ya_bits = 0, yb_bits = 0;

@@ -166,6 +166,53 @@ def test_disjoint_supports_reject_everything(algo):
     parity.compare(gpu, parity.run_oracle(algo, inp, 1.0))
 
 
+@pytest.mark.parametrize("algo", ["block", "token", "greedy"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_residual_without_mass_draws_from_the_target_row(dtype, algo, path):
+    """The draw of Y where float32 leaves a residual no mass at all (Alg. 2 draws from the residual; the kernels' and the
+    oracle's fallback is the target row itself).  Consistent arithmetic cannot reach it - a position whose residual is
+    empty cannot become tau - so the case is built from underflow: the two models agree on every token that float32 can
+    see and differ only on tokens 200 and 300 logits below the rest, one of which is drafted right behind position i.
+    Then tests 1 .. i pass with ratio 1, test i + 1 fails with a ratio of 2^-144, tau = i (as in the oracle), and the
+    kernels' S_i is exactly 0: Y must be the inverse-CDF draw from p_i.  (The oracle, in double, still sees the residual
+    on the far tokens and draws there: Y is compared with the draw from p_i instead, tau with the oracle.)  One sequence
+    per position i = 0 .. gamma - 1: the last one is the finishing wave's own row, the others come in through the
+    positions' words."""
+    gamma, V, T = 3, 20000, 1.0
+    cfg = _custom(gamma, gamma, V, dtype, sigma_t=3.0)
+    inp = workloads.generate(cfg, seed=77, device=DEV)
+    tgt = inp["target_logits"].float()
+    live = V - 64                                            # the last 64 tokens are the far ones
+    tgt[..., live:live + 32] = -300.0
+    tgt[..., live + 32:] = -200.0
+    drf = tgt[:, :gamma].clone()
+    drf[..., live:live + 32] = -200.0
+    drf[..., live + 32:] = -300.0
+    dt = inp["target_logits"].dtype
+    inp["target_logits"], inp["draft_logits"] = tgt.to(dt).contiguous(), drf.to(dt).contiguous()
+    # drafted tokens: the row's most likely token (ratio exactly 1) up to position b, a far token behind it
+    top = inp["draft_logits"].float().argmax(-1).to(torch.int32)          # [B, gamma]
+    tokens = top.clone()
+    for b in range(gamma):
+        tokens[b, b] = live + 3                                           # X_{b+1}: target -300, draft -200
+    inp["draft_tokens"] = tokens.contiguous()
+    # u in the middle of the cell of row i's most likely token: no rounding of a float32 sum moves the draw out of it
+    rows = inp["target_logits"].double()[torch.arange(gamma), torch.arange(gamma)]
+    cdf = torch.cumsum(torch.softmax(rows / T, -1), -1).cpu().numpy()
+    want = rows.argmax(-1).cpu().numpy()
+    mid = np.array([(cdf[b, want[b]] + (cdf[b, want[b] - 1] if want[b] > 0 else 0.0)) / 2 / cdf[b, -1] for b in range(gamma)])
+    assert all(cdf[b, want[b]] - (cdf[b, want[b] - 1] if want[b] > 0 else 0.0) > 1e-3 for b in range(gamma))
+    inp["uniforms"][:, :gamma] = 0.5
+    inp["uniforms"][:, gamma] = torch.as_tensor(mid.astype(np.float32), device=DEV)
+    ref = parity.run_oracle(algo, inp, T)
+    gpu = parity.run_gpu(algo, inp, T)
+    assert np.array_equal(gpu["accept_len"], np.arange(gamma)), gpu["accept_len"]
+    assert np.array_equal(gpu["accept_len"], ref["accept_len"])
+    assert np.all(gpu["dbg"][np.arange(gamma), np.arange(gamma), 1] == 0.0)      # S_i as the kernels see it
+    assert np.array_equal(gpu["next_token"], want), (gpu["next_token"], want)
+    assert np.all(gpu["next_token"] < live)
+
+
 def test_uniform_extremes():
     cfg = _custom(6, 4, 9000, "bf16")
     inp = workloads.generate(cfg, seed=8, device=DEV)
