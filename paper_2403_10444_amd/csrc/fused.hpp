@@ -488,8 +488,8 @@ __device__ __forceinline__ void publish_group_words(const u64 (&wave_words)[2][k
     double z = m > -INFINITY ? ldexp((double)stat_sum(w), (int)(shift_of(m) - shift_of(M))) : 0.0;
     z += dpp_shift_double<0xB1>(z);
     z += dpp_shift_double<0x4E>(z);
-    if (lane == 0) st_u64(pgrp_word, pack_stat(M, (float)z));
-    if (lane == 4) st_u64(qgrp_word, pack_stat(M, (float)z));
+    // (one store instruction for both words: lane 0 holds the target row's, lane 4 the draft row's)
+    if (lane == 0 || lane == 4) st_u64(lane == 0 ? pgrp_word : qgrp_word, pack_stat(M, (float)z));
 }
 
 struct Unit {
@@ -1209,6 +1209,13 @@ void fused_verify_kernel(const FusedParams P)
         // (the earlier positions have had a row's lifetime to publish what they contribute: asked for now, their words
         // come in with the row's, and the finisher does not wait for them at the end)
         if (finisher && gb > 1) res_first = ld_u64(W.rowres + seq_d + (lane < gb - 1 ? lane : 0));
+        // Alg. 2 / 4 keep the LAST position whose test passes, and test i + 1 passes whatever its uniform is where
+        // w_{i+1} >= 1 (h_{i+1} = 1; the last test: eta < min(w, 1)).  Then position i cannot be tau and its residual mass
+        // is not needed either.  w_{i+1} = w_i r_{i+1} takes this row's normalisers, which a workgroup that forms S_i waits
+        // for anyway: its first wave asks for the drafted token's two logits with them and judges like the leader does,
+        // on the same words with the same arithmetic (calls larger than one resident set; not with the debug block).
+        const bool may_skip = needed && chain && !P.debug_out && P.algo != kToken;
+        if (may_skip && !leader) { ya_bits = logit_bits(rowA + tok); yb_bits = logit_bits(rowB + tok); }
         float Mp, Mq;
         double Lp, Lq;
         const bool need_w = n_prev > 0 && !early;            // w_i still to come: the chain's word, or the ratios
@@ -1248,7 +1255,8 @@ void fused_verify_kernel(const FusedParams P)
             if (need_lane) wt = wait_word(w_word, wt, true, P.spin_limit, gave_up);
         }
         SV_STAMP(7);
-        if (leader) {
+        double lr_row = 0.0;                                 // log2 r_{i+1} as its word holds it
+        if (leader || may_skip) {
             // log2 r_{i+1} = log2 p_i(X_{i+1}) - log2 q_i(X_{i+1}), for every later position and for whoever finishes
             // the sequence.  The sweeps scale logits by the float k; the exact factor is kd = k (1 + k_eps).  To
             // first order that moves a row's log2-normaliser by k_eps * (the scaled logit where the mass sits, taken
@@ -1260,10 +1268,13 @@ void fused_verify_kernel(const FusedParams P)
             const double lq = yb * P.kd - (Lq + P.k_eps * (double)Mq);
             const double lr = fmax(lp - lq, kLog2RatioFloor);    // a drafted token the target masks out: r = 0, kept finite
             // Alg. 1's test of X_{i+1}, judged here once for everybody: eta_{i+1} < min(r_{i+1}, 1)
-            const bool passes = P.algo == kToken && (double)eta_next < exp2_precise(fmin(lr, 0.0));
-            own_word = pack_ratio(lr, passes);
-            if (gave_up) report_gave_up(P);
-            if (lane == 0) st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
+            lr_row = unpack_ratio(pack_ratio(lr, false));
+            if (leader) {
+                const bool passes = P.algo == kToken && (double)eta_next < exp2_precise(fmin(lr, 0.0));
+                own_word = pack_ratio(lr, passes);
+                if (gave_up) report_gave_up(P);
+                if (lane == 0) st_u64(W.ratio + drow, gave_up ? kPoison64 : own_word);
+            }
         }
         SV_STAMP(8);
         if (need_w) {
@@ -1278,25 +1289,32 @@ void fused_verify_kernel(const FusedParams P)
             if (gave_up) report_gave_up(P);
             if (chain && lane == 0) st_u64(W.lw + drow, gave_up ? kPoison64 : pack_ratio(lw_next, false));
         }
+        // (log2 w_{i+1} rounded as its word holds it, as the next position's leader and the finishing wave will read it)
+        const bool sweep = needed && !(may_skip && !gave_up &&
+                                       unpack_ratio(pack_ratio(next_weight(P.algo, log2w, lr_row, false), false)) >= 0.0);
         if (P.algo == kToken) log2w = 0.0;                          // the residual of token verification is p - q
         if (P.algo == kGreedy) log2w = fmin(log2w, 100.0);          // keeps w p finite in float
         // the second sweep's row constants: w p(x) = 2^(y_p - A) with A = L_p - log2 w, q(x) = 2^(y_q - L_q).  Their
         // integer parts meet the units' integer shifts in the exponent; the fractions are formed once, here, in double
         // (only where there is a second sweep: the leader of a row without one is on its way to the row's word)
-        if (needed) {
+        if (sweep) {
             const double A = Lp - log2w, Ai = rint(A), Qi = rint(Lq);
             const double fq = exp2_precise(Qi - Lq), frho = exp2_precise((Ai - A) - (Qi - Lq));
             if (lane == 0) { row_values[3] = Ai; row_values[4] = Qi; row_values[5] = fq; row_values[6] = frho; row_values[7] = 1.0 / frho; }
         }
         if (lane == 0) {
             row_values[0] = Lp; row_values[1] = Lq; row_values[2] = log2w;
-            row_flag = gave_up ? 2 : 1;
+            row_flag = gave_up ? 2 : sweep ? 1 : 3;          // (3: the residual mass was wanted and is not any more)
         }
         if (gave_up) report_gave_up(P);
         SV_STAMP(2);
     }
+    bool formed = needed;            // whether the row's residual mass is formed
     if (needed) {
         __syncthreads();
+        formed = row_flag != 3;
+    }
+    if (formed) {
         const bool poisoned = row_flag == 2 || gave_up;
         SV_STAMP(3);
 
@@ -1328,7 +1346,7 @@ void fused_verify_kernel(const FusedParams P)
         SV_STAMP(4);
     }
     if (!leader) return;
-    lead_row<T, ALIGNED, LANE>(U.b, U.i, gb, par, needed, candidate, finisher, own_word, lw_next, res_first, eta_i, eta_next, gave_up, row_values, stamps);
+    lead_row<T, ALIGNED, LANE>(U.b, U.i, gb, par, formed, candidate && formed, finisher, own_word, lw_next, res_first, eta_i, eta_next, gave_up, row_values, stamps);
 #undef SV_RATIO_WORD
 #undef SV_LW_WORD
 #undef SV_WORDS

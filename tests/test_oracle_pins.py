@@ -426,3 +426,31 @@ def test_acceptance_probability_never_exceeds_w(algo):
     for b in range(len(tau)):
         if tau[b] >= 1:
             assert not hopeless[b, tau[b] - 1]
+
+
+@pytest.mark.parametrize("algo", [oracle.BLOCK, oracle.GREEDY])
+def test_a_position_before_a_weight_of_one_is_never_the_accepted_length(algo):
+    """Alg. 2 / 4 keep the LAST position whose test passes.  Where w_{i+1} >= 1 the acceptance probability of position
+    i + 1 is 1 (h = 1 at w >= 1; the last test is eta < min(w_gamma, 1)) and its test passes whatever its uniform in
+    [0, 1) is, so tau >= i + 1 and position i is never the accepted length - what lets the kernels leave position i's
+    residual mass unformed once they know w_{i+1}.  Checked on the oracle's own w and decisions, with drafts close enough
+    to the target for weights of one to be common."""
+    rng = np.random.default_rng(4321)
+    B, gamma, V = 300, 6, 200
+    tl = rng.normal(0.0, 2.0, (B, gamma + 1, V)).astype(np.float32)
+    dl = (tl[:, :gamma] + rng.normal(0.0, 0.4, (B, gamma, V))).astype(np.float32)
+    q = np.exp(dl.astype(np.float64) / 0.8)
+    q /= q.sum(-1, keepdims=True)
+    tok = np.array([[rng.choice(V, p=q[b, i]) for i in range(gamma)] for b in range(B)], dtype=np.int32)
+    uni = rng.random((B, gamma + 1)).astype(np.float32)
+    out = oracle.verify(algo, tl, dl, tok, uni, 0.8)
+    w = out["dbg"][:, :, 0]                                     # w_0 .. w_gamma
+    sure = w[:, 1:] >= 1.0                                      # position i + 1 surely passes, i = 0 .. gamma - 1
+    assert sure.any() and (~sure).any()
+    tau = out["accept_len"]
+    for b in range(B):
+        if tau[b] < gamma:
+            assert not sure[b, tau[b]]
+    # and the position behind such a weight has acceptance probability one
+    h = out["dbg"][:, 1:, 2]
+    assert np.all(h[sure] == 1.0)
