@@ -96,7 +96,9 @@ struct Words {
     u64 *pstat;           // [B, gamma, nu]           (largest scaled logit, sum) per wave chunk of a row pair's target row: filled in
                           //                          only by a wave that has to draw from that row itself (draw_from_target_row)
     u64 *plast;           // [B, nu]                  the same of the sequence's last target row (row draft_lens[b])
-    u64 *pgrp, *qgrp;     // [B, gamma, nu / 4]       packed (shift, sum) per workgroup chunk of a row pair's target / draft row
+    u64 *pgrp, *qgrp;     // [B, gamma, nu / 4, 2]    packed (shift, sum) per workgroup chunk of a row pair's target / draft row, side by
+                          //                          side (qgrp = pgrp + 1; entry e of a row's words lies 2 e words on): a workgroup's two
+                          //                          words are one write of sixteen bytes
     unsigned *spart;      // [B, gamma, nu]           residual partial sums per wave chunk: float bits, lowest bit set
     u64 *lseen;           // [B, nu / 4]              non-zero once the workgroup of the last target row has read gen[b]
 };
@@ -316,7 +318,8 @@ struct StatAcc {
 // The words of a row's n units as a wave holds them: lane l has entries l, l + 64, ... (NW of them).
 template <int NW> struct RowWords { u64 w[NW]; };
 
-// Issues the loads of a row's words (an entry that is still 0 is polled later).
+// Issues the loads of a row's workgroup words (every second word from `words` on: the other row's lie between them;
+// an entry that is still 0 is polled later).
 template <int NW>
 __device__ __forceinline__ void load_row_words(const u64 *words, int n, RowWords<NW> &r)
 {
@@ -324,7 +327,7 @@ __device__ __forceinline__ void load_row_words(const u64 *words, int n, RowWords
 #pragma unroll
     for (int q = 0; q < NW; ++q) {
         const int e = lane + q * kWave;
-        r.w[q] = ld_u64(words + (e < n ? e : n - 1));
+        r.w[q] = ld_u64(words + 2 * (e < n ? e : n - 1));
     }
 }
 
@@ -418,7 +421,7 @@ __device__ __forceinline__ double row_normaliser(const u64 *words, int n, int li
     for (int q = 0; q < NW; ++q) {
         const int e = lane + q * kWave;
         if (q * kWave < n) {
-            const u64 w = wait_word(words + (e < n ? e : n - 1), r.w[q], e < n, limit, gave_up);
+            const u64 w = wait_word(words + 2 * (e < n ? e : n - 1), r.w[q], e < n, limit, gave_up);
             if (e < n) acc.add(w);
         }
     }
@@ -848,7 +851,7 @@ __device__ __forceinline__ void clear_row_words(const FusedParams &P, const Word
     }
     const size_t drow = (size_t)b * G + slot;
     for (int e = lane; e < nu; e += kWave) { st_u64(W.pstat + drow * nu + e, 0); st_u32(W.spart + drow * nu + e, 0); }
-    for (int e = lane; e < nwg; e += kWave) { st_u64(W.pgrp + drow * nwg + e, 0); st_u64(W.qgrp + drow * nwg + e, 0); }
+    for (int e = lane; e < 2 * nwg; e += kWave) st_u64(W.pgrp + 2 * drow * nwg + e, 0);
     if (lane == 0) { st_u64(W.ratio + drow, 0); st_u64(W.lw + drow, 0); st_u64(W.rowres + drow, 0); }
 }
 
@@ -1181,7 +1184,7 @@ void fused_verify_kernel(const FusedParams P)
         // workgroup's own words: one round trip for both, not one after the other)
         if (early) SV_NOTE(14, read_lane_u64(wt, 0) != 0 ? 1 : 2);
         if (early && read_lane_u64(wt, 0) == 0) wt = ld_u64(SV_LW_WORD);
-        publish_group_words(wave_words, W.pgrp + drow * nwg + wg_x, W.qgrp + drow * nwg + wg_x);
+        publish_group_words(wave_words, W.pgrp + 2 * (drow * nwg + wg_x), W.qgrp + 2 * (drow * nwg + wg_x));
         bool wanted = true;
         if (early) {
             wt = wait_word(SV_LW_WORD, wt, true, P.spin_limit, gave_up);
@@ -1228,7 +1231,7 @@ void fused_verify_kernel(const FusedParams P)
             // made of (if still missing) beside them; the two halves of the wave are then combined side by side
             const int e = lane & 31;
             const bool need = e < nwg;
-            const u64 *word = (lane < 32 ? W.pgrp : W.qgrp) + drow * nwg + (need ? e : nwg - 1);
+            const u64 *word = (lane < 32 ? W.pgrp : W.qgrp) + 2 * (drow * nwg + (need ? e : nwg - 1));
             u64 v = ld_u64(word);
             int spins = 0;
             while (__any((need && v == 0) || (need_lane && wt == 0))) {
@@ -1248,10 +1251,10 @@ void fused_verify_kernel(const FusedParams P)
             Lq = (double)shift_of(Mq) + log2_precise(zq);
         } else {
             RowWords<NW> pw, qw;
-            load_row_words<NW>(W.pgrp + drow * nwg, nwg, pw);
-            load_row_words<NW>(W.qgrp + drow * nwg, nwg, qw);
-            Lp = row_normaliser<NW>(W.pgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
-            Lq = row_normaliser<NW>(W.qgrp + drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
+            load_row_words<NW>(W.pgrp + 2 * drow * nwg, nwg, pw);
+            load_row_words<NW>(W.qgrp + 2 * drow * nwg, nwg, qw);
+            Lp = row_normaliser<NW>(W.pgrp + 2 * drow * nwg, nwg, P.spin_limit, gave_up, Mp, pw);
+            Lq = row_normaliser<NW>(W.qgrp + 2 * drow * nwg, nwg, P.spin_limit, gave_up, Mq, qw);
             if (need_lane) wt = wait_word(w_word, wt, true, P.spin_limit, gave_up);
         }
         SV_STAMP(7);

@@ -349,11 +349,11 @@ void resident_verify_kernel(const FusedParams P)
         double log2w = 0.0;
         u64 own_word = 0, prev_word = 0;
         bool candidate = true;
-        publish_group_words(wave_words, W.pgrp + drow * nwg + c, W.qgrp + drow * nwg + c);
+        publish_group_words(wave_words, W.pgrp + 2 * (drow * nwg + c), W.qgrp + 2 * (drow * nwg + c));
         // ---- L_p, L_q from the words of all workgroups of the row
         const int e = lane & 31;
         const bool need = e < nwg;
-        const u64 *word = (lane < 32 ? W.pgrp : W.qgrp) + drow * nwg + (need ? e : nwg - 1);
+        const u64 *word = (lane < 32 ? W.pgrp : W.qgrp) + 2 * (drow * nwg + (need ? e : nwg - 1));
         grp = wait_word(word, ld_u64(word), need, P.spin_limit, gave_up);
         StatAcc acc;
         if (need) acc.add(grp);

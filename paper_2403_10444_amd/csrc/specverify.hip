@@ -69,8 +69,9 @@ bool make_layout(int32_t B, int32_t gamma, int32_t V, Layout &L)
     L.off_rowres = off; off += rows_d * sizeof(u64);
     L.off_pstat = off;  off += rows_d * L.nu * sizeof(u64);
     L.off_plast = off;  off += (size_t)B * L.nu * sizeof(u64);
-    L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
-    L.off_qgrp = off;   off += rows_d * (L.nu / kWaves) * sizeof(u64);
+    off = align_up(off, 16);
+    L.off_pgrp = off;   off += rows_d * (L.nu / kWaves) * 2 * sizeof(u64);     // (target word, draft word) pairs
+    L.off_qgrp = L.off_pgrp + sizeof(u64);
     L.off_spart = off;  off += rows_d * L.nu * sizeof(unsigned);
     off = align_up(off, 8);
     L.off_lseen = off;  off += (size_t)B * (L.nu / kWaves) * sizeof(u64);
