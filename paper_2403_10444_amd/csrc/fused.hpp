@@ -150,6 +150,15 @@ __device__ __forceinline__ Words words_of(const FusedParams &P, unsigned copy)
 // not at the top of the kernel (where it would only be spilled until then).
 __device__ __forceinline__ unsigned launder(unsigned v) { asm volatile("" : "+s"(v)); return v; }
 
+// A barrier for what the waves of a workgroup hand each other through LDS: it orders LDS accesses only (a load from
+// device memory that a wave has under way stays under way across it).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // A load through the scalar data path for values that do not change while the kernel runs and whose address is the
 // same for the whole wave (inputs; the call count of a sequence, which changes only after its last reader).  It
 // does not queue behind the wave's sixteen-byte loads.
@@ -1066,6 +1075,7 @@ void fused_verify_kernel(const FusedParams P)
     __shared__ u64 wave_words[2][kWaves];
     __shared__ double row_values[8];
     __shared__ int row_flag;
+    __shared__ unsigned wave_shares[kWaves];
     bool gave_up = false;
 
     // Two ways to w_i.  Calls larger than one resident set ("chain"): the leader of row pair i - 1 publishes log2 w_i
@@ -1345,7 +1355,11 @@ void fused_verify_kernel(const FusedParams P)
             }
         }
         acc = wave_sum(acc);
-        if (lane == 0) st_u32(SV_WORDS.spart + drow * nu + U.c, poisoned ? kPoison32 : pack_partial(acc));
+        // (the four waves' shares meet in LDS and go out as one write of sixteen bytes: four separate small writes
+        // between the streaming reads cost more than the barrier)
+        if (lane == 0) wave_shares[wave] = poisoned ? kPoison32 : pack_partial(acc);
+        lds_barrier();
+        if (wave == 0 && lane < kWaves) st_u32(SV_WORDS.spart + drow * nu + wg_x * kWaves + lane, wave_shares[lane]);
         SV_STAMP(4);
     }
     if (!leader) return;
