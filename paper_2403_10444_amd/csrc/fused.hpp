@@ -1152,8 +1152,9 @@ void fused_verify_kernel(const FusedParams P)
     if (wave == 0) {
         const Words W = SV_WORDS;
         eta_i = load_uniform(P.uniforms + seq_u + (n_prev > 0 ? n_prev - 1 : 0));
-        if (chain) { if (n_prev > 0) wt = ld_u64(SV_LW_WORD); }
-        else wt = ld_u64(SV_RATIO_WORD);
+        // (chain: the word of log2 w_i is asked for once the sweeps are done - at a workgroup's start it is there for one
+        // workgroup in six only, and a look that finds nothing is one more small read between the streaming ones)
+        if (!chain) wt = ld_u64(SV_RATIO_WORD);
     }
     if (wave == 0) {
         tok = load_uniform(P.tokens + drow);
