@@ -103,8 +103,8 @@ sv_status_t spec_verify_workspace_check(const void *workspace, int32_t B, int32_
  * single-launch fused kernel (takes V <= 128 * 8192 and a device that keeps four rows'
  * workgroups resident; other shapes are then refused), 3 / 4 = the fused kernel with its
  * small / large units (32 / 64 logits of a row per lane; large ones exist for bf16 rows on
- * the 16-byte path only, other calls use the small ones; the library's own choice depends on
- * the shape; both also switch on, whatever the size of the call, what the library otherwise
+ * the 16-byte path only, other calls use the small ones; the library by itself takes the small
+ * ones; both also switch on, whatever the size of the call, what the library otherwise
  * does only in calls larger than one resident set of workgroups: residual masses that cannot
  * matter are left out, the last target row is read only where every token can be accepted, and
  * w_i travels from position to position as one published word); `spin_limit` bounds every wait

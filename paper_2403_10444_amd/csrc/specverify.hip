@@ -239,12 +239,13 @@ sv_status_t launch_fused(int algo, const void *target, const void *draft, const 
                          char *ws, int32_t *accept_len, int32_t *next_token, float *debug_out,
                          hipStream_t stream)
 {
-    // Unit size: 64 logits per lane (3 waves per SIMD) for bf16 rows on the vector path when the rows are very wide -
-    // half as many workgroups per row to wait for; 32 (5 waves per SIMD) otherwise.
+    // Unit size: 32 logits per lane (5 waves per SIMD).  The kernel also exists with 64 per lane (3 waves per SIMD, half
+    // as many workgroups per row to wait for; bf16 rows on the vector path), which used to be the faster one for very wide
+    // rows; since the smaller units publish less it is not any more (B = 1024, gamma = 8, V = 256000: 1414 - 1424 us
+    // against 1435 - 1439), and only the testing hook asks for it.
     // The workspace is laid out for the smaller units, whose words are a superset.
     constexpr bool kLargeOk = ALIGNED && ElemTraits<T>::kVec == 8;
-    const bool large = kLargeOk && g_lane.load() != kLaneSmall &&
-                       (g_lane.load() == kLaneLarge || V > 200000);
+    const bool large = kLargeOk && g_lane.load() == kLaneLarge;
     const int lane_logits = large ? kLaneLarge : kLaneSmall;
     const int nu = (V + kWaves * kWave * lane_logits - 1) / (kWaves * kWave * lane_logits) * kWaves;
     // the instantiation for this row width (one or two words of a row per lane of the collecting wave) and its
