@@ -80,7 +80,9 @@ __host__ __device__ inline int workspace_magic(int B, int gamma, int V)
     return (int)(0x53564b34u ^ ((unsigned)B * 2654435761u + (unsigned)gamma * 40503u + (unsigned)V * 2246822519u));
 }
 
-enum HeaderWord : int { kHdrMagic = 0, kHdrError = 1, kHdrWords = 64 };
+// (kHdrRowWords: non-zero once a kernel that publishes the per-wave words of target rows - the one of the larger units -
+// has worked on the workspace: only then do the other kernels' leaders clear those words with the rest of a row's)
+enum HeaderWord : int { kHdrMagic = 0, kHdrError = 1, kHdrRowWords = 2, kHdrWords = 64 };
 
 typedef unsigned long long u64;
 
@@ -843,13 +845,23 @@ __device__ __forceinline__ int draw_from_target_row(const FusedParams &P, const 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the words are in memory before they are read back
     AcceptTest none = {};
     double total;
-    return draw_from_row<T, ALIGNED, LANE>(P, W, st, b, row, 1, true, false, none, 0.0, 0.0, u, total, gave_up);
+    const int y = draw_from_row<T, ALIGNED, LANE>(P, W, st, b, row, 1, true, false, none, 0.0, 0.0, u, total, gave_up);
+    for (int c = lane; c < nu; c += kWave) st_u64(st + c, 0);      // (nobody clears these words for this kernel)
+    return y;
 }
 
 // ------------------------------------------------------------------ whole sequences
+// Whether a row's per-wave words of the target row may hold anything: always for the kernel that publishes them, else
+// only if such a kernel has worked on this workspace since it was prepared.
+template <int LANE> __device__ __forceinline__ bool row_words_used(const int *header)
+{
+    if constexpr (!kLazyRowWords<LANE>) return true;
+    else return load_uniform(header + kHdrRowWords) != 0;
+}
+
 // Clears the words of row slot `slot` of sequence b in one copy (one wave, all lanes, whole rows at a time: full
 // cache lines).  Slot gamma holds the words of the sequence's last target row and nothing else.
-__device__ __forceinline__ void clear_row_words(const FusedParams &P, const Words &W, int b, int slot)
+__device__ __forceinline__ void clear_row_words(const FusedParams &P, const Words &W, int b, int slot, bool row_words)
 {
     const int lane = threadIdx.x & 63;
     const int G = P.gamma, nu = P.nu, nwg = nu / kWaves;
@@ -859,7 +871,7 @@ __device__ __forceinline__ void clear_row_words(const FusedParams &P, const Word
         return;
     }
     const size_t drow = (size_t)b * G + slot;
-    for (int e = lane; e < nu; e += kWave) { st_u64(W.pstat + drow * nu + e, 0); st_u32(W.spart + drow * nu + e, 0); }
+    for (int e = lane; e < nu; e += kWave) { if (row_words) st_u64(W.pstat + drow * nu + e, 0); st_u32(W.spart + drow * nu + e, 0); }
     for (int e = lane; e < 2 * nwg; e += kWave) st_u64(W.pgrp + 2 * drow * nwg + e, 0);
     if (lane == 0) { st_u64(W.ratio + drow, 0); st_u64(W.lw + drow, 0); st_u64(W.rowres + drow, 0); }
 }
@@ -1065,7 +1077,7 @@ void fused_verify_kernel(const FusedParams P)
     if (unused) {
         // the copy in use holds nothing at an unused position; the other may hold an earlier, longer call's words:
         // both are cleared, which needs no look at the call count
-        if (clears) { clear_row_words(P, P.words, U.b, slot); clear_row_words(P, words_of(P, 1), U.b, slot); }
+        if (clears) { const bool rw = row_words_used<LANE>(header); clear_row_words(P, P.words, U.b, slot, rw); clear_row_words(P, words_of(P, 1), U.b, slot, rw); }
         return;
     }
     // (the copy of the words this call uses for the sequence - see the head of this file - is `par`; the addresses in it
@@ -1092,7 +1104,7 @@ void fused_verify_kernel(const FusedParams P)
         // ---- the last target row: needed only if every token is accepted (then Y ~ p_gamma, Alg. 1 / 2 / 4).  In
         // calls large enough for it to pay, its workgroups first look at w_gamma: where eta_gamma >= w_gamma (Alg. 1:
         // where some test fails) the row is not read at all, and nothing is said about it: nobody will ask.
-        if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
+        if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot, false);       // (slot gamma holds no such words)
         const Words W = SV_WORDS;
         // The row's workgroups are the sequence's last to start.  Each says so once it has read gen[b] (the word hangs on
         // the value read); the last of them hands the sequence's words over to the next call - it flips gen[b] - as soon
@@ -1160,7 +1172,12 @@ void fused_verify_kernel(const FusedParams P)
         tok = load_uniform(P.tokens + drow);
         eta_next = load_uniform(P.uniforms + seq_u + n_prev);
     }
-    if (clears) clear_row_words(P, words_of(P, par ^ 1u), U.b, slot);
+    if (clears) {
+        clear_row_words(P, words_of(P, par ^ 1u), U.b, slot, row_words_used<LANE>(header));
+        if constexpr (!kLazyRowWords<LANE>) {
+            if (lane == 0) __hip_atomic_store(SV_GLOBAL(int, P.header + kHdrRowWords), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 
     // ---- first sweep: exponentials stay in xa / xb; the unit's words go out
     float xa[LANE], xb[LANE];

@@ -192,10 +192,10 @@ void resident_verify_kernel(const FusedParams P)
     // workgroup (an unused position's in both copies: the other one may hold an earlier, longer call's words)
     const bool leader = wave == 0 && c == nwg - 1;
     if (unused) {
-        if (leader) { clear_row_words(P, P.words, b, slot); clear_row_words(P, words_of(P, 1), b, slot); }
+        if (leader) { const bool rw = row_words_used<kLaneSmall>(P.header); clear_row_words(P, P.words, b, slot, rw); clear_row_words(P, words_of(P, 1), b, slot, rw); }
         return;
     }
-    if (leader) clear_row_words(P, words_of(P, par ^ 1u), b, slot);
+    if (leader) clear_row_words(P, words_of(P, par ^ 1u), b, slot, slot != P.gamma && row_words_used<kLaneSmall>(P.header));
     const Words W = words_of(P, par);
     const bool token_algo = P.algo == kToken;
 
